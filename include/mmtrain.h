@@ -1,0 +1,204 @@
+/*
+ * mmtrain -- forward and backward of one transformer layer over a packed
+ * multimodal microbatch, for AMD MI355X (gfx950).
+ *
+ * The paper trains multimodal LLMs whose per-GPU work is a stack of identical
+ * transformer layers (Section 2.2 "Model Heterogeneity"; Section 4.2, where the
+ * LLM backbone is described as homogeneous transformer layers; Table 2 for the
+ * Llama3 shapes; Section 7 "Models" for the ViT encoder) applied to fixed-length
+ * sequences that interleave text subsequences and image subsequences
+ * (Section 2.1, Section 2.3 "Data Heterogeneity", Section 7 "Datasets").  It
+ * treats the layer as a black box; this library is that black box: one GPU's
+ * share of a training step.
+ *
+ * Layer kinds
+ *   DECODER  y1 = x + Wo.attn(rope(Wqkv.rmsnorm1(x)));  y = y1 + Wfc2.(silu(g)*u),
+ *            [g | u] = Wfc1.rmsnorm2(y1).   No biases.  Grouped-query attention
+ *            (query head h reads key/value head h / (n_heads / n_kv_heads)).
+ *            Rotary embedding pairs feature i with i + head_dim/2; positions
+ *            restart at 0 in every segment.
+ *   ENCODER  same skeleton with LayerNorm (gain + bias), biases on all four
+ *            linears, no rotary embedding, y = y1 + Wfc2.gelu_erf(Wfc1.ln2(y1)+b)+b.
+ *
+ * Packing.  T tokens are stored back to back in segment order; cu_seqlens[S+1]
+ * (cu[0] = 0, cu[S] = T, non-decreasing; empty segments allowed) cuts them into
+ * S segments.  Attention never crosses a segment boundary; inside a segment it
+ * is causal (key j <= query i) or bidirectional.
+ *
+ * Layout.  Activations are row-major [T, features].  Weights are row-major
+ * [out_features, in_features].  Every gradient has the shape and dtype of what
+ * it differentiates.  dtype is the storage type of all activations, weights and
+ * gradients: MMTRAIN_BF16 (bf16 storage, fp32 accumulation, MFMA kernels) or
+ * MMTRAIN_F32 (fp32 storage and arithmetic).
+ *
+ * Ownership.  The library never allocates, frees or retains memory.  The caller
+ * owns x, y, dy, dx, weights, gradients, `ctx` (opaque; written by fwd, read by
+ * bwd; size from mmtrain_layer_ctx_bytes) and `workspace` (scratch; size from
+ * mmtrain_layer_workspace_bytes; may be reused by later calls on the same
+ * stream).  All of these are DEVICE pointers, 256-byte aligned, unless a field
+ * says "host".  Host arrays need only stay valid during the call.
+ *
+ * Asynchrony.  Calls validate on the host, enqueue kernels on `hip_stream`
+ * (a hipStream_t; NULL = the default stream) and return without synchronising.
+ *
+ * Errors.  Every call returns an mmtrain_status (0 = OK, negative = error).
+ * Argument and segment validation happens before any HIP call; on such an error
+ * nothing has been enqueued.  The library never throws and never aborts.
+ */
+#ifndef MMTRAIN_H
+#define MMTRAIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MMTRAIN_API __attribute__((visibility("default")))
+
+typedef enum {
+    MMTRAIN_OK = 0,
+    MMTRAIN_ERR_INVALID_ARG = -1,   /* NULL where a pointer is required, bad enum, bad struct_size   */
+    MMTRAIN_ERR_BAD_SEGMENTS = -2,  /* cu_seqlens not starting at 0, decreasing, or not ending at T  */
+    MMTRAIN_ERR_UNSUPPORTED = -3,   /* shape outside the supported set (see mmtrain_layer_desc)      */
+    MMTRAIN_ERR_WORKSPACE = -4,     /* workspace_bytes smaller than mmtrain_layer_workspace_bytes    */
+    MMTRAIN_ERR_HIP = -5            /* a HIP call or kernel launch reported an error                 */
+} mmtrain_status;
+
+typedef enum { MMTRAIN_F32 = 0, MMTRAIN_BF16 = 1 } mmtrain_dtype;
+typedef enum { MMTRAIN_DECODER = 0, MMTRAIN_ENCODER = 1 } mmtrain_layer_kind;
+typedef enum {
+    MMTRAIN_MASK_CAUSAL = 0,        /* key j <= query i, same segment */
+    MMTRAIN_MASK_BIDIR = 1          /* every key of the same segment  */
+} mmtrain_mask_mode;
+
+/* Layer description.  Supported: head_dim in {64, 128}; n_heads % n_kv_heads == 0
+ * (encoder: n_kv_heads == n_heads); hidden, ffn_hidden and n_heads*head_dim
+ * multiples of 16.  Anything else: MMTRAIN_ERR_UNSUPPORTED. */
+typedef struct {
+    uint32_t struct_size;           /* sizeof(mmtrain_layer_desc) */
+    int32_t kind;                   /* mmtrain_layer_kind */
+    int32_t dtype;                  /* mmtrain_dtype */
+    int32_t hidden;                 /* H */
+    int32_t n_heads;                /* nh */
+    int32_t n_kv_heads;             /* nkv */
+    int32_t head_dim;               /* d */
+    int32_t ffn_hidden;             /* F */
+    float norm_eps;
+    float rope_base;                /* decoder only */
+    float softmax_scale;            /* 0 => 1/sqrt(head_dim) */
+} mmtrain_layer_desc;
+
+/* One packed microbatch (Section 2.3: a sequence of interleaved subsequences). */
+typedef struct {
+    int32_t total_tokens;           /* T >= 0 */
+    int32_t n_segments;             /* S >= 0 */
+    const int32_t *cu_seqlens_dev;  /* device [S+1] */
+    const int32_t *cu_seqlens_host; /* host   [S+1], same values: validation and launch sizing */
+    int32_t mask_mode;              /* mmtrain_mask_mode for every segment unless seg_mask_* given */
+    const uint8_t *seg_mask_dev;    /* optional device [S]: per-segment mmtrain_mask_mode */
+    const uint8_t *seg_mask_host;   /* optional host   [S]: same values; both or neither */
+} mmtrain_batch;
+
+/* Parameters.  *_b and b_* are NULL for the decoder. */
+typedef struct {
+    const void *norm1_w, *norm1_b;  /* [H] */
+    const void *w_qkv, *b_qkv;      /* [(nh + 2 nkv) d, H]; rows: q heads | k heads | v heads */
+    const void *w_o, *b_o;          /* [H, nh d] */
+    const void *norm2_w, *norm2_b;  /* [H] */
+    const void *w_fc1, *b_fc1;      /* decoder [2F, H]: gate rows then up rows; encoder [F, H] */
+    const void *w_fc2, *b_fc2;      /* [H, F] */
+} mmtrain_layer_weights;
+
+/* Where to write parameter gradients.  A NULL member means "do not compute this
+ * gradient" -- the frozen-module case of Section 7.3, where a frozen module runs
+ * forward and propagates input gradients but computes no weight gradients. */
+typedef struct {
+    void *norm1_w, *norm1_b, *w_qkv, *b_qkv, *w_o, *b_o;
+    void *norm2_w, *norm2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} mmtrain_layer_grads;
+
+/* Gradient accumulation over microbatches (summation is commutative, the
+ * property Section 5.2 relies on for reordering): matrix and bias and gain
+ * gradients are added to the buffers' contents instead of overwriting them. */
+#define MMTRAIN_BWD_ACCUMULATE_WGRAD 1u
+
+/* Bytes of `ctx` for a pack of total_tokens tokens.  0 on invalid desc. */
+MMTRAIN_API size_t mmtrain_layer_ctx_bytes(const mmtrain_layer_desc *desc, int32_t total_tokens);
+
+/* Bytes of `workspace` for fwd (is_bwd = 0) or bwd (is_bwd = 1).  0 on invalid desc. */
+MMTRAIN_API size_t mmtrain_layer_workspace_bytes(const mmtrain_layer_desc *desc, int32_t total_tokens,
+                                     int32_t n_segments, int is_bwd);
+
+/* Forward:  y[T,H] = layer(x[T,H]).  Fills ctx.  x and y may not alias. */
+MMTRAIN_API int mmtrain_layer_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch,
+                      const mmtrain_layer_weights *weights, const void *x, void *y, void *ctx,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Backward:  given dy[T,H] and the ctx of the matching forward call, writes dx[T,H]
+ * and every non-NULL member of grads (grads itself may be NULL: input gradient only). */
+MMTRAIN_API int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch,
+                      const mmtrain_layer_weights *weights, const void *x, const void *dy,
+                      const void *ctx, void *dx, const mmtrain_layer_grads *grads, uint32_t flags,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+MMTRAIN_API const char *mmtrain_status_string(int status);
+
+/* ------------------------------------------------------------------------
+ * Measurement aid (not part of the layer's arithmetic).  While enabled, the
+ * layer calls bracket each launch of the classes below with HIP events on the
+ * caller's stream; mmtrain_profile_read waits for the recorded events of one
+ * class, returns their summed duration and count, and (reset != 0) forgets
+ * them.  Process-wide, not thread-safe; event objects are created on demand
+ * and reused.  Used by the benchmark to obtain per-kernel launch durations
+ * inside the timed region.
+ * ------------------------------------------------------------------------ */
+typedef enum {
+    MMTRAIN_PROF_GEMM_NT = 0, MMTRAIN_PROF_GEMM_NN = 1, MMTRAIN_PROF_GEMM_TN = 2,
+    MMTRAIN_PROF_ATTN_FWD = 3, MMTRAIN_PROF_ATTN_BWD = 4
+} mmtrain_prof_kind;
+MMTRAIN_API void mmtrain_profile_enable(int on);
+MMTRAIN_API int mmtrain_profile_read(int32_t kind, double *total_ms, int64_t *launches, int reset);
+
+/* ------------------------------------------------------------------------
+ * Operator-level entry points: the kernels the layer calls are built from,
+ * exposed one by one so that each can be tested and timed on its own.  Same
+ * conventions as above (device pointers, caller-owned, asynchronous).
+ * ------------------------------------------------------------------------ */
+
+typedef enum {
+    MMTRAIN_GEMM_NT = 0,            /* C[M,N] = A[M,K] . B[N,K]^T   (linear forward)   */
+    MMTRAIN_GEMM_NN = 1,            /* C[M,N] = A[M,K] . B[K,N]     (input gradient)   */
+    MMTRAIN_GEMM_TN = 2             /* C[M,N] = A[K,M]^T . B[K,N]   (weight gradient)  */
+} mmtrain_gemm_layout;
+
+#define MMTRAIN_GEMM_ACCUMULATE 1u  /* C += instead of C =  */
+
+/* C = op(A).op(B) (+ bias[N] broadcast over rows) (+ residual[M,N], leading dimension ldc).
+ * Row-major with leading dimensions lda/ldb/ldc in elements.  fp32 accumulation.
+ * bf16: K-contiguous operands need K % 8 == 0, strided ones N (or M) % 8 == 0, and
+ * lda, ldb, ldc multiples of 8; otherwise MMTRAIN_ERR_UNSUPPORTED. */
+MMTRAIN_API int mmtrain_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K,
+                 const void *A, int32_t lda, const void *B, int32_t ldb, void *C, int32_t ldc,
+                 const void *bias, const void *residual, uint32_t flags, void *hip_stream);
+
+/* Bytes of workspace for the two attention operators below. */
+MMTRAIN_API size_t mmtrain_attn_workspace_bytes(int32_t total_tokens, int32_t n_segments, int32_t n_heads);
+
+/* Segment-masked attention forward over packed qkv[T, (nh + 2 nkv) d] (q heads | k heads |
+ * v heads per row; rotary embedding, if any, already applied).  Writes o[T, nh d] and
+ * lse[nh, T] (fp32 natural-log-sum-exp of the scaled, masked scores). */
+MMTRAIN_API int mmtrain_attn_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, const void *qkv,
+                     void *o, float *lse, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Attention backward: from d_o[T, nh d] and the forward's qkv, o, lse writes
+ * d_qkv[T, (nh + 2 nkv) d] (same column order as qkv). */
+MMTRAIN_API int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, const void *qkv,
+                     const void *o, const float *lse, const void *d_o, void *d_qkv,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMTRAIN_H */

@@ -1,0 +1,221 @@
+"""ctypes binding of libmmtrain.so: same names as include/mmtrain.h, argument marshalling only.
+
+PyTorch appears here only as the owner of device memory (`tensor.data_ptr()`) and
+of the current HIP stream.  Every step of the layer runs in the library's kernels.
+If the library has not been built, loading fails loudly: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmmtrain.so")
+
+OK, ERR_INVALID_ARG, ERR_BAD_SEGMENTS, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5
+F32, BF16 = 0, 1
+DECODER, ENCODER = 0, 1
+MASK_CAUSAL, MASK_BIDIR = 0, 1
+GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
+BWD_ACCUMULATE_WGRAD = 1
+GEMM_ACCUMULATE = 1
+
+EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_layer_fwd", "mmtrain_layer_bwd",
+           "mmtrain_status_string", "mmtrain_gemm", "mmtrain_attn_workspace_bytes", "mmtrain_attn_fwd",
+           "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read")
+PROF_GEMM_NT, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD = range(5)
+
+WEIGHT_FIELDS = ("norm1_w", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                 "norm2_w", "norm2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("kind", C.c_int32), ("dtype", C.c_int32), ("hidden", C.c_int32),
+                ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ffn_hidden", C.c_int32), ("norm_eps", C.c_float), ("rope_base", C.c_float),
+                ("softmax_scale", C.c_float)]
+
+
+class Batch(C.Structure):
+    _fields_ = [("total_tokens", C.c_int32), ("n_segments", C.c_int32), ("cu_seqlens_dev", C.c_void_p),
+                ("cu_seqlens_host", C.c_void_p), ("mask_mode", C.c_int32), ("seg_mask_dev", C.c_void_p),
+                ("seg_mask_host", C.c_void_p)]
+
+
+class Weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class Grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libmmtrain.so and declare its signatures.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2408_04275_amd.build). "
+                           "There is no fallback path.")
+    lib = C.CDLL(LIB_PATH)
+    P, I, U, S = C.c_void_p, C.c_int32, C.c_uint32, C.c_size_t
+    lib.mmtrain_layer_ctx_bytes.restype = S
+    lib.mmtrain_layer_ctx_bytes.argtypes = [P, I]
+    lib.mmtrain_layer_workspace_bytes.restype = S
+    lib.mmtrain_layer_workspace_bytes.argtypes = [P, I, I, C.c_int]
+    lib.mmtrain_layer_fwd.restype = C.c_int
+    lib.mmtrain_layer_fwd.argtypes = [P, P, P, P, P, P, P, S, P]
+    lib.mmtrain_layer_bwd.restype = C.c_int
+    lib.mmtrain_layer_bwd.argtypes = [P, P, P, P, P, P, P, P, U, P, S, P]
+    lib.mmtrain_status_string.restype = C.c_char_p
+    lib.mmtrain_status_string.argtypes = [C.c_int]
+    lib.mmtrain_gemm.restype = C.c_int
+    lib.mmtrain_gemm.argtypes = [I, I, I, I, I, P, I, P, I, P, I, P, P, U, P]
+    lib.mmtrain_attn_workspace_bytes.restype = S
+    lib.mmtrain_attn_workspace_bytes.argtypes = [I, I, I]
+    lib.mmtrain_attn_fwd.restype = C.c_int
+    lib.mmtrain_attn_fwd.argtypes = [P, P, P, P, P, P, S, P]
+    lib.mmtrain_attn_bwd.restype = C.c_int
+    lib.mmtrain_attn_bwd.argtypes = [P, P, P, P, P, P, P, P, S, P]
+    lib.mmtrain_profile_enable.restype = None
+    lib.mmtrain_profile_enable.argtypes = [C.c_int]
+    lib.mmtrain_profile_read.restype = C.c_int
+    lib.mmtrain_profile_read.argtypes = [I, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+    _lib = lib
+    return lib
+
+
+# ----------------------------------------------------------------------------
+# marshalling helpers
+# ----------------------------------------------------------------------------
+def _ptr(t) -> Optional[int]:
+    """Device/host address of a torch tensor, numpy array, int or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream
+
+
+def make_desc(kind, dtype, hidden, n_heads, n_kv_heads, head_dim, ffn_hidden, norm_eps=1e-5, rope_base=10000.0,
+              softmax_scale=0.0) -> LayerDesc:
+    return LayerDesc(C.sizeof(LayerDesc), kind, dtype, hidden, n_heads, n_kv_heads, head_dim, ffn_hidden,
+                     norm_eps, rope_base, softmax_scale)
+
+
+class PackedBatch:
+    """Holds the host and device copies of cu_seqlens / per-segment mask modes and the C struct that points at them."""
+
+    def __init__(self, cu_host: np.ndarray, seg_mask_host: Optional[np.ndarray] = None, mask_mode: int = MASK_CAUSAL,
+                 cu_dev=None, seg_mask_dev=None, total_tokens: Optional[int] = None):
+        self.cu_host = np.ascontiguousarray(cu_host, dtype=np.int32)
+        self.seg_mask_host = None if seg_mask_host is None else np.ascontiguousarray(seg_mask_host, dtype=np.uint8)
+        self.cu_dev, self.seg_mask_dev = cu_dev, seg_mask_dev
+        n_seg = len(self.cu_host) - 1
+        T = int(self.cu_host[-1]) if total_tokens is None else total_tokens
+        self.struct = Batch(T, n_seg, _ptr(cu_dev), _ptr(self.cu_host), mask_mode, _ptr(seg_mask_dev),
+                            _ptr(self.seg_mask_host))
+
+    @classmethod
+    def on_device(cls, cu_host, seg_mask_host=None, mask_mode=MASK_CAUSAL, device="cuda"):
+        import torch
+        cu_host = np.ascontiguousarray(cu_host, dtype=np.int32)
+        cu_dev = torch.from_numpy(cu_host).to(device)
+        sm_dev = None
+        if seg_mask_host is not None:
+            seg_mask_host = np.ascontiguousarray(seg_mask_host, dtype=np.uint8)
+            sm_dev = torch.from_numpy(seg_mask_host).to(device) if len(seg_mask_host) else torch.empty(1, dtype=torch.uint8, device=device)
+        return cls(cu_host, seg_mask_host, mask_mode, cu_dev, sm_dev)
+
+
+def make_weights(tensors: Dict[str, object]) -> Weights:
+    return Weights(*[_ptr(tensors.get(n)) for n in WEIGHT_FIELDS])
+
+
+def make_grads(tensors: Dict[str, object]) -> Grads:
+    return Grads(*[_ptr(tensors.get(n)) for n in WEIGHT_FIELDS])
+
+
+# ----------------------------------------------------------------------------
+# the C-ABI calls, same names
+# ----------------------------------------------------------------------------
+def mmtrain_status_string(status: int) -> str:
+    return load_library().mmtrain_status_string(status).decode()
+
+
+def mmtrain_layer_ctx_bytes(desc: Optional[LayerDesc], total_tokens: int) -> int:
+    return load_library().mmtrain_layer_ctx_bytes(C.byref(desc) if desc is not None else None, total_tokens)
+
+
+def mmtrain_layer_workspace_bytes(desc: Optional[LayerDesc], total_tokens: int, n_segments: int, is_bwd: int) -> int:
+    return load_library().mmtrain_layer_workspace_bytes(C.byref(desc) if desc is not None else None, total_tokens,
+                                                        n_segments, is_bwd)
+
+
+def _ref(s):
+    return None if s is None else C.byref(s)
+
+
+def mmtrain_layer_fwd(desc, batch, weights, x, y, ctx, workspace, workspace_bytes, stream=None) -> int:
+    b = batch.struct if isinstance(batch, PackedBatch) else batch
+    return load_library().mmtrain_layer_fwd(_ref(desc), _ref(b), _ref(weights), _ptr(x), _ptr(y), _ptr(ctx),
+                                            _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def mmtrain_layer_bwd(desc, batch, weights, x, dy, ctx, dx, grads, flags, workspace, workspace_bytes,
+                      stream=None) -> int:
+    b = batch.struct if isinstance(batch, PackedBatch) else batch
+    return load_library().mmtrain_layer_bwd(_ref(desc), _ref(b), _ref(weights), _ptr(x), _ptr(dy), _ptr(ctx),
+                                            _ptr(dx), _ref(grads), flags, _ptr(workspace), workspace_bytes,
+                                            _stream(stream))
+
+
+def mmtrain_gemm(dtype, layout, M, N, K, A, lda, B, ldb, Cmat, ldc, bias=None, residual=None, flags=0,
+                 stream=None) -> int:
+    return load_library().mmtrain_gemm(dtype, layout, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cmat), ldc,
+                                       _ptr(bias), _ptr(residual), flags, _stream(stream))
+
+
+def mmtrain_attn_workspace_bytes(total_tokens: int, n_segments: int, n_heads: int) -> int:
+    return load_library().mmtrain_attn_workspace_bytes(total_tokens, n_segments, n_heads)
+
+
+def mmtrain_attn_fwd(desc, batch, qkv, o, lse, workspace, workspace_bytes, stream=None) -> int:
+    b = batch.struct if isinstance(batch, PackedBatch) else batch
+    return load_library().mmtrain_attn_fwd(_ref(desc), _ref(b), _ptr(qkv), _ptr(o), _ptr(lse), _ptr(workspace),
+                                           workspace_bytes, _stream(stream))
+
+
+def mmtrain_attn_bwd(desc, batch, qkv, o, lse, d_o, d_qkv, workspace, workspace_bytes, stream=None) -> int:
+    b = batch.struct if isinstance(batch, PackedBatch) else batch
+    return load_library().mmtrain_attn_bwd(_ref(desc), _ref(b), _ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o),
+                                           _ptr(d_qkv), _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def mmtrain_profile_enable(on: bool) -> None:
+    load_library().mmtrain_profile_enable(1 if on else 0)
+
+
+def mmtrain_profile_read(kind: int, reset: bool = True):
+    """(total milliseconds, launches) of one kernel class since the last reset."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    rc = load_library().mmtrain_profile_read(kind, C.byref(ms), C.byref(n), 1 if reset else 0)
+    if rc != OK:
+        raise RuntimeError(f"mmtrain_profile_read: {mmtrain_status_string(rc)}")
+    return ms.value, n.value

@@ -1,0 +1,454 @@
+// C-ABI of the library: argument validation (host only, before any HIP call), memory
+// carving of ctx / workspace, and the launch sequence of one layer forward / backward.
+#include "../../include/mmtrain.h"
+#include "kernels.h"
+#include <vector>
+
+using namespace mmt;
+
+namespace {
+
+struct Bump {
+    uint8_t *base;
+    size_t off;
+    template <typename T> T *take(size_t n) {
+        off = (off + 255) & ~size_t(255);
+        T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += n * sizeof(T);
+        return p;
+    }
+    void *take_elems(size_t n, int dtype) {
+        return dtype == DT_F32 ? (void *)take<float>(n) : (void *)take<bf16_t>(n);
+    }
+};
+
+struct Dims {
+    int kind, dtype, H, nh, nkv, d, F, F1, nq, nk, nqkv;
+    float eps, rope_base, scale;
+};
+
+// Saved activations.  Everything the backward pass reads is kept (the forward pass produces
+// all of it anyway); nothing is recomputed.
+struct Ctx {
+    float *mean1, *rstd1, *mean2, *rstd2, *lse;
+    int *tok_seg;
+    float2 *rope_cs;
+    void *h1, *qkv, *o, *y1, *h2, *pre, *m;
+};
+
+struct BwdWs {
+    void *d_m, *d_pre, *d_h, *d_y1, *d_o, *d_qkv;
+    float *Dsum, *part_g, *part_b, *part_c;
+};
+
+int check_desc(const mmtrain_layer_desc *desc, Dims &D) {
+    if (!desc || desc->struct_size != sizeof(mmtrain_layer_desc)) return MMTRAIN_ERR_INVALID_ARG;
+    if (desc->kind != MMTRAIN_DECODER && desc->kind != MMTRAIN_ENCODER) return MMTRAIN_ERR_INVALID_ARG;
+    if (desc->dtype != MMTRAIN_F32 && desc->dtype != MMTRAIN_BF16) return MMTRAIN_ERR_INVALID_ARG;
+    if (desc->hidden <= 0 || desc->n_heads <= 0 || desc->n_kv_heads <= 0 || desc->ffn_hidden <= 0)
+        return MMTRAIN_ERR_INVALID_ARG;
+    if (!(desc->norm_eps > 0.f) || desc->softmax_scale < 0.f) return MMTRAIN_ERR_INVALID_ARG;
+    if (desc->kind == MMTRAIN_DECODER && !(desc->rope_base > 1.f)) return MMTRAIN_ERR_INVALID_ARG;
+    if (desc->head_dim != 64 && desc->head_dim != 128) return MMTRAIN_ERR_UNSUPPORTED;
+    if (desc->n_heads % desc->n_kv_heads) return MMTRAIN_ERR_UNSUPPORTED;
+    if (desc->kind == MMTRAIN_ENCODER && desc->n_kv_heads != desc->n_heads) return MMTRAIN_ERR_UNSUPPORTED;
+    if ((desc->hidden % 16) || (desc->ffn_hidden % 16)) return MMTRAIN_ERR_UNSUPPORTED;
+    if (desc->hidden > 8192) return MMTRAIN_ERR_UNSUPPORTED;
+    D.kind = desc->kind; D.dtype = desc->dtype; D.H = desc->hidden; D.nh = desc->n_heads;
+    D.nkv = desc->n_kv_heads; D.d = desc->head_dim; D.F = desc->ffn_hidden;
+    D.F1 = desc->kind == MMTRAIN_DECODER ? 2 * D.F : D.F;
+    D.nq = D.nh * D.d; D.nk = D.nkv * D.d; D.nqkv = D.nq + 2 * D.nk;
+    D.eps = desc->norm_eps; D.rope_base = desc->rope_base;
+    D.scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)D.d);
+    return MMTRAIN_OK;
+}
+
+int check_batch(const mmtrain_batch *b) {
+    if (!b) return MMTRAIN_ERR_INVALID_ARG;
+    if (b->total_tokens < 0 || b->n_segments < 0) return MMTRAIN_ERR_INVALID_ARG;
+    if (b->mask_mode != MMTRAIN_MASK_CAUSAL && b->mask_mode != MMTRAIN_MASK_BIDIR) return MMTRAIN_ERR_INVALID_ARG;
+    if (!b->cu_seqlens_host) return MMTRAIN_ERR_INVALID_ARG;
+    if ((b->seg_mask_dev == nullptr) != (b->seg_mask_host == nullptr)) return MMTRAIN_ERR_INVALID_ARG;
+    const int32_t *cu = b->cu_seqlens_host;
+    if (cu[0] != 0) return MMTRAIN_ERR_BAD_SEGMENTS;
+    for (int s = 0; s < b->n_segments; ++s)
+        if (cu[s + 1] < cu[s]) return MMTRAIN_ERR_BAD_SEGMENTS;
+    if (cu[b->n_segments] != b->total_tokens) return MMTRAIN_ERR_BAD_SEGMENTS;
+    if (b->seg_mask_host)
+        for (int s = 0; s < b->n_segments; ++s)
+            if (b->seg_mask_host[s] > 1) return MMTRAIN_ERR_INVALID_ARG;
+    if (b->total_tokens > 0 && !b->cu_seqlens_dev) return MMTRAIN_ERR_INVALID_ARG;
+    return MMTRAIN_OK;
+}
+
+int check_weights(const Dims &D, const mmtrain_layer_weights *w) {
+    if (!w) return MMTRAIN_ERR_INVALID_ARG;
+    if (!w->norm1_w || !w->w_qkv || !w->w_o || !w->norm2_w || !w->w_fc1 || !w->w_fc2) return MMTRAIN_ERR_INVALID_ARG;
+    if (D.kind == MMTRAIN_ENCODER &&
+        (!w->norm1_b || !w->b_qkv || !w->b_o || !w->norm2_b || !w->b_fc1 || !w->b_fc2))
+        return MMTRAIN_ERR_INVALID_ARG;
+    return MMTRAIN_OK;
+}
+
+void carve_ctx(Bump &b, const Dims &D, size_t T, Ctx &c) {
+    c.mean1 = b.take<float>(T); c.rstd1 = b.take<float>(T);
+    c.mean2 = b.take<float>(T); c.rstd2 = b.take<float>(T);
+    c.lse = b.take<float>(T * D.nh);
+    c.tok_seg = b.take<int>(T);
+    c.rope_cs = D.kind == MMTRAIN_DECODER ? b.take<float2>(T * (D.d / 2)) : nullptr;
+    c.h1 = b.take_elems(T * D.H, D.dtype);
+    c.qkv = b.take_elems(T * D.nqkv, D.dtype);
+    c.o = b.take_elems(T * D.nq, D.dtype);
+    c.y1 = b.take_elems(T * D.H, D.dtype);
+    c.h2 = b.take_elems(T * D.H, D.dtype);
+    c.pre = b.take_elems(T * D.F1, D.dtype);
+    c.m = b.take_elems(T * D.F, D.dtype);
+}
+
+void carve_bwd(Bump &b, const Dims &D, size_t T, BwdWs &w) {
+    w.d_m = b.take_elems(T * D.F, D.dtype);
+    w.d_pre = b.take_elems(T * D.F1, D.dtype);
+    w.d_h = b.take_elems(T * D.H, D.dtype);
+    w.d_y1 = b.take_elems(T * D.H, D.dtype);
+    w.d_o = b.take_elems(T * D.nq, D.dtype);
+    w.d_qkv = b.take_elems(T * D.nqkv, D.dtype);
+    w.Dsum = b.take<float>(T * D.nh);
+    w.part_g = b.take<float>((size_t)norm_bwd_blocks((int)T) * D.H);
+    w.part_b = b.take<float>((size_t)norm_bwd_blocks((int)T) * D.H);
+    const int maxn = D.nqkv > D.F1 ? (D.nqkv > D.H ? D.nqkv : D.H) : (D.F1 > D.H ? D.F1 : D.H);
+    w.part_c = b.take<float>((size_t)colsum_slabs((int)T) * maxn);
+}
+
+struct Profiler;
+hipError_t gemm(int dtype, const GemmArgs &g, hipStream_t st);
+
+GemmArgs mk(int layout, int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
+            const void *bias = nullptr, const void *residual = nullptr, bool accumulate = false) {
+    GemmArgs g;
+    g.layout = layout; g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+    g.bias = bias; g.residual = residual; g.accumulate = accumulate;
+    return g;
+}
+
+AttnArgs mk_attn(const Dims &D, const mmtrain_batch *b, const Ctx &c) {
+    AttnArgs a = {};
+    a.T = b->total_tokens; a.S = b->n_segments; a.nh = D.nh; a.nkv = D.nkv; a.d = D.d; a.scale = D.scale;
+    a.cu = b->cu_seqlens_dev; a.modes = b->seg_mask_dev; a.default_mode = b->mask_mode;
+    a.tok_seg = c.tok_seg; a.qkv = c.qkv; a.ld_qkv = D.nqkv; a.o = c.o; a.lse = c.lse;
+    return a;
+}
+
+__global__ void fill_zero_kernel(uint32_t *p, size_t nwords) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nwords) p[i] = 0u;
+}
+hipError_t fill_zero(void *p, size_t elems, int dtype, hipStream_t st) {
+    if (!p || elems == 0) return hipSuccess;
+    const size_t bytes = elems * (dtype == DT_F32 ? 4 : 2);
+    const size_t words = bytes / 4;            // all parameter tensors have an even element count
+    fill_zero_kernel<<<ceil_div((long)words, 256), 256, 0, st>>>((uint32_t *)p, words);
+    return hipGetLastError();
+}
+
+#define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return MMTRAIN_ERR_HIP; } while (0)
+
+// ---- optional per-kernel-class timing with HIP events on the caller's stream -------------
+struct Profiler {
+    bool on = false;
+    struct Span { int kind; hipEvent_t a, b; };
+    std::vector<Span> spans;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+};
+Profiler g_prof;
+
+struct ProfScope {
+    int kind; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
+    ProfScope(int k, hipStream_t s) : kind(k), st(s) {
+        if (!g_prof.on) return;
+        a = g_prof.get(); b = g_prof.get();
+        if (a && b) (void)hipEventRecord(a, st);
+    }
+    ~ProfScope() {
+        if (!a || !b) return;
+        (void)hipEventRecord(b, st);
+        g_prof.spans.push_back({kind, a, b});
+    }
+};
+
+hipError_t gemm(int dtype, const GemmArgs &g, hipStream_t st) {
+    ProfScope ps(g.layout, st);                    // MMTRAIN_PROF_GEMM_NT / _NN / _TN
+    if (dtype == DT_BF16 && gemm_mfma_supported(g)) return gemm_mfma(g, st);
+    return gemm_simple(dtype, g, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *mmtrain_status_string(int status) {
+    switch (status) {
+        case MMTRAIN_OK: return "ok";
+        case MMTRAIN_ERR_INVALID_ARG: return "invalid argument";
+        case MMTRAIN_ERR_BAD_SEGMENTS: return "cu_seqlens must start at 0, be non-decreasing and end at total_tokens";
+        case MMTRAIN_ERR_UNSUPPORTED: return "unsupported shape";
+        case MMTRAIN_ERR_WORKSPACE: return "workspace too small";
+        case MMTRAIN_ERR_HIP: return "HIP error";
+        default: return "unknown status";
+    }
+}
+
+size_t mmtrain_layer_ctx_bytes(const mmtrain_layer_desc *desc, int32_t total_tokens) {
+    Dims D;
+    if (check_desc(desc, D) != MMTRAIN_OK || total_tokens < 0) return 0;
+    Bump b = {nullptr, 0};
+    Ctx c;
+    carve_ctx(b, D, (size_t)total_tokens, c);
+    return ((b.off + 255) & ~size_t(255)) + 256;         // never 0 for a valid description
+}
+
+size_t mmtrain_layer_workspace_bytes(const mmtrain_layer_desc *desc, int32_t total_tokens, int32_t n_segments,
+                                     int is_bwd) {
+    Dims D;
+    if (check_desc(desc, D) != MMTRAIN_OK || total_tokens < 0 || n_segments < 0) return 0;
+    Bump b = {nullptr, 0};
+    if (is_bwd) {
+        BwdWs w;
+        carve_bwd(b, D, (size_t)total_tokens, w);
+    }
+    return ((b.off + 255) & ~size_t(255)) + 256;      // never 0 for a valid description
+}
+
+int mmtrain_layer_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, const mmtrain_layer_weights *W,
+                      const void *x, void *y, void *ctx, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    Dims D;
+    int rc = check_desc(desc, D);
+    if (rc) return rc;
+    if ((rc = check_batch(batch))) return rc;
+    if ((rc = check_weights(D, W))) return rc;
+    const int T = batch->total_tokens;
+    if (T == 0) return MMTRAIN_OK;
+    if (!x || !y || !ctx || x == y) return MMTRAIN_ERR_INVALID_ARG;
+    if (((uintptr_t)ctx | (uintptr_t)workspace) & 255) return MMTRAIN_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < mmtrain_layer_workspace_bytes(desc, T, batch->n_segments, 0))
+        return MMTRAIN_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool enc = D.kind == MMTRAIN_ENCODER;
+    Bump b = {(uint8_t *)ctx, 0};
+    Ctx c;
+    carve_ctx(b, D, (size_t)T, c);
+
+    HIP_TRY(prep_tokens(batch->cu_seqlens_dev, batch->n_segments, T, c.tok_seg, D.d, D.rope_base, c.rope_cs, st));
+    // attention block
+    HIP_TRY(norm_fwd(D.dtype, enc, x, W->norm1_w, W->norm1_b, c.h1, c.mean1, c.rstd1, T, D.H, D.eps, st));
+    HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.nqkv, D.H, c.h1, D.H, W->w_qkv, D.H, c.qkv, D.nqkv, W->b_qkv), st));
+    if (!enc) HIP_TRY(rope_inplace(D.dtype, c.qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, false, st));
+    AttnArgs a = mk_attn(D, batch, c);
+    {
+        ProfScope ps(MMTRAIN_PROF_ATTN_FWD, st);
+        HIP_TRY(attn_simple_fwd(D.dtype, a, st));
+    }
+    HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.H, D.nq, c.o, D.nq, W->w_o, D.nq, c.y1, D.H, W->b_o, x), st));
+    // MLP block
+    HIP_TRY(norm_fwd(D.dtype, enc, c.y1, W->norm2_w, W->norm2_b, c.h2, c.mean2, c.rstd2, T, D.H, D.eps, st));
+    HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.F1, D.H, c.h2, D.H, W->w_fc1, D.H, c.pre, D.F1, W->b_fc1), st));
+    if (enc) HIP_TRY(gelu_fwd(D.dtype, c.pre, c.m, (long)T * D.F, st));
+    else HIP_TRY(swiglu_fwd(D.dtype, c.pre, c.m, T, D.F, st));
+    HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.H, D.F, c.m, D.F, W->w_fc2, D.F, y, D.H, W->b_fc2, c.y1), st));
+    return MMTRAIN_OK;
+}
+
+int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, const mmtrain_layer_weights *W,
+                      const void *x, const void *dy, const void *ctx, void *dx, const mmtrain_layer_grads *grads,
+                      uint32_t flags, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    Dims D;
+    int rc = check_desc(desc, D);
+    if (rc) return rc;
+    if ((rc = check_batch(batch))) return rc;
+    if ((rc = check_weights(D, W))) return rc;
+    if (flags & ~MMTRAIN_BWD_ACCUMULATE_WGRAD) return MMTRAIN_ERR_INVALID_ARG;
+    const int T = batch->total_tokens;
+    const bool accum = flags & MMTRAIN_BWD_ACCUMULATE_WGRAD;
+    const bool enc = D.kind == MMTRAIN_ENCODER;
+    hipStream_t st = (hipStream_t)hip_stream;
+    mmtrain_layer_grads G = {};
+    if (grads) G = *grads;
+    if (T == 0) {                                   // an empty pack contributes zero gradients
+        if (!accum) {
+            HIP_TRY(fill_zero(G.norm1_w, D.H, D.dtype, st)); HIP_TRY(fill_zero(G.norm1_b, D.H, D.dtype, st));
+            HIP_TRY(fill_zero(G.w_qkv, (size_t)D.nqkv * D.H, D.dtype, st)); HIP_TRY(fill_zero(G.b_qkv, D.nqkv, D.dtype, st));
+            HIP_TRY(fill_zero(G.w_o, (size_t)D.H * D.nq, D.dtype, st)); HIP_TRY(fill_zero(G.b_o, D.H, D.dtype, st));
+            HIP_TRY(fill_zero(G.norm2_w, D.H, D.dtype, st)); HIP_TRY(fill_zero(G.norm2_b, D.H, D.dtype, st));
+            HIP_TRY(fill_zero(G.w_fc1, (size_t)D.F1 * D.H, D.dtype, st)); HIP_TRY(fill_zero(G.b_fc1, D.F1, D.dtype, st));
+            HIP_TRY(fill_zero(G.w_fc2, (size_t)D.H * D.F, D.dtype, st)); HIP_TRY(fill_zero(G.b_fc2, D.H, D.dtype, st));
+        }
+        return MMTRAIN_OK;
+    }
+    if (!x || !dy || !ctx || !dx) return MMTRAIN_ERR_INVALID_ARG;
+    if (((uintptr_t)ctx | (uintptr_t)workspace) & 255) return MMTRAIN_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < mmtrain_layer_workspace_bytes(desc, T, batch->n_segments, 1))
+        return MMTRAIN_ERR_WORKSPACE;
+    Bump bc = {(uint8_t *)const_cast<void *>(ctx), 0};
+    Ctx c;
+    carve_ctx(bc, D, (size_t)T, c);
+    Bump bw = {(uint8_t *)workspace, 0};
+    BwdWs w;
+    carve_bwd(bw, D, (size_t)T, w);
+    const int nb = norm_bwd_blocks(T), ns = colsum_slabs(T);
+
+    // ---- MLP block:  y = y1 + m . Wfc2^T (+ b_fc2)
+    HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), st));
+    if (G.w_fc2) HIP_TRY(gemm(D.dtype, mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), st));
+    if (enc && G.b_fc2) {
+        HIP_TRY(colsum_partials(D.dtype, dy, T, D.H, D.H, w.part_c, st));
+        HIP_TRY(reduce_partials(D.dtype, w.part_c, ns, D.H, G.b_fc2, accum, st));
+    }
+    if (enc) HIP_TRY(gelu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, (long)T * D.F, st));
+    else HIP_TRY(swiglu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F, st));
+    if (enc && G.b_fc1) {
+        HIP_TRY(colsum_partials(D.dtype, w.d_pre, T, D.F1, D.F1, w.part_c, st));
+        HIP_TRY(reduce_partials(D.dtype, w.part_c, ns, D.F1, G.b_fc1, accum, st));
+    }
+    HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.H, D.F1, w.d_pre, D.F1, W->w_fc1, D.H, w.d_h, D.H), st));
+    if (G.w_fc1) HIP_TRY(gemm(D.dtype, mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), st));
+    // d_y1 = dy + norm2_bwd(d_h2)
+    HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
+                     G.norm2_w ? w.part_g : nullptr, (enc && G.norm2_b) ? w.part_b : nullptr, T, D.H, st));
+    if (G.norm2_w) HIP_TRY(reduce_partials(D.dtype, w.part_g, nb, D.H, G.norm2_w, accum, st));
+    if (enc && G.norm2_b) HIP_TRY(reduce_partials(D.dtype, w.part_b, nb, D.H, G.norm2_b, accum, st));
+
+    // ---- attention block:  y1 = x + o . Wo^T (+ b_o)
+    HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.nq, D.H, w.d_y1, D.H, W->w_o, D.nq, w.d_o, D.nq), st));
+    if (G.w_o) HIP_TRY(gemm(D.dtype, mk(GEMM_TN, D.H, D.nq, T, w.d_y1, D.H, c.o, D.nq, G.w_o, D.nq, nullptr, nullptr, accum), st));
+    if (enc && G.b_o) {
+        HIP_TRY(colsum_partials(D.dtype, w.d_y1, T, D.H, D.H, w.part_c, st));
+        HIP_TRY(reduce_partials(D.dtype, w.part_c, ns, D.H, G.b_o, accum, st));
+    }
+    AttnArgs a = mk_attn(D, batch, c);
+    a.d_o = w.d_o; a.d_qkv = w.d_qkv; a.Dsum = w.Dsum;
+    {
+        ProfScope ps(MMTRAIN_PROF_ATTN_BWD, st);
+        HIP_TRY(attn_simple_bwd(D.dtype, a, st));
+    }
+    if (!enc) HIP_TRY(rope_inplace(D.dtype, w.d_qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, true, st));
+    if (enc && G.b_qkv) {
+        HIP_TRY(colsum_partials(D.dtype, w.d_qkv, T, D.nqkv, D.nqkv, w.part_c, st));
+        HIP_TRY(reduce_partials(D.dtype, w.part_c, ns, D.nqkv, G.b_qkv, accum, st));
+    }
+    HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.H, D.nqkv, w.d_qkv, D.nqkv, W->w_qkv, D.H, w.d_h, D.H), st));
+    if (G.w_qkv) HIP_TRY(gemm(D.dtype, mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), st));
+    // dx = d_y1 + norm1_bwd(d_h1)
+    HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
+                     G.norm1_w ? w.part_g : nullptr, (enc && G.norm1_b) ? w.part_b : nullptr, T, D.H, st));
+    if (G.norm1_w) HIP_TRY(reduce_partials(D.dtype, w.part_g, nb, D.H, G.norm1_w, accum, st));
+    if (enc && G.norm1_b) HIP_TRY(reduce_partials(D.dtype, w.part_b, nb, D.H, G.norm1_b, accum, st));
+    return MMTRAIN_OK;
+}
+
+// ---- profiling ---------------------------------------------------------------------
+
+void mmtrain_profile_enable(int on) { g_prof.on = on != 0; }
+
+int mmtrain_profile_read(int32_t kind, double *total_ms, int64_t *launches, int reset) {
+    if (!total_ms || !launches) return MMTRAIN_ERR_INVALID_ARG;
+    double ms = 0.0;
+    int64_t n = 0;
+    for (auto &s : g_prof.spans) {
+        if (s.kind != kind) continue;
+        if (hipEventSynchronize(s.b) != hipSuccess) return MMTRAIN_ERR_HIP;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, s.a, s.b) != hipSuccess) return MMTRAIN_ERR_HIP;
+        ms += t; ++n;
+    }
+    *total_ms = ms; *launches = n;
+    if (reset) {
+        std::vector<Profiler::Span> keep;
+        for (auto &s : g_prof.spans) {
+            if (s.kind == kind) { g_prof.pool.push_back(s.a); g_prof.pool.push_back(s.b); }
+            else keep.push_back(s);
+        }
+        g_prof.spans.swap(keep);
+    }
+    return MMTRAIN_OK;
+}
+
+// ---- operator-level entry points ----------------------------------------------------
+
+int mmtrain_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, int32_t lda,
+                 const void *B, int32_t ldb, void *C, int32_t ldc, const void *bias, const void *residual,
+                 uint32_t flags, void *hip_stream) {
+    if (dtype != MMTRAIN_F32 && dtype != MMTRAIN_BF16) return MMTRAIN_ERR_INVALID_ARG;
+    if (layout < MMTRAIN_GEMM_NT || layout > MMTRAIN_GEMM_TN) return MMTRAIN_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0 || (flags & ~MMTRAIN_GEMM_ACCUMULATE)) return MMTRAIN_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return MMTRAIN_OK;
+    if (!C || (K > 0 && (!A || !B))) return MMTRAIN_ERR_INVALID_ARG;
+    const int min_lda = layout == MMTRAIN_GEMM_TN ? M : K, min_ldb = layout == MMTRAIN_GEMM_NT ? K : N;
+    if (lda < min_lda || ldb < min_ldb || ldc < N) return MMTRAIN_ERR_INVALID_ARG;
+    GemmArgs g = mk(layout, M, N, K, A, lda, B, ldb, C, ldc, bias, residual, flags & MMTRAIN_GEMM_ACCUMULATE);
+    if (dtype == MMTRAIN_BF16 && !gemm_mfma_supported(g) && K > 0) return MMTRAIN_ERR_UNSUPPORTED;
+    HIP_TRY(gemm(dtype, g, (hipStream_t)hip_stream));
+    return MMTRAIN_OK;
+}
+
+size_t mmtrain_attn_workspace_bytes(int32_t total_tokens, int32_t n_segments, int32_t n_heads) {
+    if (total_tokens < 0 || n_segments < 0 || n_heads <= 0) return 0;
+    Bump b = {nullptr, 0};
+    b.take<int>((size_t)total_tokens);
+    b.take<float>((size_t)total_tokens * n_heads);
+    return ((b.off + 255) & ~size_t(255)) + 256;
+}
+
+static int attn_common(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, Dims &D, void *workspace,
+                       size_t workspace_bytes, AttnArgs &a, hipStream_t st) {
+    int rc = check_desc(desc, D);
+    if (rc) return rc;
+    if ((rc = check_batch(batch))) return rc;
+    const int T = batch->total_tokens;
+    if (T == 0) return MMTRAIN_OK;
+    if ((uintptr_t)workspace & 255) return MMTRAIN_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < mmtrain_attn_workspace_bytes(T, batch->n_segments, D.nh))
+        return MMTRAIN_ERR_WORKSPACE;
+    Bump b = {(uint8_t *)workspace, 0};
+    int *tok_seg = b.take<int>((size_t)T);
+    float *Dsum = b.take<float>((size_t)T * D.nh);
+    a = AttnArgs{};
+    a.T = T; a.S = batch->n_segments; a.nh = D.nh; a.nkv = D.nkv; a.d = D.d; a.scale = D.scale;
+    a.cu = batch->cu_seqlens_dev; a.modes = batch->seg_mask_dev; a.default_mode = batch->mask_mode;
+    a.tok_seg = tok_seg; a.ld_qkv = D.nqkv; a.Dsum = Dsum;
+    HIP_TRY(prep_tokens(batch->cu_seqlens_dev, batch->n_segments, T, tok_seg, D.d, 0.f, nullptr, st));
+    return MMTRAIN_OK;
+}
+
+int mmtrain_attn_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, const void *qkv, void *o,
+                     float *lse, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    Dims D;
+    AttnArgs a;
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = attn_common(desc, batch, D, workspace, workspace_bytes, a, st);
+    if (rc || batch->total_tokens == 0) return rc;
+    if (!qkv || !o || !lse) return MMTRAIN_ERR_INVALID_ARG;
+    a.qkv = qkv; a.o = o; a.lse = lse;
+    HIP_TRY(attn_simple_fwd(D.dtype, a, st));
+    return MMTRAIN_OK;
+}
+
+int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, const void *qkv, const void *o,
+                     const float *lse, const void *d_o, void *d_qkv, void *workspace, size_t workspace_bytes,
+                     void *hip_stream) {
+    Dims D;
+    AttnArgs a;
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = attn_common(desc, batch, D, workspace, workspace_bytes, a, st);
+    if (rc || batch->total_tokens == 0) return rc;
+    if (!qkv || !o || !lse || !d_o || !d_qkv) return MMTRAIN_ERR_INVALID_ARG;
+    a.qkv = qkv; a.o = const_cast<void *>(o); a.lse = const_cast<float *>(lse); a.d_o = d_o; a.d_qkv = d_qkv;
+    HIP_TRY(attn_simple_bwd(D.dtype, a, st));
+    return MMTRAIN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,398 @@
+// HBM-bound kernels of the layer: token bookkeeping, RMSNorm / LayerNorm forward and
+// backward, rotary embedding, SwiGLU / GELU, column sums.  All arithmetic is fp32;
+// storage is fp32 or bf16.  Every kernel moves 16 bytes per lane per access and
+// touches each tensor once (rows are re-read from cache, not from HBM).
+#include "kernels.h"
+
+namespace mmt {
+
+// ---- 8-element vector access --------------------------------------------------------
+__device__ __forceinline__ void load8(const float *p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t *p, float (&v)[8]) {
+    const uint4 a = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void store8(float *p, const float (&v)[8]) {
+    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(bf16_t *p, const float (&v)[8]) {
+    uint4 a;
+    a.x = pack_bf16x2(v[0], v[1]); a.y = pack_bf16x2(v[2], v[3]);
+    a.z = pack_bf16x2(v[4], v[5]); a.w = pack_bf16x2(v[6], v[7]);
+    *reinterpret_cast<uint4 *>(p) = a;
+}
+
+// ---- token bookkeeping ---------------------------------------------------------------
+// tok_seg[t] = s with cu[s] <= t < cu[s+1].
+__device__ __forceinline__ int find_segment(const int *__restrict__ cu, int S, int t) {
+    int lo = 0, hi = S;               // last s in [0, S) with cu[s] <= t
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void tok_seg_kernel(const int *__restrict__ cu, int S, int T, int *__restrict__ tok_seg) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < T) tok_seg[t] = find_segment(cu, S, t);
+}
+
+// rope_cs[t, i] = (cos, sin)(pos(t) * base^(-2i/d)), pos(t) = t - cu[seg(t)]; evaluated in double
+// so that the fp32 table is correctly rounded for any position.
+__global__ void rope_table_kernel(const int *__restrict__ cu, int S, int T, int d, float rope_base,
+                                  float2 *__restrict__ rope_cs) {
+    const int half = d >> 1;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)T * half) return;
+    const int t = (int)(idx / half), i = (int)(idx % half);
+    const double pos = (double)(t - cu[find_segment(cu, S, t)]);
+    const double phi = pos * exp(-2.0 * i / d * log((double)rope_base));
+    rope_cs[idx] = make_float2((float)cos(phi), (float)sin(phi));
+}
+
+hipError_t prep_tokens(const int *cu, int S, int T, int *tok_seg, int d, float rope_base, float2 *rope_cs,
+                       hipStream_t st) {
+    if (T == 0) return hipSuccess;
+    tok_seg_kernel<<<ceil_div(T, 256), 256, 0, st>>>(cu, S, T, tok_seg);
+    if (rope_cs) rope_table_kernel<<<ceil_div((long)T * (d / 2), 256), 256, 0, st>>>(cu, S, T, d, rope_base, rope_cs);
+    return hipGetLastError();
+}
+
+// ---- normalisation forward -----------------------------------------------------------
+// One workgroup per row.  RMSNorm: out = x * rsqrt(mean(x^2) + eps) * g.
+// LayerNorm: out = (x - mean) * rsqrt(var_biased + eps) * g + b (variance about the mean, two passes).
+template <typename T, bool LN>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, const T *__restrict__ g,
+                                                       const T *__restrict__ b, T *__restrict__ out,
+                                                       float *__restrict__ mean, float *__restrict__ rstd,
+                                                       int H, float eps) {
+    __shared__ float red[4];
+    const size_t row = blockIdx.x;
+    const T *xr = x + row * H;
+    float v[8];
+    float mu = 0.f;
+    if (LN) {
+        float s = 0.f;
+        for (int c = threadIdx.x * 8; c < H; c += 2048) {
+            load8(xr + c, v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += v[j];
+        }
+        mu = block_sum<4>(s, red) / H;
+    }
+    float ss = 0.f;
+    for (int c = threadIdx.x * 8; c < H; c += 2048) {
+        load8(xr + c, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ss += (v[j] - mu) * (v[j] - mu);
+    }
+    const float r = 1.0f / sqrtf(block_sum<4>(ss, red) / H + eps);
+    if (threadIdx.x == 0) {
+        rstd[row] = r;
+        if (LN) mean[row] = mu;
+    }
+    float gv[8], bv[8];
+    for (int c = threadIdx.x * 8; c < H; c += 2048) {
+        load8(xr + c, v);
+        load8(g + c, gv);
+        if (LN) load8(b + c, bv);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = (v[j] - mu) * r * gv[j] + (LN ? bv[j] : 0.f);
+        store8(out + row * H + c, v);
+    }
+}
+
+hipError_t norm_fwd(int dtype, bool layernorm, const void *x, const void *g, const void *b, void *out,
+                    float *mean, float *rstd, int T, int H, float eps, hipStream_t st) {
+    if (T == 0) return hipSuccess;
+#define L(TT, LNV) norm_fwd_kernel<TT, LNV><<<T, 256, 0, st>>>((const TT *)x, (const TT *)g, (const TT *)b, (TT *)out, mean, rstd, H, eps)
+    if (dtype == DT_F32) { if (layernorm) L(float, true); else L(float, false); }
+    else { if (layernorm) L(bf16_t, true); else L(bf16_t, false); }
+#undef L
+    return hipGetLastError();
+}
+
+// ---- normalisation backward ----------------------------------------------------------
+// With xhat = (x - mean) * r and ghat = d_out * g:
+//   d_in = r * (ghat - mean_H(ghat) [LayerNorm only] - xhat * mean_H(ghat * xhat)) + d_res
+//   dg = sum_t d_out * xhat,  db = sum_t d_out.
+// A workgroup walks rows blockIdx.x, blockIdx.x + gridDim.x, ...; each thread owns the same
+// columns in every row, so the gain/bias partial sums stay in registers and are written once
+// per workgroup to part_g / part_b [gridDim.x, H].
+constexpr int NORM_BWD_MAXC = 4;          // column chunks of 8 per thread: H <= 256 * 8 * 4 = 8192
+constexpr int NORM_BWD_GRID = 512;
+
+int norm_bwd_blocks(int T) { return T < NORM_BWD_GRID ? (T > 0 ? T : 1) : NORM_BWD_GRID; }
+
+template <typename T, bool LN>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ d_out, const T *__restrict__ x,
+                                                       const T *__restrict__ g, const float *__restrict__ mean,
+                                                       const float *__restrict__ rstd, const T *__restrict__ d_res,
+                                                       T *__restrict__ d_in, float *__restrict__ part_g,
+                                                       float *__restrict__ part_b, int nrows, int H) {
+    __shared__ float red[4];
+    float gv[NORM_BWD_MAXC][8], ag[NORM_BWD_MAXC][8], ab[NORM_BWD_MAXC][8];
+#pragma unroll
+    for (int i = 0; i < NORM_BWD_MAXC; ++i) {
+        const int c = (threadIdx.x + i * 256) * 8;
+        if (c < H) load8(g + c, gv[i]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { ag[i][j] = 0.f; ab[i][j] = 0.f; }
+    }
+    for (size_t row = blockIdx.x; row < (size_t)nrows; row += gridDim.x) {
+        const float r = rstd[row];
+        const float mu = LN ? mean[row] : 0.f;
+        float dv[NORM_BWD_MAXC][8], xh[NORM_BWD_MAXC][8];
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NORM_BWD_MAXC; ++i) {
+            const int c = (threadIdx.x + i * 256) * 8;
+            if (c < H) {
+                load8(d_out + row * H + c, dv[i]);
+                load8(x + row * H + c, xh[i]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    xh[i][j] = (xh[i][j] - mu) * r;
+                    ag[i][j] += dv[i][j] * xh[i][j];
+                    ab[i][j] += dv[i][j];
+                    dv[i][j] *= gv[i][j];          // ghat
+                    s0 += dv[i][j];
+                    s1 += dv[i][j] * xh[i][j];
+                }
+            }
+        }
+        s1 = block_sum<4>(s1, red) / H;
+        s0 = LN ? block_sum<4>(s0, red) / H : 0.f;
+#pragma unroll
+        for (int i = 0; i < NORM_BWD_MAXC; ++i) {
+            const int c = (threadIdx.x + i * 256) * 8;
+            if (c < H) {
+                float rv[8];
+                load8(d_res + row * H + c, rv);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) rv[j] += r * (dv[i][j] - s0 - xh[i][j] * s1);
+                store8(d_in + row * H + c, rv);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NORM_BWD_MAXC; ++i) {
+        const int c = (threadIdx.x + i * 256) * 8;
+        if (c < H) {
+            if (part_g) store8(part_g + (size_t)blockIdx.x * H + c, ag[i]);
+            if (LN && part_b) store8(part_b + (size_t)blockIdx.x * H + c, ab[i]);
+        }
+    }
+}
+
+hipError_t norm_bwd(int dtype, bool layernorm, const void *d_out, const void *x, const void *g,
+                    const float *mean, const float *rstd, const void *d_res, void *d_in, float *part_g,
+                    float *part_b, int T, int H, hipStream_t st) {
+    if (T == 0) return hipSuccess;
+    if (H > 256 * 8 * NORM_BWD_MAXC) return hipErrorInvalidValue;
+    const int grid = norm_bwd_blocks(T);
+#define L(TT, LNV) norm_bwd_kernel<TT, LNV><<<grid, 256, 0, st>>>((const TT *)d_out, (const TT *)x, (const TT *)g, mean, rstd, (const TT *)d_res, (TT *)d_in, part_g, part_b, T, H)
+    if (dtype == DT_F32) { if (layernorm) L(float, true); else L(float, false); }
+    else { if (layernorm) L(bf16_t, true); else L(bf16_t, false); }
+#undef L
+    return hipGetLastError();
+}
+
+// ---- partial-sum reduction -----------------------------------------------------------
+template <typename T>
+__global__ void reduce_partials_kernel(const float *__restrict__ part, int rows, int N, T *__restrict__ out,
+                                       bool accumulate) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= N) return;
+    float s = 0.f;
+    for (int r = 0; r < rows; ++r) s += part[(size_t)r * N + c];
+    if (accumulate) s += Elem<T>::load(out + c);
+    Elem<T>::store(out + c, s);
+}
+
+hipError_t reduce_partials(int dtype, const float *part, int rows, int N, void *out, bool accumulate,
+                           hipStream_t st) {
+    if (N == 0) return hipSuccess;
+    if (dtype == DT_F32) reduce_partials_kernel<float><<<ceil_div(N, 64), 64, 0, st>>>(part, rows, N, (float *)out, accumulate);
+    else reduce_partials_kernel<bf16_t><<<ceil_div(N, 64), 64, 0, st>>>(part, rows, N, (bf16_t *)out, accumulate);
+    return hipGetLastError();
+}
+
+// ---- column sums (bias gradients) ----------------------------------------------------
+constexpr int COLSUM_ROWS = 64;
+int colsum_slabs(int T) { return T > 0 ? ceil_div(T, COLSUM_ROWS) : 1; }
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ in, int nrows, int N, int ld,
+                                                     float *__restrict__ part) {
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 8;
+    if (c >= N) return;
+    const int r0 = blockIdx.y * COLSUM_ROWS;
+    const int r1 = min(nrows, r0 + COLSUM_ROWS);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, v[8];
+    for (int r = r0; r < r1; ++r) {
+        load8(in + (size_t)r * ld + c, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += v[j];
+    }
+    store8(part + (size_t)blockIdx.y * N + c, acc);
+}
+
+hipError_t colsum_partials(int dtype, const void *in, int T, int N, int ld, float *part, hipStream_t st) {
+    if (T == 0 || N == 0) return hipSuccess;
+    dim3 grid(ceil_div(N, 2048), colsum_slabs(T));
+    if (dtype == DT_F32) colsum_kernel<float><<<grid, 256, 0, st>>>((const float *)in, T, N, ld, part);
+    else colsum_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t *)in, T, N, ld, part);
+    return hipGetLastError();
+}
+
+// ---- rotary embedding, in place ------------------------------------------------------
+// Heads [0, n_rot_heads) of every row (the q heads then the k heads) are rotated on the pair
+// (i, i + d/2) by the tabulated angle of the token's position in its segment.  inverse = the
+// transposed rotation (backward pass).
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int ld, int ntok, int n_rot_heads, int d,
+                                                   const float2 *__restrict__ cs, float sgn) {
+    const int half = d >> 1, cpp = half >> 3;                    // 8-wide chunks per half head
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    const long total = (long)ntok * n_rot_heads * cpp;
+    if (idx >= total) return;
+    const int ch = (int)(idx % cpp);
+    const int h = (int)((idx / cpp) % n_rot_heads);
+    const long t = idx / ((long)cpp * n_rot_heads);
+    T *p = qkv + t * ld + h * d + ch * 8;
+    float lo[8], hi[8];
+    load8(p, lo);
+    load8(p + half, hi);
+    const float2 *c = cs + t * half + ch * 8;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float co = c[j].x, si = sgn * c[j].y;
+        const float a = lo[j] * co - hi[j] * si, b = hi[j] * co + lo[j] * si;
+        lo[j] = a; hi[j] = b;
+    }
+    store8(p, lo);
+    store8(p + half, hi);
+}
+
+hipError_t rope_inplace(int dtype, void *qkv, int ld, int T, int n_rot_heads, int d, const float2 *rope_cs,
+                        bool inverse, hipStream_t st) {
+    const long total = (long)T * n_rot_heads * (d / 16);
+    if (total == 0) return hipSuccess;
+    const float sgn = inverse ? -1.f : 1.f;
+    if (dtype == DT_F32) rope_kernel<float><<<ceil_div(total, 256), 256, 0, st>>>((float *)qkv, ld, T, n_rot_heads, d, rope_cs, sgn);
+    else rope_kernel<bf16_t><<<ceil_div(total, 256), 256, 0, st>>>((bf16_t *)qkv, ld, T, n_rot_heads, d, rope_cs, sgn);
+    return hipGetLastError();
+}
+
+// ---- SwiGLU --------------------------------------------------------------------------
+// gu[T, 2F] = [gate | up];  m = gate * sigmoid(gate) * up.
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T *__restrict__ gu, T *__restrict__ m, long nchunks, int F) {
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nchunks) return;
+    const int cpr = F >> 3;
+    const long t = idx / cpr;
+    const int c = (int)(idx % cpr) * 8;
+    float g[8], u[8];
+    load8(gu + t * 2 * F + c, g);
+    load8(gu + t * 2 * F + F + c, u);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) g[j] = g[j] / (1.f + expf(-g[j])) * u[j];
+    store8(m + t * F + c, g);
+}
+
+// d_gate = d_m * up * s * (1 + gate * (1 - s)),  d_up = d_m * gate * s,  s = sigmoid(gate).
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T *__restrict__ d_m, const T *__restrict__ gu,
+                                                         T *__restrict__ d_gu, long nchunks, int F) {
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nchunks) return;
+    const int cpr = F >> 3;
+    const long t = idx / cpr;
+    const int c = (int)(idx % cpr) * 8;
+    float g[8], u[8], dm[8];
+    load8(gu + t * 2 * F + c, g);
+    load8(gu + t * 2 * F + F + c, u);
+    load8(d_m + t * F + c, dm);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float s = 1.f / (1.f + expf(-g[j]));
+        const float dg = dm[j] * u[j] * s * (1.f + g[j] * (1.f - s));
+        u[j] = dm[j] * g[j] * s;
+        g[j] = dg;
+    }
+    store8(d_gu + t * 2 * F + c, g);
+    store8(d_gu + t * 2 * F + F + c, u);
+}
+
+hipError_t swiglu_fwd(int dtype, const void *gu, void *m, int T, int F, hipStream_t st) {
+    const long n = (long)T * (F / 8);
+    if (n == 0) return hipSuccess;
+    if (dtype == DT_F32) swiglu_fwd_kernel<float><<<ceil_div(n, 256), 256, 0, st>>>((const float *)gu, (float *)m, n, F);
+    else swiglu_fwd_kernel<bf16_t><<<ceil_div(n, 256), 256, 0, st>>>((const bf16_t *)gu, (bf16_t *)m, n, F);
+    return hipGetLastError();
+}
+hipError_t swiglu_bwd(int dtype, const void *d_m, const void *gu, void *d_gu, int T, int F, hipStream_t st) {
+    const long n = (long)T * (F / 8);
+    if (n == 0) return hipSuccess;
+    if (dtype == DT_F32) swiglu_bwd_kernel<float><<<ceil_div(n, 256), 256, 0, st>>>((const float *)d_m, (const float *)gu, (float *)d_gu, n, F);
+    else swiglu_bwd_kernel<bf16_t><<<ceil_div(n, 256), 256, 0, st>>>((const bf16_t *)d_m, (const bf16_t *)gu, (bf16_t *)d_gu, n, F);
+    return hipGetLastError();
+}
+
+// ---- GELU (erf form) -----------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ z, T *__restrict__ a, long nchunks) {
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nchunks) return;
+    float v[8];
+    load8(z + idx * 8, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = 0.5f * v[j] * (1.f + erff(v[j] * 0.70710678118654752f));
+    store8(a + idx * 8, v);
+}
+// gelu'(z) = Phi(z) + z * phi(z)
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(const T *__restrict__ d_a, const T *__restrict__ z,
+                                                       T *__restrict__ d_z, long nchunks) {
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nchunks) return;
+    float v[8], g[8];
+    load8(z + idx * 8, v);
+    load8(d_a + idx * 8, g);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float cdf = 0.5f * (1.f + erff(v[j] * 0.70710678118654752f));
+        const float pdf = 0.3989422804014327f * expf(-0.5f * v[j] * v[j]);
+        v[j] = g[j] * (cdf + v[j] * pdf);
+    }
+    store8(d_z + idx * 8, v);
+}
+
+hipError_t gelu_fwd(int dtype, const void *z, void *a, long n, hipStream_t st) {
+    const long nc = n / 8;
+    if (nc == 0) return hipSuccess;
+    if (dtype == DT_F32) gelu_fwd_kernel<float><<<ceil_div(nc, 256), 256, 0, st>>>((const float *)z, (float *)a, nc);
+    else gelu_fwd_kernel<bf16_t><<<ceil_div(nc, 256), 256, 0, st>>>((const bf16_t *)z, (bf16_t *)a, nc);
+    return hipGetLastError();
+}
+hipError_t gelu_bwd(int dtype, const void *d_a, const void *z, void *d_z, long n, hipStream_t st) {
+    const long nc = n / 8;
+    if (nc == 0) return hipSuccess;
+    if (dtype == DT_F32) gelu_bwd_kernel<float><<<ceil_div(nc, 256), 256, 0, st>>>((const float *)d_a, (const float *)z, (float *)d_z, nc);
+    else gelu_bwd_kernel<bf16_t><<<ceil_div(nc, 256), 256, 0, st>>>((const bf16_t *)d_a, (const bf16_t *)z, (bf16_t *)d_z, nc);
+    return hipGetLastError();
+}
+
+}  // namespace mmt

@@ -1,0 +1,74 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernel files.
+// Every launcher enqueues on `st` and returns the launch status; none synchronises.
+#pragma once
+#include "common.h"
+
+namespace mmt {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
+enum { MASK_CAUSAL = 0, MASK_BIDIR = 1 };
+
+struct GemmArgs {
+    int layout;                 // GEMM_NT / GEMM_NN / GEMM_TN
+    int M, N, K;
+    const void *A; int lda;
+    const void *B; int ldb;
+    void *C; int ldc;
+    const void *bias;           // [N] or null
+    const void *residual;       // [M, ldc] or null
+    bool accumulate;            // C += result
+};
+
+// gemm_simple.hip: any dtype, any shape, LDS-tiled FMA kernel (the fp32 path).
+hipError_t gemm_simple(int dtype, const GemmArgs &g, hipStream_t st);
+// gemm_mfma.hip: bf16 MFMA kernel.  `supported` checks alignment requirements.
+bool gemm_mfma_supported(const GemmArgs &g);
+hipError_t gemm_mfma(const GemmArgs &g, hipStream_t st);
+
+// Segment bookkeeping produced by prep_tokens():
+//   tok_seg[t] = index of the segment that holds token t.
+struct AttnArgs {
+    int T, S, nh, nkv, d;
+    float scale;
+    const int *cu;              // device [S+1]
+    const uint8_t *modes;       // device [S] or null
+    int default_mode;
+    const int *tok_seg;         // device [T]
+    const void *qkv; int ld_qkv;
+    void *o;                    // [T, nh*d]
+    float *lse;                 // [nh, T]
+    const void *d_o;            // bwd: [T, nh*d]
+    void *d_qkv;                // bwd: [T, ld_qkv]
+    float *Dsum;                // bwd scratch: [nh, T]
+    // MFMA path: tile work list (device, built by prep_attn_tiles)
+    const int4 *q_tiles; int n_q_tiles;     // {row0, seg_begin, seg_end, mode}
+    const int4 *kv_tiles; int n_kv_tiles;
+};
+hipError_t attn_simple_fwd(int dtype, const AttnArgs &a, hipStream_t st);
+hipError_t attn_simple_bwd(int dtype, const AttnArgs &a, hipStream_t st);
+
+// elementwise.hip
+hipError_t prep_tokens(const int *cu, int S, int T, int *tok_seg, int d, float rope_base,
+                       float2 *rope_cs /* [T, d/2] or null */, hipStream_t st);
+hipError_t norm_fwd(int dtype, bool layernorm, const void *x, const void *g, const void *b, void *out,
+                    float *mean, float *rstd, int T, int H, float eps, hipStream_t st);
+// d_in = norm_bwd(d_out) + d_res;  gain/bias gradient partial sums go to part_g/part_b
+// ([norm_bwd_blocks(T), H] fp32 each; null = skip).
+int norm_bwd_blocks(int T);
+hipError_t norm_bwd(int dtype, bool layernorm, const void *d_out, const void *x, const void *g,
+                    const float *mean, const float *rstd, const void *d_res, void *d_in,
+                    float *part_g, float *part_b, int T, int H, hipStream_t st);
+// out[c] (+)= sum_r part[r, c]
+hipError_t reduce_partials(int dtype, const float *part, int rows, int N, void *out, bool accumulate,
+                           hipStream_t st);
+int colsum_slabs(int T);
+hipError_t colsum_partials(int dtype, const void *in, int T, int N, int ld, float *part, hipStream_t st);
+hipError_t rope_inplace(int dtype, void *qkv, int ld, int T, int n_rot_heads, int d, const float2 *rope_cs,
+                        bool inverse, hipStream_t st);
+hipError_t swiglu_fwd(int dtype, const void *gu, void *m, int T, int F, hipStream_t st);
+hipError_t swiglu_bwd(int dtype, const void *d_m, const void *gu, void *d_gu, int T, int F, hipStream_t st);
+hipError_t gelu_fwd(int dtype, const void *z, void *a, long n, hipStream_t st);
+hipError_t gelu_bwd(int dtype, const void *d_a, const void *z, void *d_z, long n, hipStream_t st);
+
+}  // namespace mmt

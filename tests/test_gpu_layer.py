@@ -1,0 +1,116 @@
+"""GPU parity of mmtrain_layer_fwd / mmtrain_layer_bwd against the fp64 oracle, element by element,
+on the same seeded inputs: small cases that span several tiles with ragged tails, the edge
+cases, and the five workloads at full size."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2408_04275_amd import binding as mm
+from paper_2408_04275_amd import workloads as wl
+from paper_2408_04275_amd.harness import LayerRunner, check
+from util import compare_layer, gpu_run, oracle_run, say, summary
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(shape, cu, modes, seed=0, std=0.02, what="", bars=None):
+    W = wl.make_weights(shape, seed, std=std)
+    x, dy = wl.make_activations(shape, int(cu[-1]), seed)
+    ref = oracle_run(shape, cu, modes, W, x, dy)
+    got = gpu_run(shape, cu, modes, W, x, dy)
+    errs = compare_layer(shape, got, ref, what, bars)
+    say(f"{what or shape.name}: worst over {len(errs)} tensors: {summary(errs)}")
+    return errs
+
+
+# ---- workload 1 (fp32), both readings of the image span's mask ------------------------
+@pytest.mark.parametrize("image_bidir", [False, True])
+def test_config1_fp32(image_bidir):
+    cu, modes, _ = wl.make_segments(1, image_bidir=image_bidir)
+    run_case(wl.SHAPES[1], cu, modes, what=f"config1 image_bidir={image_bidir} ")
+
+
+# ---- reduced shapes: several tiles, ragged tails, every code path ----------------------
+RAGGED_CU = np.array([0, 1, 1, 70, 199, 200, 457, 648], dtype=np.int32)
+RAGGED_MODES = np.array([0, 1, 1, 0, 1, 0, 1], dtype=np.uint8)
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("nh,nkv,d,H,F", [(4, 2, 64, 272, 688), (2, 1, 128, 256, 528)])
+def test_small_decoder(dtype, nh, nkv, d, H, F):
+    shape = wl.LayerShape("small-dec", wl.DECODER, dtype, H, nh, nkv, d, F, 648)
+    run_case(shape, RAGGED_CU, RAGGED_MODES, seed=1, std=0.05, what=f"small decoder dtype={dtype} d={d} ")
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_small_encoder(dtype):
+    shape = wl.LayerShape("small-enc", wl.ENCODER, dtype, 272, 4, 4, 64, 528, 648)
+    run_case(shape, RAGGED_CU, np.ones(7, dtype=np.uint8), seed=2, std=0.05, what=f"small encoder dtype={dtype} ")
+
+
+def test_peaky_softmax_decoder():
+    # large weights make the softmax far from uniform, so masking and max-subtraction mistakes show
+    shape = wl.LayerShape("peaky", wl.DECODER, wl.F32, 256, 4, 2, 64, 512, 648)
+    run_case(shape, RAGGED_CU, RAGGED_MODES, seed=3, std=0.15, what="peaky decoder ")
+
+
+# ---- edge cases ----------------------------------------------------------------------
+def test_empty_pack():
+    shape = wl.LayerShape("e", wl.DECODER, wl.BF16, 256, 4, 2, 64, 512, 0)
+    W = wl.make_weights(shape, 0)
+    r = LayerRunner(shape, W, np.array([0, 0], dtype=np.int32))
+    for g in r.g.values():
+        g.fill_(1.0)
+    r.step()
+    torch.cuda.synchronize()
+    assert all(float(g.abs().max()) == 0.0 for g in r.g.values())      # an empty pack contributes zero gradients
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_single_token_segments_only(dtype):
+    # nine tokens: a weight gradient is a sum of nine products, whose near-zero elements make the
+    # floored element-wise ratio heavy-tailed in bf16; the fp32 run holds the edge logic to 1e-4
+    shape = wl.LayerShape("one", wl.DECODER, dtype, 256, 4, 2, 64, 512, 16)
+    run_case(shape, np.arange(0, 10, dtype=np.int32), np.zeros(9, dtype=np.uint8), seed=4,
+             what=f"single-token segments dtype={dtype} ", bars={"floor_err": 1e-1} if dtype == wl.BF16 else None)
+
+
+def test_accumulate_and_frozen():
+    shape = wl.LayerShape("acc", wl.DECODER, wl.BF16, 256, 4, 2, 64, 512, 648)
+    W = wl.make_weights(shape, 5, std=0.05)
+    x, dy = wl.make_activations(shape, 648, 5)
+    y, dx, G = oracle_run(shape, RAGGED_CU, RAGGED_MODES, W, x, dy)
+    # two accumulating backward passes give twice the gradient
+    r = LayerRunner(shape, W, RAGGED_CU, RAGGED_MODES)
+    r.set_inputs(x, dy)
+    r.step()
+    check(r.backward(mm.BWD_ACCUMULATE_WGRAD), "bwd accumulate")
+    gy, gdx, gG = r.results()
+    compare_layer(shape, (gy, gdx, gG), (y, dx, {k: 2 * v for k, v in G.items()}), "accumulate ")
+    # frozen module: no weight gradients requested, input gradient still produced
+    r2 = LayerRunner(shape, W, RAGGED_CU, RAGGED_MODES, grad_names=[])
+    r2.set_inputs(x, dy)
+    r2.step()
+    _, fdx, fG = r2.results()
+    assert fG == {} and np.array_equal(fdx, gdx)
+    # partially frozen: only the MLP matrices
+    gy3, gdx3, gG3 = gpu_run(shape, RAGGED_CU, RAGGED_MODES, W, x, dy, grad_names=["w_fc1", "w_fc2"])
+    compare_layer(shape, (gy3, gdx3, gG3), (y, dx, {k: G[k] for k in ("w_fc1", "w_fc2")}), "partial ")
+
+
+def test_segment_order_invariance_on_gpu():
+    # Section 5.2: reordering subsequences permutes outputs block-wise; summed weight gradients agree to rounding
+    shape = wl.LayerShape("perm", wl.DECODER, wl.BF16, 256, 4, 2, 64, 512, 648)
+    W = wl.make_weights(shape, 6, std=0.05)
+    x, dy = wl.make_activations(shape, 648, 6)
+    y, dx, G = gpu_run(shape, RAGGED_CU, RAGGED_MODES, W, x, dy)
+    perm = [5, 0, 3, 6, 2, 1, 4]
+    blocks = [(RAGGED_CU[s], RAGGED_CU[s + 1]) for s in perm]
+    xp = np.concatenate([x[a:b] for a, b in blocks]); dyp = np.concatenate([dy[a:b] for a, b in blocks])
+    cup = np.concatenate([[0], np.cumsum([b - a for a, b in blocks])]).astype(np.int32)
+    yp, dxp, Gp = gpu_run(shape, cup, RAGGED_MODES[perm], W, xp, dyp)
+    from paper_2408_04275_amd.parity import check as bars
+    bars("y", yp, np.concatenate([y[a:b] for a, b in blocks]), wl.BF16)
+    bars("dx", dxp, np.concatenate([dx[a:b] for a, b in blocks]), wl.BF16)
+    for k in G:
+        bars(k, Gp[k], G[k], wl.BF16)

@@ -1,0 +1,120 @@
+"""GPU parity of the operator-level entry points (GEMM family, attention) against fp64 definitions."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer_oracle as orc
+from paper_2408_04275_amd import binding as mm
+from paper_2408_04275_amd import workloads as wl
+from paper_2408_04275_amd.harness import check, to_device, to_host, torch_dtype
+from util import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def gemm_case(dtype, layout, M, N, K, bias=False, residual=False, accumulate=False, seed=0):
+    rng = np.random.default_rng(seed)
+    shp_a = (K, M) if layout == mm.GEMM_TN else (M, K)
+    shp_b = (N, K) if layout == mm.GEMM_NT else (K, N)
+    A = wl.round_to(rng.standard_normal(shp_a), dtype)
+    B = wl.round_to(rng.standard_normal(shp_b), dtype)
+    C0 = wl.round_to(rng.standard_normal((M, N)), dtype)
+    bv = wl.round_to(rng.standard_normal(N), dtype) if bias else None
+    R = wl.round_to(rng.standard_normal((M, N)), dtype) if residual else None
+    a64 = A.astype(np.float64).T if layout == mm.GEMM_TN else A.astype(np.float64)
+    b64 = B.astype(np.float64).T if layout == mm.GEMM_NT else B.astype(np.float64)
+    ref = a64 @ b64
+    if bias: ref = ref + bv[None, :]
+    if residual: ref = ref + R
+    if accumulate: ref = ref + C0
+    dA, dB, dC = to_device(A, dtype), to_device(B, dtype), to_device(C0, dtype)
+    dbias = to_device(bv, dtype) if bias else None
+    dR = to_device(R, dtype) if residual else None
+    check(mm.mmtrain_gemm(dtype, layout, M, N, K, dA, shp_a[1], dB, shp_b[1], dC, N, dbias, dR,
+                          mm.GEMM_ACCUMULATE if accumulate else 0), "mmtrain_gemm")
+    torch.cuda.synchronize()
+    got = to_host(dC)
+    # one bf16 rounding of the fp32-accumulated result: at most 2^-9 relative per element
+    bars = {"max_err": 4e-3, "floor_err": 8e-3, "l2_err": 2.5e-3} if dtype == mm.BF16 else \
+        {k: 2e-6 * np.sqrt(max(K, 1)) for k in ("max_err", "floor_err", "l2_err")}
+    assert_parity(f"gemm{layout} {M}x{N}x{K}", got, ref, dtype, bars)
+
+
+SHAPES = [(8, 8, 8), (256, 256, 64), (304, 520, 136), (512, 1376, 256), (264, 248, 688), (1000, 264, 72)]
+
+
+@pytest.mark.parametrize("layout", [mm.GEMM_NT, mm.GEMM_NN, mm.GEMM_TN])
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_gemm_bf16(layout, M, N, K):
+    gemm_case(mm.BF16, layout, M, N, K)
+
+
+@pytest.mark.parametrize("layout", [mm.GEMM_NT, mm.GEMM_NN, mm.GEMM_TN])
+def test_gemm_bf16_epilogues(layout):
+    gemm_case(mm.BF16, layout, 520, 776, 200, bias=True, residual=True, seed=1)
+    gemm_case(mm.BF16, layout, 520, 776, 200, accumulate=True, seed=2)
+    gemm_case(mm.BF16, layout, 520, 776, 200, bias=True, accumulate=True, residual=True, seed=3)
+
+
+@pytest.mark.parametrize("layout", [mm.GEMM_NT, mm.GEMM_NN, mm.GEMM_TN])
+def test_gemm_bf16_many_tiles(layout):
+    # more tiles than compute units' worth of one XCD, ragged in every dimension
+    gemm_case(mm.BF16, layout, 2056, 2312, 328, seed=4)
+
+
+@pytest.mark.parametrize("layout", [mm.GEMM_NT, mm.GEMM_NN, mm.GEMM_TN])
+@pytest.mark.parametrize("M,N,K", [(7, 5, 3), (130, 70, 33), (512, 768, 256), (64, 64, 0)])
+def test_gemm_f32(layout, M, N, K):
+    gemm_case(mm.F32, layout, M, N, K, bias=True, residual=True, accumulate=(K == 33))
+
+
+def attn_case(dtype, nh, nkv, d, cu, modes, seed=0, std=1.0):
+    rng = np.random.default_rng(seed)
+    T = int(cu[-1])
+    nq, nk = nh * d, nkv * d
+    qkv = wl.round_to(rng.standard_normal((T, nq + 2 * nk)) * std, dtype)
+    d_o = wl.round_to(rng.standard_normal((T, nq)), dtype)
+    q = qkv[:, :nq].reshape(T, nh, d).astype(np.float64)
+    k = qkv[:, nq:nq + nk].reshape(T, nkv, d).astype(np.float64)
+    v = qkv[:, nq + nk:].reshape(T, nkv, d).astype(np.float64)
+    scale = 1.0 / np.sqrt(d)
+    o_ref, lse_ref = orc.attention_fwd(q, k, v, cu, modes, scale)
+    desc = mm.make_desc(mm.DECODER, dtype, 64, nh, nkv, d, 64)
+    batch = mm.PackedBatch.on_device(cu, modes)
+    wsb = mm.mmtrain_attn_workspace_bytes(T, len(cu) - 1, nh)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    dqkv = to_device(qkv, dtype)
+    o = torch.zeros((T, nq), dtype=torch_dtype(dtype), device="cuda")
+    lse = torch.zeros((nh, T), dtype=torch.float32, device="cuda")
+    check(mm.mmtrain_attn_fwd(desc, batch, dqkv, o, lse, ws, wsb), "mmtrain_attn_fwd")
+    torch.cuda.synchronize()
+    bars = {"max_err": 4e-3, "floor_err": 1e-2, "l2_err": 3e-3} if dtype == mm.BF16 else \
+        {k: 2e-5 for k in ("max_err", "floor_err", "l2_err")}
+    assert_parity("o", to_host(o), o_ref.reshape(T, nq), dtype, bars)
+    assert np.max(np.abs(lse.cpu().numpy() - lse_ref)) < (2e-2 if dtype == mm.BF16 else 1e-4)
+    # backward from the oracle's view of the stored (rounded) output
+    dq, dk, dv = orc.attention_bwd(d_o.reshape(T, nh, d).astype(np.float64), q, k, v, cu, modes, scale)
+    ref = np.concatenate([dq.reshape(T, nq), dk.reshape(T, nk), dv.reshape(T, nk)], axis=1)
+    d_qkv = torch.zeros_like(dqkv)
+    check(mm.mmtrain_attn_bwd(desc, batch, dqkv, o, lse, to_device(d_o, dtype), d_qkv, ws, wsb), "mmtrain_attn_bwd")
+    torch.cuda.synchronize()
+    got = to_host(d_qkv)
+    assert_parity("dq", got[:, :nq], ref[:, :nq], dtype)
+    assert_parity("dk", got[:, nq:nq + nk], ref[:, nq:nq + nk], dtype)
+    assert_parity("dv", got[:, nq + nk:], ref[:, nq + nk:], dtype)
+
+
+RAGGED_CU = np.array([0, 1, 1, 70, 199, 200, 457, 640], dtype=np.int32)   # length-1, empty, mid-tile boundaries
+RAGGED_MODES = np.array([0, 1, 1, 0, 1, 0, 1], dtype=np.uint8)
+
+
+@pytest.mark.parametrize("dtype", [mm.F32, mm.BF16])
+@pytest.mark.parametrize("nh,nkv,d", [(4, 4, 64), (4, 2, 128), (8, 1, 64)])
+def test_attention_ragged(dtype, nh, nkv, d):
+    attn_case(dtype, nh, nkv, d, RAGGED_CU, RAGGED_MODES, std=1.5)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_attention_one_long_segment(mode):
+    attn_case(mm.BF16, 2, 1, 128, np.array([0, 1100], dtype=np.int32), np.array([mode], dtype=np.uint8), seed=3)
+    attn_case(mm.BF16, 2, 2, 64, np.array([0, 777], dtype=np.int32), np.array([mode], dtype=np.uint8), seed=4)
