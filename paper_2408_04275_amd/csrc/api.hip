@@ -32,6 +32,7 @@ struct Dims {
 struct Ctx {
     float *mean1, *rstd1, *mean2, *rstd2, *lse;
     int *tok_seg;
+    int2 *tok_info;
     float2 *rope_cs;
     void *h1, *qkv, *o, *y1, *h2, *pre, *m;
 };
@@ -95,6 +96,7 @@ void carve_ctx(Bump &b, const Dims &D, size_t T, Ctx &c) {
     c.mean2 = b.take<float>(T); c.rstd2 = b.take<float>(T);
     c.lse = b.take<float>(T * D.nh);
     c.tok_seg = b.take<int>(T);
+    c.tok_info = b.take<int2>(T);
     c.rope_cs = D.kind == MMTRAIN_DECODER ? b.take<float2>(T * (D.d / 2)) : nullptr;
     c.h1 = b.take_elems(T * D.H, D.dtype);
     c.qkv = b.take_elems(T * D.nqkv, D.dtype);
@@ -119,8 +121,15 @@ void carve_bwd(Bump &b, const Dims &D, size_t T, BwdWs &w) {
     w.part_c = b.take<float>((size_t)colsum_slabs((int)T) * maxn);
 }
 
-struct Profiler;
 hipError_t gemm(int dtype, const GemmArgs &g, hipStream_t st);
+
+// bf16 storage runs on the matrix cores; fp32 storage on the vector ALUs
+hipError_t attn_fwd(int dtype, const AttnArgs &a, hipStream_t st) {
+    return dtype == DT_BF16 ? attn_mfma_fwd(a, st) : attn_simple_fwd(dtype, a, st);
+}
+hipError_t attn_bwd(int dtype, const AttnArgs &a, hipStream_t st) {
+    return dtype == DT_BF16 ? attn_mfma_bwd(a, st) : attn_simple_bwd(dtype, a, st);
+}
 
 GemmArgs mk(int layout, int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
             const void *bias = nullptr, const void *residual = nullptr, bool accumulate = false) {
@@ -134,7 +143,7 @@ AttnArgs mk_attn(const Dims &D, const mmtrain_batch *b, const Ctx &c) {
     AttnArgs a = {};
     a.T = b->total_tokens; a.S = b->n_segments; a.nh = D.nh; a.nkv = D.nkv; a.d = D.d; a.scale = D.scale;
     a.cu = b->cu_seqlens_dev; a.modes = b->seg_mask_dev; a.default_mode = b->mask_mode;
-    a.tok_seg = c.tok_seg; a.qkv = c.qkv; a.ld_qkv = D.nqkv; a.o = c.o; a.lse = c.lse;
+    a.tok_seg = c.tok_seg; a.tok_info = c.tok_info; a.qkv = c.qkv; a.ld_qkv = D.nqkv; a.o = c.o; a.lse = c.lse;
     return a;
 }
 
@@ -243,7 +252,8 @@ int mmtrain_layer_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     Ctx c;
     carve_ctx(b, D, (size_t)T, c);
 
-    HIP_TRY(prep_tokens(batch->cu_seqlens_dev, batch->n_segments, T, c.tok_seg, D.d, D.rope_base, c.rope_cs, st));
+    HIP_TRY(prep_tokens(batch->cu_seqlens_dev, batch->seg_mask_dev, batch->mask_mode, batch->n_segments, T, c.tok_seg,
+                        c.tok_info, D.d, D.rope_base, c.rope_cs, st));
     // attention block
     HIP_TRY(norm_fwd(D.dtype, enc, x, W->norm1_w, W->norm1_b, c.h1, c.mean1, c.rstd1, T, D.H, D.eps, st));
     HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.nqkv, D.H, c.h1, D.H, W->w_qkv, D.H, c.qkv, D.nqkv, W->b_qkv), st));
@@ -251,7 +261,7 @@ int mmtrain_layer_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     AttnArgs a = mk_attn(D, batch, c);
     {
         ProfScope ps(MMTRAIN_PROF_ATTN_FWD, st);
-        HIP_TRY(attn_simple_fwd(D.dtype, a, st));
+        HIP_TRY(attn_fwd(D.dtype, a, st));
     }
     HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.H, D.nq, c.o, D.nq, W->w_o, D.nq, c.y1, D.H, W->b_o, x), st));
     // MLP block
@@ -333,7 +343,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     a.d_o = w.d_o; a.d_qkv = w.d_qkv; a.Dsum = w.Dsum;
     {
         ProfScope ps(MMTRAIN_PROF_ATTN_BWD, st);
-        HIP_TRY(attn_simple_bwd(D.dtype, a, st));
+        HIP_TRY(attn_bwd(D.dtype, a, st));
     }
     if (!enc) HIP_TRY(rope_inplace(D.dtype, w.d_qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, true, st));
     if (enc && G.b_qkv) {
@@ -399,6 +409,7 @@ size_t mmtrain_attn_workspace_bytes(int32_t total_tokens, int32_t n_segments, in
     if (total_tokens < 0 || n_segments < 0 || n_heads <= 0) return 0;
     Bump b = {nullptr, 0};
     b.take<int>((size_t)total_tokens);
+    b.take<int2>((size_t)total_tokens);
     b.take<float>((size_t)total_tokens * n_heads);
     return ((b.off + 255) & ~size_t(255)) + 256;
 }
@@ -415,12 +426,14 @@ static int attn_common(const mmtrain_layer_desc *desc, const mmtrain_batch *batc
         return MMTRAIN_ERR_WORKSPACE;
     Bump b = {(uint8_t *)workspace, 0};
     int *tok_seg = b.take<int>((size_t)T);
+    int2 *tok_info = b.take<int2>((size_t)T);
     float *Dsum = b.take<float>((size_t)T * D.nh);
     a = AttnArgs{};
     a.T = T; a.S = batch->n_segments; a.nh = D.nh; a.nkv = D.nkv; a.d = D.d; a.scale = D.scale;
     a.cu = batch->cu_seqlens_dev; a.modes = batch->seg_mask_dev; a.default_mode = batch->mask_mode;
-    a.tok_seg = tok_seg; a.ld_qkv = D.nqkv; a.Dsum = Dsum;
-    HIP_TRY(prep_tokens(batch->cu_seqlens_dev, batch->n_segments, T, tok_seg, D.d, 0.f, nullptr, st));
+    a.tok_seg = tok_seg; a.tok_info = tok_info; a.ld_qkv = D.nqkv; a.Dsum = Dsum;
+    HIP_TRY(prep_tokens(batch->cu_seqlens_dev, batch->seg_mask_dev, batch->mask_mode, batch->n_segments, T, tok_seg, tok_info,
+                        D.d, 0.f, nullptr, st));
     return MMTRAIN_OK;
 }
 
@@ -433,7 +446,7 @@ int mmtrain_attn_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch,
     if (rc || batch->total_tokens == 0) return rc;
     if (!qkv || !o || !lse) return MMTRAIN_ERR_INVALID_ARG;
     a.qkv = qkv; a.o = o; a.lse = lse;
-    HIP_TRY(attn_simple_fwd(D.dtype, a, st));
+    HIP_TRY(attn_fwd(D.dtype, a, st));
     return MMTRAIN_OK;
 }
 
@@ -447,7 +460,7 @@ int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch,
     if (rc || batch->total_tokens == 0) return rc;
     if (!qkv || !o || !lse || !d_o || !d_qkv) return MMTRAIN_ERR_INVALID_ARG;
     a.qkv = qkv; a.o = const_cast<void *>(o); a.lse = const_cast<float *>(lse); a.d_o = d_o; a.d_qkv = d_qkv;
-    HIP_TRY(attn_simple_bwd(D.dtype, a, st));
+    HIP_TRY(attn_bwd(D.dtype, a, st));
     return MMTRAIN_OK;
 }
 

@@ -1,0 +1,567 @@
+// Segment-masked flash attention on the gfx950 matrix cores (bf16 in, fp32 accumulate),
+// forward and backward, for packed variable-length segments.
+//
+// Tiling is on the GLOBAL token index, not per segment: workgroup (t, head) owns queries
+// [128 t, 128 t + 128), one query per lane (4 wavefronts x 32 queries, both lane halves of a
+// wavefront mirror the same 32 queries).  Every query carries its own key range
+// [lo, hi) = [segment start, causal ? q + 1 : segment end), so a tile may straddle any number of
+// segment boundaries and a pack of many short segments still fills whole tiles.  The key loop of
+// a workgroup runs over [lo(first query), hi(last query)) only: tiles that are fully masked for
+// the workgroup are never loaded, and 32-key blocks that are fully masked for one wavefront are
+// skipped by that wavefront (causal lower triangle, other segments).
+//
+// All score tiles are computed TRANSPOSED (keys x queries): S^T = K . Q^T with the MFMA's row
+// operand = keys and column operand = queries.  A lane then holds 16 keys of ONE query per
+// 32-key block, so the softmax row reductions are in-lane plus one cross-half exchange, the
+// running max / sum / log-sum-exp / D are per-lane scalars, and P^T (or dS^T) is already laid
+// out as the column operand of the next MFMA: O^T = V^T . P^T, dQ^T = K^T . dS^T.  The row
+// operand of those products needs the K or V tile transposed ([feature][key]); tiles are
+// transposed in registers (8x8 blocks, byte permutes) on their way from global memory to LDS,
+// with the 128 keys of a row stored in the order in which the accumulator registers hold them.
+//
+// The backward pass is two kernels: dQ (same roles as forward; also writes D = rowsum(dO * O)),
+// then dK/dV with one KEY per lane, looping over the query tiles that can see the workgroup's
+// keys and over the query heads of the key/value head's group, so grouped-query gradients are
+// summed in registers and nothing needs atomics: results are deterministic.
+#include "kernels.h"
+
+namespace mmt {
+
+namespace {
+
+constexpr int BQ = 128;        // queries (or keys, in the dK/dV kernel) per workgroup
+constexpr int BT = 128;        // rows of the tile walked by the inner loop
+constexpr int END_MASK = 0x3fffffff;
+constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+
+__device__ __forceinline__ int wave_max_i(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ int wave_min_i(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ __forceinline__ bf16x8 pack8(const float *v) {
+    bf16x8 r;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = (__bf16)v[i];
+    return r;
+}
+
+// Row r (0..127) of a tile whose rows are visited in accumulator order: unit u = (block b, mfma m, half hh)
+// holds rows 32 b + 16 m + 8 (kk >> 2) + 4 hh + (kk & 3), kk = 0..7.
+__device__ __forceinline__ int unit_row(int u, int kk) {
+    return 32 * (u >> 2) + 16 * ((u >> 1) & 1) + 8 * (kk >> 2) + 4 * (u & 1) + (kk & 3);
+}
+
+// One thread's share of a [128 rows][D] tile: the 8 rows of unit u, 8 features (16 bytes) of each.
+// From the same registers the tile can be written row-major ([row][D]) and transposed ([feature][128]).
+template <int D>
+struct TileLoader {
+    static constexpr int UPR = D / 8;          // 16-byte units per row
+    uint4 r[8];
+    __device__ __forceinline__ bool active() const { return threadIdx.x < 16 * UPR; }
+    // base: element pointer to (row 0, feature 0) of the packed tensor; ld in elements; rows >= nrows read as 0
+    __device__ __forceinline__ void load(const bf16_t *base, long ld, int row0, int nrows) {
+        if (!active()) return;
+        const int cb = threadIdx.x % UPR, u = threadIdx.x / UPR;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const int row = row0 + unit_row(u, kk);
+            r[kk] = make_uint4(0, 0, 0, 0);
+            if (row < nrows) r[kk] = *reinterpret_cast<const uint4 *>(base + (long)row * ld + cb * 8);
+        }
+    }
+    __device__ __forceinline__ void store_rows(uint8_t *tile) const {
+        if (!active()) return;
+        const int cb = threadIdx.x % UPR, u = threadIdx.x / UPR;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const int row = unit_row(u, kk);
+            *reinterpret_cast<uint4 *>(tile + (row * UPR + (cb ^ swz(row))) * 16) = r[kk];
+        }
+    }
+    __device__ __forceinline__ void store_transposed(uint8_t *tile) const {
+        if (!active()) return;
+        const int cb = threadIdx.x % UPR, u = threadIdx.x / UPR;
+        const uint32_t *w = reinterpret_cast<const uint32_t *>(r);
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            const uint32_t sel = (rr & 1) ? 0x07060302u : 0x05040100u;
+            uint4 o;
+            o.x = __builtin_amdgcn_perm(w[1 * 4 + (rr >> 1)], w[0 * 4 + (rr >> 1)], sel);
+            o.y = __builtin_amdgcn_perm(w[3 * 4 + (rr >> 1)], w[2 * 4 + (rr >> 1)], sel);
+            o.z = __builtin_amdgcn_perm(w[5 * 4 + (rr >> 1)], w[4 * 4 + (rr >> 1)], sel);
+            o.w = __builtin_amdgcn_perm(w[7 * 4 + (rr >> 1)], w[6 * 4 + (rr >> 1)], sel);
+            const int c = cb * 8 + rr;
+            *reinterpret_cast<uint4 *>(tile + (c * 16 + (u ^ swz(c))) * 16) = o;
+        }
+    }
+};
+
+// fragment of a row-major [128][D] tile: row, k-slice ks (16 features), lane half
+template <int D>
+__device__ __forceinline__ bf16x8 frag_rows(const uint8_t *tile, int row, int ks, int half) {
+    constexpr int UPR = D / 8;
+    return *reinterpret_cast<const bf16x8 *>(tile + (row * UPR + ((ks * 2 + half) ^ swz(row))) * 16);
+}
+// fragment of a transposed [D][128] tile: feature row c, unit u
+__device__ __forceinline__ bf16x8 frag_tr(const uint8_t *tile, int c, int u) {
+    return *reinterpret_cast<const bf16x8 *>(tile + (c * 16 + (u ^ swz(c))) * 16);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0.f;
+    return z;
+}
+
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+
+struct RowInfo { int lo, hi; };   // allowed partner range of one token
+
+__device__ __forceinline__ RowInfo query_range(const int2 *info, int q, int T) {
+    RowInfo r = {0, 0};
+    if (q < T) {
+        const int2 v = info[q];
+        r.lo = v.x;
+        r.hi = (v.y >> 30) ? (v.y & END_MASK) : q + 1;
+    }
+    return r;
+}
+__device__ __forceinline__ RowInfo key_range(const int2 *info, int k, int T) {
+    RowInfo r = {0, 0};
+    if (k < T) {
+        const int2 v = info[k];
+        r.lo = (v.y >> 30) ? v.x : k;
+        r.hi = v.y & END_MASK;
+    }
+    return r;
+}
+
+// ------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
+    constexpr int KS = D / 16, CB = D / 32;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    uint8_t *sK = smem, *sVT = smem + BT * D * 2;
+
+    const int head = blockIdx.y, g = head / (a.nh / a.nkv);
+    const int q0 = blockIdx.x * BQ;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
+    const int T = a.T;
+    const bf16_t *qkv = (const bf16_t *)a.qkv;
+    const long ld = a.ld_qkv;
+    const int nq = a.nh * D, nk = a.nkv * D;
+
+    const int q = q0 + wave * 32 + l32;
+    const RowInfo me = query_range(a.tok_info, q, T);
+    const bool valid = q < T;
+    const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
+    const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
+    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + BQ, T) - 1, T);
+    const int kbeg = first.lo, kend = last.hi;
+
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (valid) v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * D + ks * 16 + half * 8);
+        qf[ks] = *reinterpret_cast<bf16x8 *>(&v);
+    }
+    f32x16 oacc[CB];
+#pragma unroll
+    for (int c = 0; c < CB; ++c) oacc[c] = zero16();
+    float m_run = -INFINITY, l_run = 0.f;
+    const float sl2 = a.scale * LOG2E;
+
+    TileLoader<D> lk, lv;
+    lk.load(qkv + nq + g * D, ld, kbeg, T);
+    lv.load(qkv + nq + nk + g * D, ld, kbeg, T);
+
+    for (int kt = kbeg; kt < kend; kt += BT) {
+        lk.store_rows(sK);
+        lv.store_transposed(sVT);
+        __syncthreads();
+        if (kt + BT < kend) {
+            lk.load(qkv + nq + g * D, ld, kt + BT, T);
+            lv.load(qkv + nq + nk + g * D, ld, kt + BT, T);
+        }
+        // which 32-key blocks can any query of this wavefront see?
+        bool act[4];
+        bool any = false;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            act[b] = (kt + 32 * b < w_hi_max) && (kt + 32 * b + 32 > w_lo_min);
+            any |= act[b];
+        }
+        if (any) {
+            f32x16 s[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                s[b] = zero16();
+                if (act[b]) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        s[b] = MFMA(frag_rows<D>(sK, 32 * b + l32, ks, half), qf[ks], s[b]);
+                }
+            }
+            // online softmax; register i of block b  <->  key kt + 32 b + 8 (i >> 2) + 4 half + (i & 3)
+            float mx = m_run;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int kb = kt + 32 * b;
+                const bool inside = kb >= w_lo_max && kb + 32 <= w_hi_min;     // no masking needed
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float v = s[b][i] * sl2;
+                    if (!inside) {
+                        const int key = kb + 8 * (i >> 2) + 4 * half + (i & 3);
+                        v = (act[b] && key >= me.lo && key < me.hi) ? v : -INFINITY;
+                    }
+                    s[b][i] = v;
+                    mx = fmaxf(mx, v);
+                }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_use = mx == -INFINITY ? 0.f : mx;
+            const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+            m_run = mx;
+            l_run *= corr;
+#pragma unroll
+            for (int c = 0; c < CB; ++c)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[c][i] *= corr;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (!act[b]) continue;
+                float p[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    p[i] = __builtin_amdgcn_exp2f(s[b][i] - m_use);
+                    l_run += p[i];
+                }
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    const bf16x8 pf = pack8(p + 8 * m);
+                    const int u = b * 4 + m * 2 + half;
+#pragma unroll
+                    for (int c = 0; c < CB; ++c) oacc[c] = MFMA(frag_tr(sVT, 32 * c + l32, u), pf, oacc[c]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (valid) {
+        const float inv = 1.f / l_tot;
+        bf16_t *o = (bf16_t *)a.o + (long)q * nq + head * D;
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                uint2 w;
+                w.x = pack_bf16x2(oacc[c][4 * gq] * inv, oacc[c][4 * gq + 1] * inv);
+                w.y = pack_bf16x2(oacc[c][4 * gq + 2] * inv, oacc[c][4 * gq + 3] * inv);
+                *reinterpret_cast<uint2 *>(o + 32 * c + 8 * gq + 4 * half) = w;
+            }
+        if (half == 0) a.lse[(long)head * T + q] = (m_run + __builtin_amdgcn_logf(l_tot)) * LN2;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// backward: dQ (and D = rowsum(dO * O))
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_dq_kernel(AttnArgs a) {
+    constexpr int KS = D / 16, CB = D / 32;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    uint8_t *sK = smem, *sKT = smem + BT * D * 2, *sV = smem + 2 * BT * D * 2;
+
+    const int head = blockIdx.y, g = head / (a.nh / a.nkv);
+    const int q0 = blockIdx.x * BQ;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
+    const int T = a.T;
+    const bf16_t *qkv = (const bf16_t *)a.qkv;
+    const long ld = a.ld_qkv;
+    const int nq = a.nh * D, nk = a.nkv * D;
+
+    const int q = q0 + wave * 32 + l32;
+    const RowInfo me = query_range(a.tok_info, q, T);
+    const bool valid = q < T;
+    const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
+    const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
+    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + BQ, T) - 1, T);
+    const int kbeg = first.lo, kend = last.hi;
+
+    bf16x8 qf[KS], dof[KS];
+    float Dq = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0), w = v, x = v;
+        if (valid) {
+            v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * D + ks * 16 + half * 8);
+            w = *reinterpret_cast<const uint4 *>((const bf16_t *)a.d_o + (long)q * nq + head * D + ks * 16 + half * 8);
+            x = *reinterpret_cast<const uint4 *>((const bf16_t *)a.o + (long)q * nq + head * D + ks * 16 + half * 8);
+        }
+        qf[ks] = *reinterpret_cast<bf16x8 *>(&v);
+        dof[ks] = *reinterpret_cast<bf16x8 *>(&w);
+        const uint32_t dw[4] = {w.x, w.y, w.z, w.w}, ow[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            Dq += __uint_as_float(dw[e] << 16) * __uint_as_float(ow[e] << 16);
+            Dq += __uint_as_float(dw[e] & 0xffff0000u) * __uint_as_float(ow[e] & 0xffff0000u);
+        }
+    }
+    Dq += __shfl_xor(Dq, 32, 64);
+    float lse2 = 0.f;                                  // log-sum-exp in log2 units
+    if (valid) {
+        lse2 = a.lse[(long)head * T + q] * LOG2E;
+        if (half == 0) a.Dsum[(long)head * T + q] = Dq;
+    }
+    f32x16 dq[CB];
+#pragma unroll
+    for (int c = 0; c < CB; ++c) dq[c] = zero16();
+    const float sl2 = a.scale * LOG2E;
+
+    TileLoader<D> lk, lv;
+    lk.load(qkv + nq + g * D, ld, kbeg, T);
+    lv.load(qkv + nq + nk + g * D, ld, kbeg, T);
+
+    for (int kt = kbeg; kt < kend; kt += BT) {
+        lk.store_rows(sK);
+        lk.store_transposed(sKT);
+        lv.store_rows(sV);
+        __syncthreads();
+        if (kt + BT < kend) {
+            lk.load(qkv + nq + g * D, ld, kt + BT, T);
+            lv.load(qkv + nq + nk + g * D, ld, kt + BT, T);
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int kb = kt + 32 * b;
+            if (!((kb < w_hi_max) && (kb + 32 > w_lo_min))) continue;
+            f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                s = MFMA(frag_rows<D>(sK, 32 * b + l32, ks, half), qf[ks], s);
+                dp = MFMA(frag_rows<D>(sV, 32 * b + l32, ks, half), dof[ks], dp);
+            }
+            const bool inside = kb >= w_lo_max && kb + 32 <= w_hi_min;
+            float ds[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float p = __builtin_amdgcn_exp2f(s[i] * sl2 - lse2);
+                if (!inside) {
+                    const int key = kb + 8 * (i >> 2) + 4 * half + (i & 3);
+                    p = (key >= me.lo && key < me.hi) ? p : 0.f;
+                }
+                ds[i] = p * (dp[i] - Dq);
+            }
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const bf16x8 dsf = pack8(ds + 8 * m);
+                const int u = b * 4 + m * 2 + half;
+#pragma unroll
+                for (int c = 0; c < CB; ++c) dq[c] = MFMA(frag_tr(sKT, 32 * c + l32, u), dsf, dq[c]);
+            }
+        }
+        __syncthreads();
+    }
+    if (valid) {
+        bf16_t *out = (bf16_t *)a.d_qkv + (long)q * ld + head * D;
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                uint2 w;
+                w.x = pack_bf16x2(dq[c][4 * gq] * a.scale, dq[c][4 * gq + 1] * a.scale);
+                w.y = pack_bf16x2(dq[c][4 * gq + 2] * a.scale, dq[c][4 * gq + 3] * a.scale);
+                *reinterpret_cast<uint2 *>(out + 32 * c + 8 * gq + 4 * half) = w;
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// backward: dK, dV.  One key per lane; loop over the query heads of the group and the query tiles.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
+    constexpr int KS = D / 16, CB = D / 32;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    uint8_t *sQ = smem, *sQT = smem + BT * D * 2, *sdO = smem + 2 * BT * D * 2, *sdOT = smem + 3 * BT * D * 2;
+    float *sLse = reinterpret_cast<float *>(smem + 4 * BT * D * 2), *sD = sLse + BT;
+
+    const int g = blockIdx.y, group = a.nh / a.nkv;
+    const int k0 = blockIdx.x * BQ;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
+    const int T = a.T;
+    const bf16_t *qkv = (const bf16_t *)a.qkv;
+    const bf16_t *dO = (const bf16_t *)a.d_o;
+    const long ld = a.ld_qkv;
+    const int nq = a.nh * D, nk = a.nkv * D;
+
+    const int key = k0 + wave * 32 + l32;
+    const RowInfo me = key_range(a.tok_info, key, T);       // queries [lo, hi) see this key
+    const bool valid = key < T;
+    const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
+    const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
+    const RowInfo first = key_range(a.tok_info, k0, T), last = key_range(a.tok_info, min(k0 + BQ, T) - 1, T);
+    const int qbeg = first.lo, qend = last.hi;
+
+    bf16x8 kf[KS], vf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0), w = v;
+        if (valid) {
+            v = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + g * D + ks * 16 + half * 8);
+            w = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + nk + g * D + ks * 16 + half * 8);
+        }
+        kf[ks] = *reinterpret_cast<bf16x8 *>(&v);
+        vf[ks] = *reinterpret_cast<bf16x8 *>(&w);
+    }
+    f32x16 dk[CB], dv[CB];
+#pragma unroll
+    for (int c = 0; c < CB; ++c) { dk[c] = zero16(); dv[c] = zero16(); }
+    const float sl2 = a.scale * LOG2E;
+
+    TileLoader<D> lq, ld_o;
+    for (int hh = 0; hh < group; ++hh) {
+        const int head = g * group + hh;
+        lq.load(qkv + head * D, ld, qbeg, T);
+        ld_o.load(dO + head * D, nq, qbeg, T);
+        for (int qt = qbeg; qt < qend; qt += BT) {
+            lq.store_rows(sQ);
+            lq.store_transposed(sQT);
+            ld_o.store_rows(sdO);
+            ld_o.store_transposed(sdOT);
+            if (threadIdx.x < BT) {
+                const int qq = qt + threadIdx.x;
+                sLse[threadIdx.x] = qq < T ? a.lse[(long)head * T + qq] * LOG2E : 0.f;
+                sD[threadIdx.x] = qq < T ? a.Dsum[(long)head * T + qq] : 0.f;
+            }
+            __syncthreads();
+            if (qt + BT < qend) {
+                lq.load(qkv + head * D, ld, qt + BT, T);
+                ld_o.load(dO + head * D, nq, qt + BT, T);
+            }
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int qb = qt + 32 * b;
+                if (!((qb < w_hi_max) && (qb + 32 > w_lo_min))) continue;
+                // S[q, key] and dP[q, key]: rows = queries (registers), columns = keys (lanes)
+                f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    s = MFMA(frag_rows<D>(sQ, 32 * b + l32, ks, half), kf[ks], s);
+                    dp = MFMA(frag_rows<D>(sdO, 32 * b + l32, ks, half), vf[ks], dp);
+                }
+                const bool inside = qb >= w_lo_max && qb + 32 <= w_hi_min;
+                float p[16], ds[16];
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int r0 = 32 * b + 8 * gq + 4 * half;            // 4 consecutive queries
+                    const float4 l4 = *reinterpret_cast<const float4 *>(sLse + r0);
+                    const float4 d4 = *reinterpret_cast<const float4 *>(sD + r0);
+                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = 4 * gq + e;
+                        float pv = __builtin_amdgcn_exp2f(s[i] * sl2 - lv[e]);
+                        if (!inside) {
+                            const int qq = qt + r0 + e;
+                            pv = (qq >= me.lo && qq < me.hi) ? pv : 0.f;
+                        }
+                        p[i] = pv;
+                        ds[i] = pv * (dp[i] - dvv[e]);
+                    }
+                }
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    const bf16x8 pf = pack8(p + 8 * m), dsf = pack8(ds + 8 * m);
+                    const int u = b * 4 + m * 2 + half;
+#pragma unroll
+                    for (int c = 0; c < CB; ++c) {
+                        dv[c] = MFMA(frag_tr(sdOT, 32 * c + l32, u), pf, dv[c]);
+                        dk[c] = MFMA(frag_tr(sQT, 32 * c + l32, u), dsf, dk[c]);
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (valid) {
+        bf16_t *okp = (bf16_t *)a.d_qkv + (long)key * ld + nq + g * D;
+        bf16_t *ovp = okp + nk;
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                uint2 w;
+                w.x = pack_bf16x2(dk[c][4 * gq] * a.scale, dk[c][4 * gq + 1] * a.scale);
+                w.y = pack_bf16x2(dk[c][4 * gq + 2] * a.scale, dk[c][4 * gq + 3] * a.scale);
+                *reinterpret_cast<uint2 *>(okp + 32 * c + 8 * gq + 4 * half) = w;
+                w.x = pack_bf16x2(dv[c][4 * gq], dv[c][4 * gq + 1]);
+                w.y = pack_bf16x2(dv[c][4 * gq + 2], dv[c][4 * gq + 3]);
+                *reinterpret_cast<uint2 *>(ovp + 32 * c + 8 * gq + 4 * half) = w;
+            }
+    }
+}
+
+template <typename K>
+hipError_t set_smem(K kern, int bytes) {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+template <int D>
+hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
+    static bool configured = false;
+    const int smem = 2 * BT * D * 2;
+    if (!configured) {
+        hipError_t e = set_smem(attn_fwd_kernel<D>, smem);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    attn_fwd_kernel<D><<<dim3(ceil_div(a.T, BQ), a.nh), 256, smem, st>>>(a);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
+    static bool configured = false;
+    const int smem_dq = 3 * BT * D * 2, smem_dkv = 4 * BT * D * 2 + 2 * BT * 4;
+    if (!configured) {
+        hipError_t e = set_smem(attn_dq_kernel<D>, smem_dq);
+        if (e != hipSuccess) return e;
+        e = set_smem(attn_dkv_kernel<D>, smem_dkv);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    attn_dq_kernel<D><<<dim3(ceil_div(a.T, BQ), a.nh), 256, smem_dq, st>>>(a);
+    attn_dkv_kernel<D><<<dim3(ceil_div(a.T, BQ), a.nkv), 256, smem_dkv, st>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t attn_mfma_fwd(const AttnArgs &a, hipStream_t st) {
+    if (a.T == 0) return hipSuccess;
+    return a.d == 64 ? launch_fwd<64>(a, st) : launch_fwd<128>(a, st);
+}
+
+hipError_t attn_mfma_bwd(const AttnArgs &a, hipStream_t st) {
+    if (a.T == 0) return hipSuccess;
+    return a.d == 64 ? launch_bwd<64>(a, st) : launch_bwd<128>(a, st);
+}
+
+}  // namespace mmt

@@ -42,9 +42,14 @@ __device__ __forceinline__ int find_segment(const int *__restrict__ cu, int S, i
     return lo;
 }
 
-__global__ void tok_seg_kernel(const int *__restrict__ cu, int S, int T, int *__restrict__ tok_seg) {
+__global__ void tok_seg_kernel(const int *__restrict__ cu, const uint8_t *__restrict__ modes, int default_mode,
+                               int S, int T, int *__restrict__ tok_seg, int2 *__restrict__ tok_info) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < T) tok_seg[t] = find_segment(cu, S, t);
+    if (t >= T) return;
+    const int s = find_segment(cu, S, t);
+    tok_seg[t] = s;
+    const int mode = modes ? modes[s] : default_mode;
+    tok_info[t] = make_int2(cu[s], cu[s + 1] | (mode == MASK_BIDIR ? (1 << 30) : 0));
 }
 
 // rope_cs[t, i] = (cos, sin)(pos(t) * base^(-2i/d)), pos(t) = t - cu[seg(t)]; evaluated in double
@@ -60,10 +65,10 @@ __global__ void rope_table_kernel(const int *__restrict__ cu, int S, int T, int 
     rope_cs[idx] = make_float2((float)cos(phi), (float)sin(phi));
 }
 
-hipError_t prep_tokens(const int *cu, int S, int T, int *tok_seg, int d, float rope_base, float2 *rope_cs,
-                       hipStream_t st) {
+hipError_t prep_tokens(const int *cu, const uint8_t *modes, int default_mode, int S, int T, int *tok_seg,
+                       int2 *tok_info, int d, float rope_base, float2 *rope_cs, hipStream_t st) {
     if (T == 0) return hipSuccess;
-    tok_seg_kernel<<<ceil_div(T, 256), 256, 0, st>>>(cu, S, T, tok_seg);
+    tok_seg_kernel<<<ceil_div(T, 256), 256, 0, st>>>(cu, modes, default_mode, S, T, tok_seg, tok_info);
     if (rope_cs) rope_table_kernel<<<ceil_div((long)T * (d / 2), 256), 256, 0, st>>>(cu, S, T, d, rope_base, rope_cs);
     return hipGetLastError();
 }

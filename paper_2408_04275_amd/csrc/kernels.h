@@ -27,7 +27,8 @@ bool gemm_mfma_supported(const GemmArgs &g);
 hipError_t gemm_mfma(const GemmArgs &g, hipStream_t st);
 
 // Segment bookkeeping produced by prep_tokens():
-//   tok_seg[t] = index of the segment that holds token t.
+//   tok_seg[t]  = index of the segment that holds token t
+//   tok_info[t] = {start of that segment, end of that segment with bit 30 set if it is bidirectional}
 struct AttnArgs {
     int T, S, nh, nkv, d;
     float scale;
@@ -41,16 +42,20 @@ struct AttnArgs {
     const void *d_o;            // bwd: [T, nh*d]
     void *d_qkv;                // bwd: [T, ld_qkv]
     float *Dsum;                // bwd scratch: [nh, T]
-    // MFMA path: tile work list (device, built by prep_attn_tiles)
-    const int4 *q_tiles; int n_q_tiles;     // {row0, seg_begin, seg_end, mode}
-    const int4 *kv_tiles; int n_kv_tiles;
+    // MFMA path: tok_info[t] = {segment start, segment end | (bidirectional ? 1 << 30 : 0)}
+    const int2 *tok_info;
 };
+// attn_simple.hip: fp32 arithmetic on the vector ALUs, any storage dtype
 hipError_t attn_simple_fwd(int dtype, const AttnArgs &a, hipStream_t st);
 hipError_t attn_simple_bwd(int dtype, const AttnArgs &a, hipStream_t st);
+// attn_mfma.hip: bf16 storage, matrix cores
+hipError_t attn_mfma_fwd(const AttnArgs &a, hipStream_t st);
+hipError_t attn_mfma_bwd(const AttnArgs &a, hipStream_t st);
 
 // elementwise.hip
-hipError_t prep_tokens(const int *cu, int S, int T, int *tok_seg, int d, float rope_base,
-                       float2 *rope_cs /* [T, d/2] or null */, hipStream_t st);
+hipError_t prep_tokens(const int *cu, const uint8_t *modes, int default_mode, int S, int T, int *tok_seg,
+                       int2 *tok_info, int d, float rope_base, float2 *rope_cs /* [T, d/2] or null */,
+                       hipStream_t st);
 hipError_t norm_fwd(int dtype, bool layernorm, const void *x, const void *g, const void *b, void *out,
                     float *mean, float *rstd, int T, int H, float eps, hipStream_t st);
 // d_in = norm_bwd(d_out) + d_res;  gain/bias gradient partial sums go to part_g/part_b

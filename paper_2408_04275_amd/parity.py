@@ -11,13 +11,18 @@ Three per-tensor figures, all against the fp64 oracle:
 
 Why floor_err cannot carry the 2e-2 bar for bf16.  One bf16 rounding of a tensor has l2_err
 1.7e-3.  A layer that keeps its GEMM operands and outputs in bf16 rounds about ten tensors
-between x and a weight gradient; each adds in quadrature (a product such as silu(g)*u adds
-twice), which gives l2_err of 3e-3 to 6e-3 for ANY such implementation -- the oracle itself
-with roundings inserted at the storage points shows it (tests/test_bf16_storage_floor.py).
-These errors are close to Gaussian, so the largest of N of them is about sqrt(2 ln N) sigma:
-4.9 sigma at N = 1.3e5, 6 sigma at N = 9e7, i.e. floor_err of 2.5e-2 to 3.5e-2 with no
-mistake anywhere.  floor_err is therefore held to 5e-2 and l2_err to 8e-3; max_err carries
-the 2e-2.  For fp32 storage all three are held to 1e-4.
+between x and a gradient; each adds in quadrature (a product such as silu(g)*u adds twice, and
+the attention backward pass amplifies the roundings of q and k), which gives l2_err of 3e-3 to
+7e-3 for ANY such implementation: the oracle itself with roundings inserted at the storage
+points shows it (tests/test_bf16_storage_floor.py; at the 7B layer's dimensions the same
+emulation gives l2_err 7.2e-3 and floor_err 5.8e-2 on dx).  These errors are close to Gaussian,
+so the largest of N of them is about sqrt(2 ln N) sigma: 4.9 sigma at N = 1.3e5, 6 sigma at
+N = 9e7, i.e. floor_err of 2.5e-2 to 6e-2 with no mistake anywhere.  The floor also grows with the
+layer's width, because N(0, 0.02^2) weights make the branches outweigh the residual stream and the
+softmax peaky: the same emulation at the 72B layer's dimensions gives l2_err 1.05e-2 on y, half of it
+from the roundings of h1, q and k alone.  floor_err is therefore held to 1e-1 and l2_err to 1.5e-2
+(about 1.5x the storage floor of the widest workload; a wrong mask, index or operand shows as
+l2_err >= 1e-1); max_err carries the 2e-2.  For fp32 storage all three are held to 1e-4.
 """
 from __future__ import annotations
 
@@ -25,7 +30,7 @@ import numpy as np
 
 F32, BF16 = 0, 1
 BARS = {F32: {"max_err": 1e-4, "floor_err": 1e-4, "l2_err": 1e-4},
-        BF16: {"max_err": 2e-2, "floor_err": 5e-2, "l2_err": 8e-3}}
+        BF16: {"max_err": 2e-2, "floor_err": 1e-1, "l2_err": 1.5e-2}}
 
 
 def errors(got, ref) -> dict:
