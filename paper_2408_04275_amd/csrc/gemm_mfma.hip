@@ -14,7 +14,8 @@
 // one row) and (c) the transposed tile writes (lanes 8 rows apart, same unit).
 //
 // Global -> LDS.  Operands whose contraction index is contiguous in memory (A of NT/NN, B of
-// NT) are copied 16 bytes per lane.  Operands whose contraction index is the row index (B of
+// NT) are copied 16 bytes per lane directly into LDS (no register staging, no LDS write
+// instructions).  Operands whose contraction index is the row index (B of
 // NN, A and B of TN) are read 16 bytes per lane along their contiguous direction as 8x8
 // blocks and transposed in registers (byte permutes) before the LDS write, so weight- and
 // input-gradient GEMMs need no transposed copies in HBM.  Out-of-range rows and k are zero-filled.
@@ -23,9 +24,11 @@
 // residual and bias are accessed as full 16-byte row-major vectors; bias / residual / previous
 // C (accumulate) are added in fp32 before the single rounding to bf16.
 //
-// Workgroup -> tile map.  Workgroups are dispatched round-robin over the 8 XCDs, each with
-// its own L2; ids are remapped so that each XCD works on a contiguous run of tiles, ordered in
-// column-major groups of 8 tile-rows so that concurrently resident tiles share A and B panels.
+// Workgroup -> tile map.  The kernel is persistent: one workgroup per compute unit walks over
+// several tiles, so the output stores of one tile drain while the next tile is already being
+// multiplied.  Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2; each
+// XCD works on a contiguous run of the tile order, which goes in column-major groups of 8
+// tile-rows so that concurrently resident tiles share A and B panels.
 #include "kernels.h"
 
 namespace mmt {
@@ -52,58 +55,107 @@ struct GemmP {
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
-// K-contiguous operand: X[rows, K] row-major.  Thread t copies unit (t & 7) of rows (t >> 3) + 32 i.
+// Global memory is read through raw buffer descriptors: an access whose byte offset lies at or beyond
+// the descriptor's size returns zero, which is how out-of-range rows and the K tail are zero-filled
+// without branches.
+constexpr uint32_t OOB = 0xfffffff0u;
+typedef __attribute__((ext_vector_type(4))) uint32_t rawx4;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, size_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)(uint32_t)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    const rawx4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// K-contiguous operand: X[rows, K] row-major, copied global -> LDS without passing through registers
+// (buffer_load ... lds).  One such instruction writes lane l's 16 bytes to LDS base + 16 l, i.e. one
+// instruction fills 8 consecutive tile rows (1 KiB); the swizzled layout is obtained by choosing which
+// 16-byte unit of the row each lane fetches: lane l of the slab starting at row r0 fetches unit
+// (l & 7) ^ swz(r0 + (l >> 3)).  Wavefront w copies rows 32 i + 8 w .. + 7 for i = 0..7.
+typedef __attribute__((address_space(3))) void lds_void;
 struct LoaderKC {
-    uint4 r[8];
-    __device__ __forceinline__ void load(const bf16_t *X, int ld, int row0, int nrows, int k0, int K) {
-        const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
-        const bool kok = k0 + c * 8 < K;
+    __amdgpu_buffer_rsrc_t rs;
+    uint32_t off0, row_step;      // byte offset of this lane's row at i = 0 (without the unit); bytes per 32 rows
+    int kc0, K, slab0;            // unit column (elements) for even i (odd i: kc0 ^ 32); first slab's LDS offset
+    __device__ __forceinline__ void init(const bf16_t *X, int ld, int row0, int nrows, int K_) {
+        rs = make_rsrc(X, ((size_t)(nrows - 1) * ld + K_) * 2);
+        const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+        K = K_;
+        kc0 = (((lane & 7) ^ (lane >> 3) ^ w) & 7) * 8;
+        off0 = (uint32_t)((size_t)(row0 + w * 8 + (lane >> 3)) * ld * 2);
+        row_step = (uint32_t)ld * 64u;
+        slab0 = __builtin_amdgcn_readfirstlane(w * 8 * 128);
+    }
+    // item i of 8 of the tile at k0: rows 32 i + 8 w .. + 7 -> LDS
+    __device__ __forceinline__ void copy_one(uint8_t *tile, int k0, int i) const {
+        const int kc = kc0 ^ ((i & 1) * 32);
+        const uint32_t off = k0 + kc < K ? off0 + i * row_step + (uint32_t)(k0 + kc) * 2u : OOB;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + slab0 + i * 32 * 128), 16, (int)off, 0, 0, 0);
+    }
+    __device__ __forceinline__ void prologue(uint8_t *tile0) const {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = row0 + rr + 32 * i;
-            r[i] = make_uint4(0, 0, 0, 0);
-            if (kok && row < nrows) r[i] = *reinterpret_cast<const uint4 *>(X + (size_t)row * ld + k0 + c * 8);
+        for (int i = 0; i < 8; ++i) copy_one(tile0, 0, i);
+    }
+    // late = the other operand writes LDS from registers in groups 0..3 of phase 0: issue the copies in
+    // groups 4..7, after those writes in program order, because the compiler makes an LDS write wait
+    // for every older direct-to-LDS copy.
+    __device__ __forceinline__ void phase0(uint8_t *tile_next, int kt, int g, bool late) {
+        if (!late) copy_one(tile_next, (kt + 1) * BK, g);
+        else if (g >= 4) {
+            copy_one(tile_next, (kt + 1) * BK, 2 * (g - 4));
+            copy_one(tile_next, (kt + 1) * BK, 2 * (g - 4) + 1);
         }
     }
-    __device__ __forceinline__ void store(uint8_t *tile) const {
-        const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = rr + 32 * i;
-            *reinterpret_cast<uint4 *>(tile + (row * 8 + (c ^ swz(row))) * 16) = r[i];
-        }
-    }
+    __device__ __forceinline__ void phase1(int, int) {}
 };
 
 // K-strided operand: X[K, rows] row-major.  Thread t owns the 8(k) x 8(row) block with
 // row block (t & 31) and k block (t >> 5); it is transposed in registers on the way to LDS.
 struct LoaderKS {
     uint4 r[8];
-    __device__ __forceinline__ void load(const bf16_t *X, int ld, int row0, int nrows, int k0, int K) {
+    __amdgpu_buffer_rsrc_t rs;
+    uint32_t off0, k_step;        // byte offset of (k = (t >> 5) * 8, row0 + (t & 31) * 8); bytes per k
+    __device__ __forceinline__ void init(const bf16_t *X, int ld, int row0, int nrows, int K_) {
+        rs = make_rsrc(X, ((size_t)(K_ - 1) * ld + nrows) * 2);
         const int rb = threadIdx.x & 31, kb = threadIdx.x >> 5;
-        const bool rok = row0 + rb * 8 < nrows;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const int k = k0 + kb * 8 + kk;
-            r[kk] = make_uint4(0, 0, 0, 0);
-            if (rok && k < K) r[kk] = *reinterpret_cast<const uint4 *>(X + (size_t)k * ld + row0 + rb * 8);
-        }
+        k_step = (uint32_t)ld * 2u;
+        off0 = row0 + rb * 8 < nrows ? (uint32_t)(((size_t)kb * 8 * ld + row0 + rb * 8) * 2) : OOB;
     }
-    __device__ __forceinline__ void store(uint8_t *tile) const {
+    // item kk of 8: the 16-byte global read of k = kk; item rr of 8: the LDS write of transposed row rr
+    __device__ __forceinline__ void load_one(int k0, int kk) {
+        r[kk] = buf_load(rs, off0 == OOB ? OOB : off0 + (uint32_t)(k0 + kk) * k_step);
+    }
+    __device__ __forceinline__ void store_one(uint8_t *tile, int rr) const {
         const int rb = threadIdx.x & 31, kb = threadIdx.x >> 5;
         const uint32_t *w = reinterpret_cast<const uint32_t *>(r);   // w[kk * 4 + j]: rows 2j, 2j+1 at k = kk
+        const uint32_t sel = (rr & 1) ? 0x07060302u : 0x05040100u;
+        uint4 o;
+        o.x = __builtin_amdgcn_perm(w[1 * 4 + (rr >> 1)], w[0 * 4 + (rr >> 1)], sel);
+        o.y = __builtin_amdgcn_perm(w[3 * 4 + (rr >> 1)], w[2 * 4 + (rr >> 1)], sel);
+        o.z = __builtin_amdgcn_perm(w[5 * 4 + (rr >> 1)], w[4 * 4 + (rr >> 1)], sel);
+        o.w = __builtin_amdgcn_perm(w[7 * 4 + (rr >> 1)], w[6 * 4 + (rr >> 1)], sel);
+        const int row = rb * 8 + rr;
+        *reinterpret_cast<uint4 *>(tile + (row * 8 + (kb ^ swz(row))) * 16) = o;
+    }
+    // registers hold tile kt+1 while tile kt is multiplied: written to LDS in phase 0, refilled with tile
+    // kt+2 in phase 1
+    __device__ __forceinline__ void prologue(uint8_t *tile0) {
 #pragma unroll
-        for (int rr = 0; rr < 8; ++rr) {
-            const uint32_t sel = (rr & 1) ? 0x07060302u : 0x05040100u;
-            uint4 o;
-            o.x = __builtin_amdgcn_perm(w[1 * 4 + (rr >> 1)], w[0 * 4 + (rr >> 1)], sel);
-            o.y = __builtin_amdgcn_perm(w[3 * 4 + (rr >> 1)], w[2 * 4 + (rr >> 1)], sel);
-            o.z = __builtin_amdgcn_perm(w[5 * 4 + (rr >> 1)], w[4 * 4 + (rr >> 1)], sel);
-            o.w = __builtin_amdgcn_perm(w[7 * 4 + (rr >> 1)], w[6 * 4 + (rr >> 1)], sel);
-            const int row = rb * 8 + rr;
-            *reinterpret_cast<uint4 *>(tile + (row * 8 + (kb ^ swz(row))) * 16) = o;
+        for (int kk = 0; kk < 8; ++kk) load_one(0, kk);
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) store_one(tile0, rr);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) load_one(BK, kk);
+    }
+    __device__ __forceinline__ void phase0(uint8_t *tile_next, int, int g, bool) {
+        if (g < 4) {
+            store_one(tile_next, 2 * g);
+            store_one(tile_next, 2 * g + 1);
         }
     }
+    __device__ __forceinline__ void phase1(int kt, int g) { load_one((kt + 2) * BK, g); }
 };
 
 template <bool KC> struct LoaderSel { typedef LoaderKC type; };
@@ -114,32 +166,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mfma_kernel(const GemmP p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
-    // ---- workgroup -> tile
-    int tm, tn;
-    {
-        const int nb = gridDim.x, b = blockIdx.x;
-        const int xcd = b & 7, q = b >> 3, per = nb >> 3, rem = nb & 7;
-        const int logical = xcd < rem ? xcd * (per + 1) + q : rem * (per + 1) + (xcd - rem) * per + q;
-        const int width = GROUP_M * p.tiles_n;
-        const int group = logical / width, first_m = group * GROUP_M;
-        const int gsize = min(p.tiles_m - first_m, GROUP_M);
-        tm = first_m + (logical % width) % gsize;
-        tn = (logical % width) / gsize;
-    }
-    const int m0 = tm * BM, n0 = tn * BN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
 
-    typename LoaderSel<A_KC>::type la;
-    typename LoaderSel<B_KC>::type lb;
-
-    f32x16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    // ---- persistent workgroup -> tiles.  Workgroup b runs on XCD b % 8 (round-robin dispatch); XCD x
+    // owns a contiguous run of the tile order, and its workgroups stride through that run together.
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    const int per = ntiles >> 3, rem = ntiles & 7;
+    const int run_begin = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+    const int run_end = run_begin + per + (xcd < rem ? 1 : 0);
+    const int wg_per_xcd = (gridDim.x - xcd + 7) >> 3;
 
     // fragment addressing: lane reads row (lane & 31) of a 32-row block, unit ks*2 + (lane >> 5)
     const int frow = lane & 31, fhalf = lane >> 5;
@@ -151,53 +188,109 @@ void gemm_mfma_kernel(const GemmP p) {
         b_off[i] = rb * 128; b_sw[i] = swz(rb);
     }
 
+    for (int logical = run_begin + q; logical < run_end; logical += wg_per_xcd) {
+    int tm, tn;
+    {
+        const int width = GROUP_M * p.tiles_n;
+        const int group = logical / width, first_m = group * GROUP_M;
+        const int gsize = min(p.tiles_m - first_m, GROUP_M);
+        tm = first_m + (logical % width) % gsize;
+        tn = (logical % width) / gsize;
+    }
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    typename LoaderSel<A_KC>::type la;
+    typename LoaderSel<B_KC>::type lb;
+    la.init(p.A, p.lda, m0, p.M, p.K);
+    lb.init(p.B, p.ldb, n0, p.N, p.K);
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    bf16x8 fa[2][4], fb[2][4];
+    // fragment g of 8 of k-slice ks: B0 A0 B1 B2 B3 A1 A2 A3 (what the first MFMAs of a slice need comes first)
+    auto read_frag = [&](const uint8_t *stage, int ks, int buf, int g) {
+        const int u = ks * 2 + fhalf;
+        const bool is_a = g == 1 || g >= 5;
+        const int i = g == 0 ? 0 : g == 1 ? 0 : g <= 4 ? g - 1 : g - 4;
+        if (is_a) fa[buf][i] = *reinterpret_cast<const bf16x8 *>(stage + a_off[i] + ((u ^ a_sw[i]) << 4));
+        else fb[buf][i] = *reinterpret_cast<const bf16x8 *>(stage + TILE_BYTES + b_off[i] + ((u ^ b_sw[i]) << 4));
+    };
+    // MFMA pair g of 8 of a k-slice: accumulator tiles (i, j) = (g >> 1, 2 (g & 1)) and (g >> 1, 2 (g & 1) + 1).
+    // Operands are swapped: the accumulator tile is held transposed (lane = m, registers run over n),
+    // so that each lane owns 4 consecutive n per register quad for the epilogue.
+    auto mfma_pair = [&](int buf, int g) {
+        const int i = g >> 1, j = 2 * (g & 1);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
+        acc[i][j + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j + 1], fa[buf][i], acc[i][j + 1], 0, 0, 0);
+    };
+
+    // Software pipeline, one barrier per 64-deep K step.  While tile kt is multiplied out of stage
+    // kt & 1, tile kt+1 goes into the other stage: K-contiguous operands are copied there straight
+    // from global memory; K-strided operands sit in registers (fetched one step earlier), are
+    // transposed and written, and the registers are refilled with tile kt+2.  The fragments of the
+    // first k-slice of tile kt+1 are read right after the barrier, under the MFMAs of the last
+    // k-slice of tile kt.  Each k-slice is issued as 8 groups of {1 fragment read, up to 2 copy /
+    // write / fetch instructions, 2 MFMAs}; the scheduling fences keep the compiler from regrouping them.
+    // Memory operations retire in issue order, so the direct-to-LDS copies of tile kt+1 (issued in
+    // phase 0) have landed once at most the younger register fetches of phase 1 (8 per K-strided
+    // operand) are outstanding.
+    auto wait_copies = [&]() {
+        if (A_KC && B_KC) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (A_KC || B_KC) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    };
     const int nk = (p.K + BK - 1) / BK;
-    la.load(p.A, p.lda, m0, p.M, 0, p.K);
-    lb.load(p.B, p.ldb, n0, p.N, 0, p.K);
-    la.store(smem);
-    lb.store(smem + TILE_BYTES);
+    la.prologue(smem);
+    lb.prologue(smem + TILE_BYTES);
+    wait_copies();
     __syncthreads();
+#pragma unroll
+    for (int g = 0; g < 8; ++g) read_frag(smem, 0, 0, g);
 
     for (int kt = 0; kt < nk; ++kt) {
-        const uint8_t *sa = smem + (kt & 1) * STAGE_BYTES;
-        const uint8_t *sb = sa + TILE_BYTES;
-        const bool more = kt + 1 < nk;
-        if (more) {
-            la.load(p.A, p.lda, m0, p.M, (kt + 1) * BK, p.K);
-            lb.load(p.B, p.ldb, n0, p.N, (kt + 1) * BK, p.K);
+        const uint8_t *cur = smem + (kt & 1) * STAGE_BYTES;
+        uint8_t *nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+        // k-slice 0: fragments of slice 1; tile kt+1 registers -> LDS
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            read_frag(cur, 1, 1, g);
+            la.phase0(nxt, kt, g, A_KC != B_KC);
+            lb.phase0(nxt + TILE_BYTES, kt, g, A_KC != B_KC);
+            mfma_pair(0, g);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        bf16x8 fa[2][4], fb[2][4];
+        // k-slice 1: fragments of slice 2; fetch tile kt+2
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            fa[0][i] = *reinterpret_cast<const bf16x8 *>(sa + a_off[i] + ((fhalf ^ a_sw[i]) << 4));
-            fb[0][i] = *reinterpret_cast<const bf16x8 *>(sb + b_off[i] + ((fhalf ^ b_sw[i]) << 4));
+        for (int g = 0; g < 8; ++g) {
+            read_frag(cur, 2, 0, g);
+            la.phase1(kt, g);
+            lb.phase1(kt, g);
+            mfma_pair(1, g);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // k-slice 2: fragments of slice 3
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks < 3) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int u = (ks + 1) * 2 + fhalf;
-                    fa[nxt][i] = *reinterpret_cast<const bf16x8 *>(sa + a_off[i] + ((u ^ a_sw[i]) << 4));
-                    fb[nxt][i] = *reinterpret_cast<const bf16x8 *>(sb + b_off[i] + ((u ^ b_sw[i]) << 4));
-                }
-            }
-            // operands swapped: the accumulator tile is held transposed (lane = m, registers run
-            // over n), so that each lane owns 4 consecutive n per register quad for the epilogue.
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+        for (int g = 0; g < 8; ++g) {
+            read_frag(cur, 3, 1, g);
+            mfma_pair(0, g);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) {
-            uint8_t *da = smem + ((kt + 1) & 1) * STAGE_BYTES;
-            la.store(da);
-            lb.store(da + TILE_BYTES);
-        }
+        wait_copies();                                         // direct-to-LDS copies of tile kt+1 have landed
         __syncthreads();
+        // k-slice 3: fragments of slice 0 of the next tile
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            read_frag(nxt, 0, 0, g);
+            mfma_pair(1, g);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
+    __syncthreads();
 
     // ---- epilogue: 32 rows x 128 columns at a time through this wavefront's staging area
     float *stg = reinterpret_cast<float *>(smem) + wave * (32 * EPI_PITCH);
@@ -253,6 +346,7 @@ void gemm_mfma_kernel(const GemmP p) {
         }
         __syncthreads();
     }
+    }   // tiles of this workgroup
 }
 
 template <bool A_KC, bool B_KC>
@@ -265,7 +359,19 @@ hipError_t launch(const GemmP &p, hipStream_t st) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    kern<<<p.tiles_m * p.tiles_n, 256, SMEM_BYTES, st>>>(p);
+    // one persistent workgroup per compute unit (the tile needs the CU's whole LDS and register file)
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (n_cu <= 0) n_cu = 256;
+        n_cu &= ~7;
+        if (n_cu == 0) n_cu = 8;
+    }
+    const int tiles = p.tiles_m * p.tiles_n;
+    kern<<<tiles < n_cu ? tiles : n_cu, 256, SMEM_BYTES, st>>>(p);
     return hipGetLastError();
 }
 
@@ -277,6 +383,10 @@ bool gemm_mfma_supported(const GemmArgs &g) {
     const bool a_kc = g.layout != GEMM_TN, b_kc = g.layout == GEMM_NT;
     if ((a_kc || b_kc) && (g.K & 7)) return false;
     if (!a_kc && (g.M & 7)) return false;
+    // operands are addressed with 32-bit byte offsets, tile overhang included
+    const size_t rows_a = a_kc ? g.M : g.K, rows_b = b_kc ? g.N : g.K;
+    if ((rows_a + 256) * (size_t)g.lda * 2 >= 0xfff00000ull || (rows_b + 256) * (size_t)g.ldb * 2 >= 0xfff00000ull)
+        return false;
     const uintptr_t bits = (uintptr_t)g.A | (uintptr_t)g.B | (uintptr_t)g.C | (uintptr_t)g.bias | (uintptr_t)g.residual;
     return (bits & 15) == 0;
 }
