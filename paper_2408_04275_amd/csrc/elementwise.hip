@@ -214,22 +214,31 @@ hipError_t norm_bwd(int dtype, bool layernorm, const void *d_out, const void *x,
 }
 
 // ---- partial-sum reduction -----------------------------------------------------------
+// 32 columns per workgroup; 8 row lanes per column walk the partial rows, then combine through LDS.
 template <typename T>
-__global__ void reduce_partials_kernel(const float *__restrict__ part, int rows, int N, T *__restrict__ out,
-                                       bool accumulate) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= N) return;
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int rows, int N,
+                                                              T *__restrict__ out, bool accumulate) {
+    __shared__ float red[8][33];
+    const int c = blockIdx.x * 32 + (threadIdx.x & 31), rl = threadIdx.x >> 5;
     float s = 0.f;
-    for (int r = 0; r < rows; ++r) s += part[(size_t)r * N + c];
-    if (accumulate) s += Elem<T>::load(out + c);
-    Elem<T>::store(out + c, s);
+    if (c < N)
+        for (int r = rl; r < rows; r += 8) s += part[(size_t)r * N + c];
+    red[rl][threadIdx.x & 31] = s;
+    __syncthreads();
+    if (rl == 0 && c < N) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t += red[i][threadIdx.x];
+        if (accumulate) t += Elem<T>::load(out + c);
+        Elem<T>::store(out + c, t);
+    }
 }
 
 hipError_t reduce_partials(int dtype, const float *part, int rows, int N, void *out, bool accumulate,
                            hipStream_t st) {
     if (N == 0) return hipSuccess;
-    if (dtype == DT_F32) reduce_partials_kernel<float><<<ceil_div(N, 64), 64, 0, st>>>(part, rows, N, (float *)out, accumulate);
-    else reduce_partials_kernel<bf16_t><<<ceil_div(N, 64), 64, 0, st>>>(part, rows, N, (bf16_t *)out, accumulate);
+    if (dtype == DT_F32) reduce_partials_kernel<float><<<ceil_div(N, 32), 256, 0, st>>>(part, rows, N, (float *)out, accumulate);
+    else reduce_partials_kernel<bf16_t><<<ceil_div(N, 32), 256, 0, st>>>(part, rows, N, (bf16_t *)out, accumulate);
     return hipGetLastError();
 }
 

@@ -94,21 +94,24 @@ struct LoaderKC {
         const uint32_t off = k0 + kc < K ? off0 + i * row_step + (uint32_t)(k0 + kc) * 2u : OOB;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + slab0 + i * 32 * 128), 16, (int)off, 0, 0, 0);
     }
-    __device__ __forceinline__ void prologue(uint8_t *tile0) const {
+    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) copy_one(tile0, 0, i);
+        for (int i = 0; i < 8; ++i) copy_one(slot0, 0, i);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) copy_one(slot1, BK, i);
     }
-    // late = the other operand writes LDS from registers in groups 0..3 of phase 0: issue the copies in
-    // groups 4..7, after those writes in program order, because the compiler makes an LDS write wait
-    // for every older direct-to-LDS copy.
-    __device__ __forceinline__ void phase0(uint8_t *tile_next, int kt, int g, bool late) {
-        if (!late) copy_one(tile_next, (kt + 1) * BK, g);
+    __device__ __forceinline__ void fetch(int, int) {}
+    // group g of 8 of the hand-over phase: copy K tile kt+2 into the slot that has just been released.
+    // mixed = the other operand writes LDS from registers in groups 0..3: the copies then go to groups
+    // 4..7, after those writes in program order, because the compiler makes an LDS write wait for every
+    // older direct-to-LDS copy.
+    __device__ __forceinline__ void issue(uint8_t *slot, int kt, int g, bool mixed) {
+        if (!mixed) copy_one(slot, (kt + 2) * BK, g);
         else if (g >= 4) {
-            copy_one(tile_next, (kt + 1) * BK, 2 * (g - 4));
-            copy_one(tile_next, (kt + 1) * BK, 2 * (g - 4) + 1);
+            copy_one(slot, (kt + 2) * BK, 2 * (g - 4));
+            copy_one(slot, (kt + 2) * BK, 2 * (g - 4) + 1);
         }
     }
-    __device__ __forceinline__ void phase1(int, int) {}
 };
 
 // K-strided operand: X[K, rows] row-major.  Thread t owns the 8(k) x 8(row) block with
@@ -139,29 +142,44 @@ struct LoaderKS {
         const int row = rb * 8 + rr;
         *reinterpret_cast<uint4 *>(tile + (row * 8 + (kb ^ swz(row))) * 16) = o;
     }
-    // registers hold tile kt+1 while tile kt is multiplied: written to LDS in phase 0, refilled with tile
-    // kt+2 in phase 1
-    __device__ __forceinline__ void prologue(uint8_t *tile0) {
+    // The registers are filled with K tile kt+2 in the first phase of step kt and written to LDS in its
+    // last phase, when the slot of tile kt has been released.
+    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1) {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) load_one(0, kk);
 #pragma unroll
-        for (int rr = 0; rr < 8; ++rr) store_one(tile0, rr);
+        for (int rr = 0; rr < 8; ++rr) store_one(slot0, rr);
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) load_one(BK, kk);
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) store_one(slot1, rr);
     }
-    __device__ __forceinline__ void phase0(uint8_t *tile_next, int, int g, bool) {
-        if (g < 4) {
-            store_one(tile_next, 2 * g);
-            store_one(tile_next, 2 * g + 1);
+    __device__ __forceinline__ void fetch(int kt, int g) { load_one((kt + 2) * BK, g); }
+    __device__ __forceinline__ void issue(uint8_t *slot, int, int g, bool mixed) {
+        if (!mixed) store_one(slot, g);
+        else if (g < 4) {
+            store_one(slot, 2 * g);
+            store_one(slot, 2 * g + 1);
         }
     }
-    __device__ __forceinline__ void phase1(int kt, int g) { load_one((kt + 2) * BK, g); }
 };
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
+// global store to be acknowledged (its release fence), which would expose the latency of the output
+// stores at each barrier; here only LDS operations (lgkmcnt) are waited for.  Direct-to-LDS copies are
+// tracked by vmcnt and waited for separately where a stage is handed over.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+// Orders this wavefront's own LDS writes before its later LDS reads (other lanes' data, same wavefront).
+__device__ __forceinline__ void lds_wave_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 template <bool KC> struct LoaderSel { typedef LoaderKC type; };
 template <> struct LoaderSel<false> { typedef LoaderKS type; };
 
-template <bool A_KC, bool B_KC>
+template <bool A_KC, bool B_KC, bool HAS_ADD>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mfma_kernel(const GemmP p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -230,46 +248,48 @@ void gemm_mfma_kernel(const GemmP p) {
         acc[i][j + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j + 1], fa[buf][i], acc[i][j + 1], 0, 0, 0);
     };
 
-    // Software pipeline, one barrier per 64-deep K step.  While tile kt is multiplied out of stage
-    // kt & 1, tile kt+1 goes into the other stage: K-contiguous operands are copied there straight
-    // from global memory; K-strided operands sit in registers (fetched one step earlier), are
-    // transposed and written, and the registers are refilled with tile kt+2.  The fragments of the
-    // first k-slice of tile kt+1 are read right after the barrier, under the MFMAs of the last
-    // k-slice of tile kt.  Each k-slice is issued as 8 groups of {1 fragment read, up to 2 copy /
-    // write / fetch instructions, 2 MFMAs}; the scheduling fences keep the compiler from regrouping them.
-    // Memory operations retire in issue order, so the direct-to-LDS copies of tile kt+1 (issued in
-    // phase 0) have landed once at most the younger register fetches of phase 1 (8 per K-strided
-    // operand) are outstanding.
+    // Software pipeline, one barrier per 64-deep K step, two LDS slots.  Step kt multiplies K tile kt out
+    // of slot kt & 1 in four k-slices; the fragments of a slice are read one slice ahead.  After the third
+    // slice every wavefront has read all of slot kt & 1, so past the barrier the slot is handed over: in
+    // the fourth phase K tile kt+2 is put there -- K-contiguous operands are copied straight from global
+    // memory, K-strided operands come transposed from registers that were filled in the first phase --
+    // while the first fragments of tile kt+1 are read from the other slot.  A copy thus has a whole step to
+    // land and the memory pipe always has the next tile in flight.  Each phase is issued as 8 groups of
+    // {1 fragment read, up to 2 copy / write / fetch instructions, 2 MFMAs}; the scheduling fences keep the
+    // compiler from regrouping them.
+    //
+    // Memory operations retire in issue order, so the direct-to-LDS copies of tile kt+1 (issued in the last
+    // phase of step kt-1) have landed once at most the younger register fetches of this step's first phase
+    // (8 per K-strided operand) are outstanding.
     auto wait_copies = [&]() {
         if (A_KC && B_KC) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         else if (A_KC || B_KC) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     };
+    constexpr bool MIXED = A_KC != B_KC;
     const int nk = (p.K + BK - 1) / BK;
-    la.prologue(smem);
-    lb.prologue(smem + TILE_BYTES);
-    wait_copies();
-    __syncthreads();
+    la.prologue(smem, smem + STAGE_BYTES);
+    lb.prologue(smem + TILE_BYTES, smem + STAGE_BYTES + TILE_BYTES);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
 #pragma unroll
     for (int g = 0; g < 8; ++g) read_frag(smem, 0, 0, g);
 
     for (int kt = 0; kt < nk; ++kt) {
-        const uint8_t *cur = smem + (kt & 1) * STAGE_BYTES;
-        uint8_t *nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-        // k-slice 0: fragments of slice 1; tile kt+1 registers -> LDS
+        uint8_t *cur = smem + (kt & 1) * STAGE_BYTES;
+        const uint8_t *nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+        // k-slice 0: fragments of slice 1; K-strided operands fetch tile kt+2 into registers
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             read_frag(cur, 1, 1, g);
-            la.phase0(nxt, kt, g, A_KC != B_KC);
-            lb.phase0(nxt + TILE_BYTES, kt, g, A_KC != B_KC);
+            la.fetch(kt, g);
+            lb.fetch(kt, g);
             mfma_pair(0, g);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // k-slice 1: fragments of slice 2; fetch tile kt+2
+        // k-slice 1: fragments of slice 2
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             read_frag(cur, 2, 0, g);
-            la.phase1(kt, g);
-            lb.phase1(kt, g);
             mfma_pair(1, g);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -280,19 +300,23 @@ void gemm_mfma_kernel(const GemmP p) {
             mfma_pair(0, g);
             __builtin_amdgcn_sched_barrier(0);
         }
-        wait_copies();                                         // direct-to-LDS copies of tile kt+1 have landed
-        __syncthreads();
-        // k-slice 3: fragments of slice 0 of the next tile
+        wait_copies();                                         // tile kt+1 has landed in the other slot
+        lds_barrier();                                         // and nobody reads this slot any more
+        // k-slice 3: fragments of slice 0 of tile kt+1; tile kt+2 goes into the released slot
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             read_frag(nxt, 0, 0, g);
+            la.issue(cur, kt, g, MIXED);
+            lb.issue(cur + TILE_BYTES, kt, g, MIXED);
             mfma_pair(1, g);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // copies past the end of K (zero-filled) are done
+    lds_barrier();
 
-    // ---- epilogue: 32 rows x 128 columns at a time through this wavefront's staging area
+    // ---- epilogue: 32 rows x 128 columns at a time through this wavefront's own staging area; the output
+    // stores are left in flight (nothing below waits for them) and drain under the next tile's K loop
     float *stg = reinterpret_cast<float *>(smem) + wave * (32 * EPI_PITCH);
     const int er = lane >> 4, ec = (lane & 15) * 8;      // read-back: row er + 4*pass, columns ec..ec+7
     const int gn = n0 + wn * 128 + ec;
@@ -304,6 +328,22 @@ void gemm_mfma_kernel(const GemmP p) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) { bv[2 * e] = __uint_as_float(w[e] << 16); bv[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u); }
     }
+    // Everything that is added to the product (residual, previous C) is fetched before the first output
+    // store is issued: memory operations retire in order, so a load issued after a store would have to
+    // wait for that store to be acknowledged.
+    const bf16_t *addend = p.residual ? p.residual : p.C;      // HAS_ADD: residual and / or accumulate
+    uint4 add[HAS_ADD ? 4 : 1][8];
+    if (HAS_ADD) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass) {
+                const int gm = m0 + wm * 128 + i * 32 + pass * 4 + er;
+                add[i][pass] = make_uint4(0, 0, 0, 0);
+                if (gm < p.M && nok) add[i][pass] = *reinterpret_cast<const uint4 *>(addend + (size_t)gm * p.ldc + gn);
+            }
+    }
+    const bool both = HAS_ADD && p.residual && p.accumulate;   // rare: the second addend is read in the store loop
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -314,7 +354,7 @@ void gemm_mfma_kernel(const GemmP p) {
                 float4 v = make_float4(acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]);
                 *reinterpret_cast<float4 *>(stg + frow * EPI_PITCH + j * 32 + gq * 8 + fhalf * 4) = v;
             }
-        __syncthreads();
+        lds_wave_sync();
 #pragma unroll
         for (int pass = 0; pass < 8; ++pass) {
             const int r = pass * 4 + er;
@@ -326,13 +366,12 @@ void gemm_mfma_kernel(const GemmP p) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] += bv[e];
                 const size_t off = (size_t)gm * p.ldc + gn;
-                if (p.residual) {
-                    const uint4 raw = *reinterpret_cast<const uint4 *>(p.residual + off);
-                    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+                if (HAS_ADD) {
+                    const uint32_t w[4] = {add[i][pass].x, add[i][pass].y, add[i][pass].z, add[i][pass].w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(w[e] << 16); v[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u); }
                 }
-                if (p.accumulate) {
+                if (both) {
                     const uint4 raw = *reinterpret_cast<const uint4 *>(p.C + off);
                     const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
@@ -344,15 +383,16 @@ void gemm_mfma_kernel(const GemmP p) {
                 *reinterpret_cast<uint4 *>(p.C + off) = o;
             }
         }
-        __syncthreads();
+        lds_wave_sync();
     }
+    lds_barrier();      // staging area is free again: the next tile's first stage may overwrite it
     }   // tiles of this workgroup
 }
 
-template <bool A_KC, bool B_KC>
+template <bool A_KC, bool B_KC, bool HAS_ADD>
 hipError_t launch(const GemmP &p, hipStream_t st) {
     static bool configured = false;
-    auto kern = gemm_mfma_kernel<A_KC, B_KC>;
+    auto kern = gemm_mfma_kernel<A_KC, B_KC, HAS_ADD>;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
@@ -402,10 +442,11 @@ hipError_t gemm_mfma(const GemmArgs &g, hipStream_t st) {
     p.accumulate = g.accumulate ? 1 : 0;
     p.tiles_m = ceil_div(g.M, BM);
     p.tiles_n = ceil_div(g.N, BN);
+    const bool add = p.residual || p.accumulate;
     switch (g.layout) {
-        case GEMM_NT: return launch<true, true>(p, st);
-        case GEMM_NN: return launch<true, false>(p, st);
-        default: return launch<false, false>(p, st);
+        case GEMM_NT: return add ? launch<true, true, true>(p, st) : launch<true, true, false>(p, st);
+        case GEMM_NN: return add ? launch<true, false, true>(p, st) : launch<true, false, false>(p, st);
+        default: return add ? launch<false, false, true>(p, st) : launch<false, false, false>(p, st);
     }
 }
 
