@@ -215,39 +215,42 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
                         s[b] = MFMA(frag_rows<D>(sK, 32 * b + l32, ks, half), qf[ks], s[b]);
                 }
             }
-            // online softmax; register i of block b  <->  key kt + 32 b + 8 (i >> 2) + 4 half + (i & 3)
+            // online softmax on the raw scores (the scale is folded into the exponent);
+            // register i of block b  <->  key kt + 32 b + 8 (i >> 2) + 4 half + (i & 3)
             float mx = m_run;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
+                if (!act[b]) continue;
                 const int kb = kt + 32 * b;
-                const bool inside = kb >= w_lo_max && kb + 32 <= w_hi_min;     // no masking needed
+                if (!(kb >= w_lo_max && kb + 32 <= w_hi_min)) {            // some lane needs masking
+                    const unsigned span = (unsigned)(me.hi - me.lo);
+                    const int rel = kb + 4 * half - me.lo;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float v = s[b][i] * sl2;
-                    if (!inside) {
-                        const int key = kb + 8 * (i >> 2) + 4 * half + (i & 3);
-                        v = (act[b] && key >= me.lo && key < me.hi) ? v : -INFINITY;
-                    }
-                    s[b][i] = v;
-                    mx = fmaxf(mx, v);
+                    for (int i = 0; i < 16; ++i)
+                        s[b][i] = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? s[b][i] : -INFINITY;
                 }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[b][i]);
             }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_use = mx == -INFINITY ? 0.f : mx;
-            const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+            if (__builtin_amdgcn_ballot_w64(mx != m_run) != 0) {           // some lane's maximum moved
+                const float corr = __builtin_amdgcn_exp2f((m_run - m_use) * sl2);
+                l_run *= corr;
+#pragma unroll
+                for (int c = 0; c < CB; ++c)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[c][i] *= corr;
+            }
             m_run = mx;
-            l_run *= corr;
-#pragma unroll
-            for (int c = 0; c < CB; ++c)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[c][i] *= corr;
+            const float msc = m_use * sl2;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 if (!act[b]) continue;
                 float p[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    p[i] = __builtin_amdgcn_exp2f(s[b][i] - m_use);
+                    p[i] = __builtin_amdgcn_exp2f(fmaf(s[b][i], sl2, -msc));
                     l_run += p[i];
                 }
 #pragma unroll
@@ -275,7 +278,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
                 w.y = pack_bf16x2(oacc[c][4 * gq + 2] * inv, oacc[c][4 * gq + 3] * inv);
                 *reinterpret_cast<uint2 *>(o + 32 * c + 8 * gq + 4 * half) = w;
             }
-        if (half == 0) a.lse[(long)head * T + q] = (m_run + __builtin_amdgcn_logf(l_tot)) * LN2;
+        if (half == 0) a.lse[(long)head * T + q] = (m_run * sl2 + __builtin_amdgcn_logf(l_tot)) * LN2;
     }
 }
 
@@ -358,14 +361,13 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(AttnArgs a) {
                 dp = MFMA(frag_rows<D>(sV, 32 * b + l32, ks, half), dof[ks], dp);
             }
             const bool inside = kb >= w_lo_max && kb + 32 <= w_hi_min;
+            const unsigned span = (unsigned)(me.hi - me.lo);
+            const int rel = kb + 4 * half - me.lo;
             float ds[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                float p = __builtin_amdgcn_exp2f(s[i] * sl2 - lse2);
-                if (!inside) {
-                    const int key = kb + 8 * (i >> 2) + 4 * half + (i & 3);
-                    p = (key >= me.lo && key < me.hi) ? p : 0.f;
-                }
+                float p = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lse2));
+                if (!inside) p = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? p : 0.f;
                 ds[i] = p * (dp[i] - Dq);
             }
 #pragma unroll
@@ -467,6 +469,7 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
                     dp = MFMA(frag_rows<D>(sdO, 32 * b + l32, ks, half), vf[ks], dp);
                 }
                 const bool inside = qb >= w_lo_max && qb + 32 <= w_hi_min;
+                const unsigned span = (unsigned)(me.hi - me.lo);
                 float p[16], ds[16];
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
@@ -477,11 +480,8 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int i = 4 * gq + e;
-                        float pv = __builtin_amdgcn_exp2f(s[i] * sl2 - lv[e]);
-                        if (!inside) {
-                            const int qq = qt + r0 + e;
-                            pv = (qq >= me.lo && qq < me.hi) ? pv : 0.f;
-                        }
+                        float pv = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lv[e]));
+                        if (!inside) pv = (unsigned)(qt + r0 + e - me.lo) < span ? pv : 0.f;
                         p[i] = pv;
                         ds[i] = pv * (dp[i] - dvv[e]);
                     }
