@@ -94,23 +94,15 @@ struct LoaderKC {
         const uint32_t off = k0 + kc < K ? off0 + i * row_step + (uint32_t)(k0 + kc) * 2u : OOB;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + slab0 + i * 32 * 128), 16, (int)off, 0, 0, 0);
     }
-    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1) {
+    __device__ __forceinline__ void load_one(int, int) {}
+    __device__ __forceinline__ void store_one(uint8_t *, int) const {}
+    // tile 0 completely, and the items of tile 1 that the K loop does not copy itself (first = how many)
+    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1, int first) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) copy_one(slot0, 0, i);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) copy_one(slot1, BK, i);
-    }
-    __device__ __forceinline__ void fetch(int, int) {}
-    // group g of 8 of the hand-over phase: copy K tile kt+2 into the slot that has just been released.
-    // mixed = the other operand writes LDS from registers in groups 0..3: the copies then go to groups
-    // 4..7, after those writes in program order, because the compiler makes an LDS write wait for every
-    // older direct-to-LDS copy.
-    __device__ __forceinline__ void issue(uint8_t *slot, int kt, int g, bool mixed) {
-        if (!mixed) copy_one(slot, (kt + 2) * BK, g);
-        else if (g >= 4) {
-            copy_one(slot, (kt + 2) * BK, 2 * (g - 4));
-            copy_one(slot, (kt + 2) * BK, 2 * (g - 4) + 1);
-        }
+        for (int i = 0; i < 8; ++i)
+            if (i < first) copy_one(slot1, BK, i);
     }
 };
 
@@ -142,9 +134,9 @@ struct LoaderKS {
         const int row = rb * 8 + rr;
         *reinterpret_cast<uint4 *>(tile + (row * 8 + (kb ^ swz(row))) * 16) = o;
     }
-    // The registers are filled with K tile kt+2 in the first phase of step kt and written to LDS in its
-    // last phase, when the slot of tile kt has been released.
-    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1) {
+    // The registers are filled with K tile kt+2 during the first two phases of step kt and written to LDS
+    // in its last phase, when the slot of tile kt has been released.
+    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1, int) {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) load_one(0, kk);
 #pragma unroll
@@ -154,14 +146,8 @@ struct LoaderKS {
 #pragma unroll
         for (int rr = 0; rr < 8; ++rr) store_one(slot1, rr);
     }
-    __device__ __forceinline__ void fetch(int kt, int g) { load_one((kt + 2) * BK, g); }
-    __device__ __forceinline__ void issue(uint8_t *slot, int, int g, bool mixed) {
-        if (!mixed) store_one(slot, g);
-        else if (g < 4) {
-            store_one(slot, 2 * g);
-            store_one(slot, 2 * g + 1);
-        }
-    }
+    // uniform names so that the K loop can be written once
+    __device__ __forceinline__ void copy_one(uint8_t *, int, int) const {}
 };
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
@@ -249,26 +235,30 @@ void gemm_mfma_kernel(const GemmP p) {
     };
 
     // Software pipeline, one barrier per 64-deep K step, two LDS slots.  Step kt multiplies K tile kt out
-    // of slot kt & 1 in four k-slices; the fragments of a slice are read one slice ahead.  After the third
-    // slice every wavefront has read all of slot kt & 1, so past the barrier the slot is handed over: in
-    // the fourth phase K tile kt+2 is put there -- K-contiguous operands are copied straight from global
-    // memory, K-strided operands come transposed from registers that were filled in the first phase --
-    // while the first fragments of tile kt+1 are read from the other slot.  A copy thus has a whole step to
-    // land and the memory pipe always has the next tile in flight.  Each phase is issued as 8 groups of
-    // {1 fragment read, up to 2 copy / write / fetch instructions, 2 MFMAs}; the scheduling fences keep the
-    // compiler from regrouping them.
+    // of slot kt & 1 in four k-slices (phases); the fragments of a slice are read one slice ahead.  After
+    // the third slice every wavefront has read all of slot kt & 1, so past the barrier the slot is handed
+    // over to K tile kt+2.
     //
-    // Memory operations retire in issue order, so the direct-to-LDS copies of tile kt+1 (issued in the last
-    // phase of step kt-1) have landed once at most the younger register fetches of this step's first phase
-    // (8 per K-strided operand) are outstanding.
+    // Feeding is spread out in time, because the CU's address/data path takes about 16 cycles per 1 KiB
+    // wavefront access and an access that finds it busy blocks the MFMAs queued behind it:
+    //   K-contiguous operands (direct global -> LDS copies, 8 per operand and tile): 3 in the hand-over
+    //     phase, 3 and 2 in the first two phases of the next step; all must have landed at that step's
+    //     barrier (vmcnt).
+    //   K-strided operands (registers): 4 + 4 global fetches of tile kt+2 in the first two phases of step
+    //     kt, 8 transposing LDS writes in the hand-over phase.
+    // When both kinds are present the LDS writes come first in the hand-over phase: the compiler makes an
+    // LDS write wait for every older direct-to-LDS copy.  Each phase is issued as 8 groups of {1 fragment
+    // read, feed instructions, 2 MFMAs}; the scheduling fences keep the compiler from regrouping them.
+    constexpr bool NT_ = A_KC && B_KC, NN_ = A_KC && !B_KC;
+    // Memory operations retire in issue order: at the barrier the copies of tile kt+1 have landed once at
+    // most the register fetches issued after the last copy (3 in the mixed case) are outstanding.
     auto wait_copies = [&]() {
-        if (A_KC && B_KC) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else if (A_KC || B_KC) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if (NT_) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (NN_) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
     };
-    constexpr bool MIXED = A_KC != B_KC;
     const int nk = (p.K + BK - 1) / BK;
-    la.prologue(smem, smem + STAGE_BYTES);
-    lb.prologue(smem + TILE_BYTES, smem + STAGE_BYTES + TILE_BYTES);
+    la.prologue(smem, smem + STAGE_BYTES, NT_ ? 3 : 2);
+    lb.prologue(smem + TILE_BYTES, smem + STAGE_BYTES + TILE_BYTES, 3);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();
 #pragma unroll
@@ -276,24 +266,38 @@ void gemm_mfma_kernel(const GemmP p) {
 
     for (int kt = 0; kt < nk; ++kt) {
         uint8_t *cur = smem + (kt & 1) * STAGE_BYTES;
-        const uint8_t *nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-        // k-slice 0: fragments of slice 1; K-strided operands fetch tile kt+2 into registers
+        uint8_t *nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+        const int k1 = (kt + 1) * BK, k2 = (kt + 2) * BK;
+        // phase 0: fragments of slice 1; more of tile kt+1 into the other slot; register fetches of tile kt+2
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             read_frag(cur, 1, 1, g);
-            la.fetch(kt, g);
-            lb.fetch(kt, g);
+            if (NT_) {
+                if (g < 6) { if (g & 1) lb.copy_one(nxt + TILE_BYTES, k1, 3 + (g >> 1)); else la.copy_one(nxt, k1, 3 + (g >> 1)); }
+            } else if (NN_) {
+                if (g < 4) { la.copy_one(nxt, k1, 2 + g); lb.load_one(k2, g); }
+            } else {
+                if (g < 4) { la.load_one(k2, g); lb.load_one(k2, g); }
+            }
             mfma_pair(0, g);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // k-slice 1: fragments of slice 2
+        // phase 1: fragments of slice 2; the rest of tile kt+1; the rest of the register fetches
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             read_frag(cur, 2, 0, g);
+            if (NT_) {
+                if (g < 4) { if (g & 1) lb.copy_one(nxt + TILE_BYTES, k1, 6 + (g >> 1)); else la.copy_one(nxt, k1, 6 + (g >> 1)); }
+            } else if (NN_) {
+                if (g < 2) la.copy_one(nxt, k1, 6 + g);
+                if (g < 4) lb.load_one(k2, 4 + g);
+            } else {
+                if (g < 4) { la.load_one(k2, 4 + g); lb.load_one(k2, 4 + g); }
+            }
             mfma_pair(1, g);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // k-slice 2: fragments of slice 3
+        // phase 2: fragments of slice 3
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             read_frag(cur, 3, 1, g);
@@ -302,12 +306,19 @@ void gemm_mfma_kernel(const GemmP p) {
         }
         wait_copies();                                         // tile kt+1 has landed in the other slot
         lds_barrier();                                         // and nobody reads this slot any more
-        // k-slice 3: fragments of slice 0 of tile kt+1; tile kt+2 goes into the released slot
+        // phase 3 (hand-over): fragments of slice 0 of tile kt+1; tile kt+2 starts to fill the released slot
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             read_frag(nxt, 0, 0, g);
-            la.issue(cur, kt, g, MIXED);
-            lb.issue(cur + TILE_BYTES, kt, g, MIXED);
+            if (NT_) {
+                if (g < 6) { if (g & 1) lb.copy_one(cur + TILE_BYTES, k2, g >> 1); else la.copy_one(cur, k2, g >> 1); }
+            } else if (NN_) {
+                if (g < 4) { lb.store_one(cur + TILE_BYTES, 2 * g); lb.store_one(cur + TILE_BYTES, 2 * g + 1); }
+                else if (g < 6) la.copy_one(cur, k2, g - 4);
+            } else {
+                la.store_one(cur, g);
+                lb.store_one(cur + TILE_BYTES, g);
+            }
             mfma_pair(1, g);
             __builtin_amdgcn_sched_barrier(0);
         }
