@@ -149,14 +149,45 @@ __device__ __forceinline__ RowInfo key_range(const int2 *info, int k, int T) {
 // ------------------------------------------------------------------------------------------
 // forward
 // ------------------------------------------------------------------------------------------
+// 512 threads: 8 wavefronts x 32 queries = 256 queries per workgroup (two wavefronts per SIMD, so that
+// one can run its softmax on the vector ALUs while the other occupies the matrix core), walking the
+// keys 64 at a time through two LDS slots of {K tile [64][D], V^T tile [D][64]}.  K goes global -> LDS
+// directly (buffer_load ... lds, issued by wavefronts 4..7); V is fetched into registers by wavefronts
+// 0..3, transposed there and written one step later.  One barrier per step: after it every wavefront has
+// finished the previous step, so the slot that step used may be refilled.
+constexpr int FQ = 256, FT = 64;
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((ext_vector_type(4))) uint32_t rawx4;
+
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// fragment of a row-major [rows][D] tile (row bytes 2 D): row, k-slice ks (16 features), lane half
 template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
-    constexpr int KS = D / 16, CB = D / 32;
+__device__ __forceinline__ bf16x8 frag_k(const uint8_t *tile, int row, int ks, int half) {
+    constexpr int UPR = D / 8;
+    return *reinterpret_cast<const bf16x8 *>(tile + (row * UPR + ((ks * 2 + half) ^ swz(row))) * 16);
+}
+// fragment of a transposed [D][64] tile: feature row c, unit u (0..7)
+__device__ __forceinline__ bf16x8 frag_vt(const uint8_t *tile, int c, int u) {
+    return *reinterpret_cast<const bf16x8 *>(tile + (c * 8 + (u ^ swz(c))) * 16);
+}
+
+template <int D>
+__global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
+    constexpr int KS = D / 16, CB = D / 32, UPR = D / 8;
+    constexpr int K_BYTES = FT * D * 2, SLOT = 2 * K_BYTES;          // K tile, then V^T tile
+    constexpr int ROWS_PER_COPY = 1024 / (2 * D);                   // tile rows filled by one 1 KiB copy
+    constexpr int COPIES = FT / ROWS_PER_COPY / 4;                  // per copying wavefront (4 of them)
+    constexpr int V_TASKS = 8 * UPR * 2;                            // (unit, 8-feature block, half of the unit's keys)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    uint8_t *sK = smem, *sVT = smem + BT * D * 2;
 
     const int head = blockIdx.y, g = head / (a.nh / a.nkv);
-    const int q0 = blockIdx.x * BQ;
+    const int q0 = blockIdx.x * FQ;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
@@ -168,7 +199,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
     const bool valid = q < T;
     const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
     const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
-    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + BQ, T) - 1, T);
+    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
     const int kbeg = first.lo, kend = last.hi;
 
     bf16x8 qf[KS];
@@ -184,85 +215,124 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
     float m_run = -INFINITY, l_run = 0.f;
     const float sl2 = a.scale * LOG2E;
 
-    TileLoader<D> lk, lv;
-    lk.load(qkv + nq + g * D, ld, kbeg, T);
-    lv.load(qkv + nq + nk + g * D, ld, kbeg, T);
+    // ---- feeding roles
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
+    // K copies (wavefronts 4..7): copy i of this wavefront fills tile rows r0 .. r0 + ROWS_PER_COPY - 1
+    const int cw = wave - 4;
+    const int k_lrow = lane / UPR, k_pos = lane % UPR;              // row within the copy, unit position in the row
+    auto copy_k = [&](uint8_t *slot, int kt) {
+#pragma unroll
+        for (int i = 0; i < COPIES; ++i) {
+            const int r0 = (cw * COPIES + i) * ROWS_PER_COPY, row = r0 + k_lrow;
+            const int unit = (k_pos & ~7) | ((k_pos & 7) ^ swz(row));
+            const uint32_t off = (uint32_t)(((size_t)(kt + row) * ld + nq + g * D + unit * 8) * 2);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(slot + r0 * 2 * D), 16, (int)off, 0, 0, 0);
+        }
+    };
+    // V tasks (threads < V_TASKS): unit u of 8 keys, 8-feature block cb, keys kk = 4 part .. 4 part + 3 of the unit.
+    // Unit u = (block b, mfma m, lane half hh) of the 64-key tile holds keys 32 b + 16 m + 8 (kk >> 2) + 4 hh + (kk & 3).
+    const bool v_thread = threadIdx.x < V_TASKS;
+    const int v_cb = threadIdx.x % UPR, v_u = (threadIdx.x / UPR) & 7, v_part = threadIdx.x / (UPR * 8);
+    uint4 vr[4];
+    auto load_v = [&](int kt) {
+        if (!v_thread) return;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int key = kt + 32 * (v_u >> 2) + 16 * ((v_u >> 1) & 1) + 8 * v_part + 4 * (v_u & 1) + j;
+            const uint32_t off = (uint32_t)(((size_t)key * ld + nq + nk + g * D + v_cb * 8) * 2);
+            const rawx4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+            vr[j] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+    };
+    auto store_v = [&](uint8_t *vt) {
+        if (!v_thread) return;
+        const uint32_t *w = reinterpret_cast<const uint32_t *>(vr);   // w[j * 4 + e]: features 2e, 2e+1 of key j
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            const uint32_t sel = (rr & 1) ? 0x07060302u : 0x05040100u;
+            uint2 o;
+            o.x = __builtin_amdgcn_perm(w[1 * 4 + (rr >> 1)], w[0 * 4 + (rr >> 1)], sel);
+            o.y = __builtin_amdgcn_perm(w[3 * 4 + (rr >> 1)], w[2 * 4 + (rr >> 1)], sel);
+            const int c = v_cb * 8 + rr;
+            *reinterpret_cast<uint2 *>(vt + (c * 8 + (v_u ^ swz(c))) * 16 + v_part * 8) = o;
+        }
+    };
 
-    for (int kt = kbeg; kt < kend; kt += BT) {
-        lk.store_rows(sK);
-        lv.store_transposed(sVT);
-        __syncthreads();
-        if (kt + BT < kend) {
-            lk.load(qkv + nq + g * D, ld, kt + BT, T);
-            lv.load(qkv + nq + nk + g * D, ld, kt + BT, T);
+    // ---- prologue: tile 0
+    if (wave >= 4) copy_k(smem, kbeg);
+    load_v(kbeg);
+
+    int slot = 0;
+    for (int kt = kbeg; kt < kend; kt += FT, slot ^= 1) {
+        uint8_t *sK = smem + slot * SLOT, *sVT = sK + K_BYTES;
+        store_v(sVT);                                                // V^T of this step (slot last read two steps ago)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // this step's K copy has landed
+        lds_barrier();                                               // ... and everyone is done with the other slot
+        if (kt + FT < kend) {
+            if (wave >= 4) copy_k(smem + (slot ^ 1) * SLOT, kt + FT);
+            load_v(kt + FT);
         }
         // which 32-key blocks can any query of this wavefront see?
-        bool act[4];
-        bool any = false;
+        bool act[2];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            act[b] = (kt + 32 * b < w_hi_max) && (kt + 32 * b + 32 > w_lo_min);
-            any |= act[b];
-        }
-        if (any) {
-            f32x16 s[4];
+        for (int b = 0; b < 2; ++b) act[b] = (kt + 32 * b < w_hi_max) && (kt + 32 * b + 32 > w_lo_min);
+        if (!(act[0] || act[1])) continue;
+        f32x16 s[2];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                s[b] = zero16();
-                if (act[b]) {
+        for (int b = 0; b < 2; ++b) {
+            s[b] = zero16();
+            if (act[b]) {
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks)
-                        s[b] = MFMA(frag_rows<D>(sK, 32 * b + l32, ks, half), qf[ks], s[b]);
-                }
-            }
-            // online softmax on the raw scores (the scale is folded into the exponent);
-            // register i of block b  <->  key kt + 32 b + 8 (i >> 2) + 4 half + (i & 3)
-            float mx = m_run;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (!act[b]) continue;
-                const int kb = kt + 32 * b;
-                if (!(kb >= w_lo_max && kb + 32 <= w_hi_min)) {            // some lane needs masking
-                    const unsigned span = (unsigned)(me.hi - me.lo);
-                    const int rel = kb + 4 * half - me.lo;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        s[b][i] = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? s[b][i] : -INFINITY;
-                }
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[b][i]);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_use = mx == -INFINITY ? 0.f : mx;
-            if (__builtin_amdgcn_ballot_w64(mx != m_run) != 0) {           // some lane's maximum moved
-                const float corr = __builtin_amdgcn_exp2f((m_run - m_use) * sl2);
-                l_run *= corr;
-#pragma unroll
-                for (int c = 0; c < CB; ++c)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[c][i] *= corr;
-            }
-            m_run = mx;
-            const float msc = m_use * sl2;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (!act[b]) continue;
-                float p[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    p[i] = __builtin_amdgcn_exp2f(fmaf(s[b][i], sl2, -msc));
-                    l_run += p[i];
-                }
-#pragma unroll
-                for (int m = 0; m < 2; ++m) {
-                    const bf16x8 pf = pack8(p + 8 * m);
-                    const int u = b * 4 + m * 2 + half;
-#pragma unroll
-                    for (int c = 0; c < CB; ++c) oacc[c] = MFMA(frag_tr(sVT, 32 * c + l32, u), pf, oacc[c]);
-                }
+                for (int ks = 0; ks < KS; ++ks) s[b] = MFMA(frag_k<D>(sK, 32 * b + l32, ks, half), qf[ks], s[b]);
             }
         }
-        __syncthreads();
+        // online softmax on the raw scores (the scale is folded into the exponent);
+        // register i of block b  <->  key kt + 32 b + 8 (i >> 2) + 4 half + (i & 3)
+        float mx = m_run;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            if (!act[b]) continue;
+            const int kb = kt + 32 * b;
+            if (!(kb >= w_lo_max && kb + 32 <= w_hi_min)) {            // some lane needs masking
+                const unsigned span = (unsigned)(me.hi - me.lo);
+                const int rel = kb + 4 * half - me.lo;
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    s[b][i] = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? s[b][i] : -INFINITY;
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[b][i]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_use = mx == -INFINITY ? 0.f : mx;
+        if (__builtin_amdgcn_ballot_w64(mx != m_run) != 0) {           // some lane's maximum moved
+            const float corr = __builtin_amdgcn_exp2f((m_run - m_use) * sl2);
+            l_run *= corr;
+#pragma unroll
+            for (int c = 0; c < CB; ++c)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[c][i] *= corr;
+        }
+        m_run = mx;
+        const float msc = m_use * sl2;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            if (!act[b]) continue;
+            float p[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                p[i] = __builtin_amdgcn_exp2f(fmaf(s[b][i], sl2, -msc));
+                l_run += p[i];
+            }
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const bf16x8 pf = pack8(p + 8 * m);
+                const int u = b * 4 + m * 2 + half;
+#pragma unroll
+                for (int c = 0; c < CB; ++c) oacc[c] = MFMA(frag_vt(sVT, 32 * c + l32, u), pf, oacc[c]);
+            }
+        }
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -526,13 +596,13 @@ hipError_t set_smem(K kern, int bytes) {
 template <int D>
 hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
-    const int smem = 2 * BT * D * 2;
+    const int smem = 2 * 2 * FT * D * 2;
     if (!configured) {
         hipError_t e = set_smem(attn_fwd_kernel<D>, smem);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    attn_fwd_kernel<D><<<dim3(ceil_div(a.T, BQ), a.nh), 256, smem, st>>>(a);
+    attn_fwd_kernel<D><<<dim3(ceil_div(a.T, FQ), a.nh), 512, smem, st>>>(a);
     return hipGetLastError();
 }
 
