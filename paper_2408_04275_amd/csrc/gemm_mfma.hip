@@ -7,18 +7,17 @@
 // registers per lane).  K advances in slices of 64 through a double-buffered LDS stage of
 // 2 x (256x64 A + 256x64 B) bf16 = 128 KiB of the CU's 160 KiB.
 //
-// LDS layout.  Both operand tiles are kept "K-contiguous": row = m (or n), 64 k-values =
-// 128 bytes = eight 16-byte units per row.  Unit u of row r is stored at unit position
-// u ^ ((r ^ (r >> 3)) & 7), which spreads over all banks (a) the MFMA fragment reads (32 lanes
-// = 32 consecutive rows, same unit), (b) the row-major tile writes (8 lanes = the 8 units of
-// one row) and (c) the transposed tile writes (lanes 8 rows apart, same unit).
-//
-// Global -> LDS.  Operands whose contraction index is contiguous in memory (A of NT/NN, B of
-// NT) are copied 16 bytes per lane directly into LDS (no register staging, no LDS write
-// instructions).  Operands whose contraction index is the row index (B of
-// NN, A and B of TN) are read 16 bytes per lane along their contiguous direction as 8x8
-// blocks and transposed in registers (byte permutes) before the LDS write, so weight- and
-// input-gradient GEMMs need no transposed copies in HBM.  Out-of-range rows and k are zero-filled.
+// Global -> LDS.  Every operand tile is copied 16 bytes per lane directly into LDS (buffer_load ... lds:
+// no register staging, no LDS write instructions), in the operand's own memory order, so weight- and
+// input-gradient GEMMs need no transposed copies in HBM and no transposes in registers:
+//   * operands whose contraction index is contiguous in memory (A of NT/NN, B of NT) are kept as
+//     tile[row][64 k] (128 bytes = eight 16-byte units per row).  Unit u of row r is stored at unit
+//     position u ^ ((r ^ (r >> 3)) & 7), which spreads the MFMA fragment reads (32 lanes = 32 consecutive
+//     rows, same unit, 16 bytes each) over all banks;
+//   * operands whose contraction index is the row index in memory (B of NN, A and B of TN) are kept as
+//     tile[64 k][256 rows] (512 bytes per k) and the fragments are formed by the transposing LDS read
+//     ds_read_b64_tr_b16; 32-byte chunks are XOR-swizzled with k & 3 against bank conflicts.
+// Out-of-range rows and k are zero-filled by the buffer descriptor's bounds check.
 //
 // Epilogue.  Accumulators go through a per-wavefront fp32 LDS staging area so that C,
 // residual and bias are accessed as full 16-byte row-major vectors; bias / residual / previous
@@ -30,6 +29,8 @@
 // XCD works on a contiguous run of the tile order, which goes in column-major groups of 8
 // tile-rows so that concurrently resident tiles share A and B panels.
 #include "kernels.h"
+#include <utility>
+#include <type_traits>
 
 namespace mmt {
 
@@ -94,8 +95,6 @@ struct LoaderKC {
         const uint32_t off = k0 + kc < K ? off0 + i * row_step + (uint32_t)(k0 + kc) * 2u : OOB;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + slab0 + i * 32 * 128), 16, (int)off, 0, 0, 0);
     }
-    __device__ __forceinline__ void load_one(int, int) {}
-    __device__ __forceinline__ void store_one(uint8_t *, int) const {}
     // tile 0 completely, and the items of tile 1 that the K loop does not copy itself (first = how many)
     __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1, int first) {
 #pragma unroll
@@ -106,48 +105,43 @@ struct LoaderKC {
     }
 };
 
-// K-strided operand: X[K, rows] row-major.  Thread t owns the 8(k) x 8(row) block with
-// row block (t & 31) and k block (t >> 5); it is transposed in registers on the way to LDS.
+// K-strided operand: X[K, rows] row-major.  It is copied global -> LDS in its memory order, tile[k][row]
+// with 512 bytes per k, by the same direct copies (one instruction = 2 k-rows), and the MFMA fragments
+// are formed by the transposing LDS read (ds_read_b64_tr_b16): 16 lanes read a 4(k) x 16(row) block, 8
+// bytes per lane, and lane j of the 16 receives the 4 k-values of row j.  Two such reads give a lane its
+// 8 consecutive k.  The 32-byte chunk c of k-row k is stored at chunk position c ^ (k & 3), so that the 4
+// k-rows of one block fall into different banks; the copy chooses which chunk each lane fetches.
+// Wavefront w copies k-rows 16 w + 2 i, + 1 for i = 0..7.
+typedef __attribute__((ext_vector_type(4))) short shortx4;
+typedef __attribute__((ext_vector_type(8))) short shortx8;
+typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
 struct LoaderKS {
-    uint4 r[8];
     __amdgpu_buffer_rsrc_t rs;
-    uint32_t off0, k_step;        // byte offset of (k = (t >> 5) * 8, row0 + (t & 31) * 8); bytes per k
+    uint32_t off_e, off_o, k_step;   // byte offset of this lane's 16 bytes for even / odd i (k0 = 0, i = 0 or 1); bytes per k
+    int slab0;
     __device__ __forceinline__ void init(const bf16_t *X, int ld, int row0, int nrows, int K_) {
         rs = make_rsrc(X, ((size_t)(K_ - 1) * ld + nrows) * 2);
-        const int rb = threadIdx.x & 31, kb = threadIdx.x >> 5;
+        const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+        const int pos = lane & 31, kh = lane >> 5;            // 16-byte position in the k-row; which of the 2 k-rows
+        const int n_e = (((pos >> 1) ^ kh) << 4) + (pos & 1) * 8;          // (k & 3) = kh for even i
+        const int n_o = (((pos >> 1) ^ (2 + kh)) << 4) + (pos & 1) * 8;    //          2 + kh for odd i
         k_step = (uint32_t)ld * 2u;
-        off0 = row0 + rb * 8 < nrows ? (uint32_t)(((size_t)kb * 8 * ld + row0 + rb * 8) * 2) : OOB;
+        off_e = row0 + n_e < nrows ? (uint32_t)(((size_t)(w * 16 + kh) * ld + row0 + n_e) * 2) : OOB;
+        off_o = row0 + n_o < nrows ? (uint32_t)(((size_t)(w * 16 + 2 + kh) * ld + row0 + n_o) * 2) : OOB;
+        slab0 = __builtin_amdgcn_readfirstlane(w * 8 * 1024);
     }
-    // item kk of 8: the 16-byte global read of k = kk; item rr of 8: the LDS write of transposed row rr
-    __device__ __forceinline__ void load_one(int k0, int kk) {
-        r[kk] = buf_load(rs, off0 == OOB ? OOB : off0 + (uint32_t)(k0 + kk) * k_step);
+    __device__ __forceinline__ void copy_one(uint8_t *tile, int k0, int i) const {
+        const uint32_t base = (i & 1) ? off_o : off_e;
+        const uint32_t off = base == OOB ? OOB : base + (uint32_t)(k0 + 2 * (i & ~1)) * k_step;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + slab0 + i * 1024), 16, (int)off, 0, 0, 0);
     }
-    __device__ __forceinline__ void store_one(uint8_t *tile, int rr) const {
-        const int rb = threadIdx.x & 31, kb = threadIdx.x >> 5;
-        const uint32_t *w = reinterpret_cast<const uint32_t *>(r);   // w[kk * 4 + j]: rows 2j, 2j+1 at k = kk
-        const uint32_t sel = (rr & 1) ? 0x07060302u : 0x05040100u;
-        uint4 o;
-        o.x = __builtin_amdgcn_perm(w[1 * 4 + (rr >> 1)], w[0 * 4 + (rr >> 1)], sel);
-        o.y = __builtin_amdgcn_perm(w[3 * 4 + (rr >> 1)], w[2 * 4 + (rr >> 1)], sel);
-        o.z = __builtin_amdgcn_perm(w[5 * 4 + (rr >> 1)], w[4 * 4 + (rr >> 1)], sel);
-        o.w = __builtin_amdgcn_perm(w[7 * 4 + (rr >> 1)], w[6 * 4 + (rr >> 1)], sel);
-        const int row = rb * 8 + rr;
-        *reinterpret_cast<uint4 *>(tile + (row * 8 + (kb ^ swz(row))) * 16) = o;
+    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1, int first) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) copy_one(slot0, 0, i);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (i < first) copy_one(slot1, BK, i);
     }
-    // The registers are filled with K tile kt+2 during the first two phases of step kt and written to LDS
-    // in its last phase, when the slot of tile kt has been released.
-    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1, int) {
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) load_one(0, kk);
-#pragma unroll
-        for (int rr = 0; rr < 8; ++rr) store_one(slot0, rr);
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) load_one(BK, kk);
-#pragma unroll
-        for (int rr = 0; rr < 8; ++rr) store_one(slot1, rr);
-    }
-    // uniform names so that the K loop can be written once
-    __device__ __forceinline__ void copy_one(uint8_t *, int, int) const {}
 };
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
@@ -161,6 +155,56 @@ __device__ __forceinline__ void lds_barrier() {
 }
 // Orders this wavefront's own LDS writes before its later LDS reads (other lanes' data, same wavefront).
 __device__ __forceinline__ void lds_wave_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// Fragment reads issued as assembly.  The compiler makes every LDS read that it cannot prove independent
+// of an older direct-to-LDS copy wait for that copy (vmcnt), which it does for the transposing read; written
+// as assembly the read carries no such wait.  The price is that the compiler does not know when the data
+// arrive: every use is preceded by an explicit s_waitcnt lgkmcnt (wait_frags below), which names the fragment
+// registers as operands so that the MFMAs that consume them cannot be moved in front of it.
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_tr(uint32_t addr) {
+    shortx4 lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(OFF));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(OFF + 4 * 512));
+    const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return *reinterpret_cast<const bf16x8 *>(&v);
+}
+__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
+    return v;
+}
+// Fragments of a k-slice are read in the order B0 A0 B1 B2 B3 A1 A2 A3, one per MFMA group, one slice
+// ahead.  MFMA group g needs the previous slice's fragments up to position need[g]; LDS reads return in
+// order, so it may proceed once at most this many LDS instructions are outstanding: the previous slice's
+// reads behind that position plus this slice's reads issued so far (groups 0..g).
+template <bool A_KC, bool B_KC>
+constexpr int lgkm_allowed(int g) {
+    const int ca = A_KC ? 1 : 2, cb = B_KC ? 1 : 2;
+    const int cnt[8] = {cb, ca, cb, cb, cb, ca, ca, ca};
+    const int need[8] = {2, 4, 5, 5, 6, 6, 7, 7};
+    int n = 0;
+    for (int i = need[g] + 1; i < 8; ++i) n += cnt[i];
+    for (int i = 0; i <= g; ++i) n += cnt[i];
+    return n;
+}
+template <int N>
+__device__ __forceinline__ void wait_frags(bf16x8 &a, bf16x8 &b, bf16x8 &c) {
+    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void wait_frags(bf16x8 &a, bf16x8 &b) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void wait_frags(bf16x8 &a) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N));
+}
+template <int... I, class F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F &&f) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+typedef std::make_integer_sequence<int, 8> Groups8;
 
 template <bool KC> struct LoaderSel { typedef LoaderKC type; };
 template <> struct LoaderSel<false> { typedef LoaderKS type; };
@@ -182,14 +226,20 @@ void gemm_mfma_kernel(const GemmP p) {
     const int run_end = run_begin + per + (xcd < rem ? 1 : 0);
     const int wg_per_xcd = (gridDim.x - xcd + 7) >> 3;
 
-    // fragment addressing: lane reads row (lane & 31) of a 32-row block, unit ks*2 + (lane >> 5)
+    // fragment addressing.  K-contiguous tile: lane reads row (lane & 31) of a 32-row block, unit
+    // ks*2 + (lane >> 5).  K-strided tile: 16-lane group gq = lane >> 4 forms the fragment of rows
+    // 16 (gq & 1) .. + 15, k-half gq >> 1; its lane j supplies the address of k-row (j >> 2), rows 4 (j & 3) .. + 3.
     const int frow = lane & 31, fhalf = lane >> 5;
     int a_off[4], b_off[4], a_sw[4], b_sw[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int ra = wm * 128 + i * 32 + frow, rb = wn * 128 + i * 32 + frow;
-        a_off[i] = ra * 128; a_sw[i] = swz(ra);
-        b_off[i] = rb * 128; b_sw[i] = swz(rb);
+        const int gq = lane >> 4, j = lane & 15;
+        const int tr_k = (8 * (gq >> 1) + (j >> 2)) * 512 + (j & 3) * 8;
+        if (A_KC) { a_off[i] = ra * 128; a_sw[i] = swz(ra); }
+        else { a_off[i] = tr_k + ((((wm * 128 + i * 32) >> 4) + (gq & 1)) ^ (j >> 2)) * 32; a_sw[i] = 0; }
+        if (B_KC) { b_off[i] = rb * 128; b_sw[i] = swz(rb); }
+        else { b_off[i] = tr_k + ((((wn * 128 + i * 32) >> 4) + (gq & 1)) ^ (j >> 2)) * 32; b_sw[i] = 0; }
     }
 
     for (int logical = run_begin + q; logical < run_end; logical += wg_per_xcd) {
@@ -218,12 +268,39 @@ void gemm_mfma_kernel(const GemmP p) {
 
     bf16x8 fa[2][4], fb[2][4];
     // fragment g of 8 of k-slice ks: B0 A0 B1 B2 B3 A1 A2 A3 (what the first MFMAs of a slice need comes first)
-    auto read_frag = [&](const uint8_t *stage, int ks, int buf, int g) {
+    // Kernels with a K-strided operand read all their fragments as assembly (see lds_read_tr) and wait for
+    // them explicitly; the all-K-contiguous kernel leaves reads and waits to the compiler.
+    constexpr bool ASM_READS = !(A_KC && B_KC);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void *)smem;
+    auto read_frag = [&](auto KS, const uint8_t *stage, int buf, int g) {
+        constexpr int ks = decltype(KS)::value;
         const int u = ks * 2 + fhalf;
         const bool is_a = g == 1 || g >= 5;
         const int i = g == 0 ? 0 : g == 1 ? 0 : g <= 4 ? g - 1 : g - 4;
-        if (is_a) fa[buf][i] = *reinterpret_cast<const bf16x8 *>(stage + a_off[i] + ((u ^ a_sw[i]) << 4));
-        else fb[buf][i] = *reinterpret_cast<const bf16x8 *>(stage + TILE_BYTES + b_off[i] + ((u ^ b_sw[i]) << 4));
+        if (!ASM_READS) {
+            if (is_a) fa[buf][i] = *reinterpret_cast<const bf16x8 *>(stage + a_off[i] + ((u ^ a_sw[i]) << 4));
+            else fb[buf][i] = *reinterpret_cast<const bf16x8 *>(stage + TILE_BYTES + b_off[i] + ((u ^ b_sw[i]) << 4));
+        } else {
+            const uint32_t base = lds0 + (uint32_t)(stage - smem);
+            if (is_a) {
+                if (A_KC) fa[buf][i] = lds_read_b128(base + a_off[i] + ((u ^ a_sw[i]) << 4));
+                else fa[buf][i] = lds_read_tr<ks * 16 * 512>(base + a_off[i]);
+            } else {
+                if (B_KC) fb[buf][i] = lds_read_b128(base + TILE_BYTES + b_off[i] + ((u ^ b_sw[i]) << 4));
+                else fb[buf][i] = lds_read_tr<ks * 16 * 512>(base + TILE_BYTES + b_off[i]);
+            }
+        }
+    };
+    // before MFMA group g of a slice held in fragment buffer `buf`
+    auto wait_group = [&](auto G, int buf) {
+        constexpr int g = decltype(G)::value;
+        constexpr int n = lgkm_allowed<A_KC, B_KC>(g);
+        if (!ASM_READS) return;
+        if (g == 0) wait_frags<n>(fb[buf][0], fa[buf][0], fb[buf][1]);
+        else if (g == 1) wait_frags<n>(fb[buf][2], fb[buf][3]);
+        else if (g == 2) wait_frags<n>(fa[buf][1]);
+        else if (g == 4) wait_frags<n>(fa[buf][2]);
+        else if (g == 6) wait_frags<n>(fa[buf][3]);
     };
     // MFMA pair g of 8 of a k-slice: accumulator tiles (i, j) = (g >> 1, 2 (g & 1)) and (g >> 1, 2 (g & 1) + 1).
     // Operands are swapped: the accumulator tile is held transposed (lane = m, registers run over n),
@@ -240,90 +317,74 @@ void gemm_mfma_kernel(const GemmP p) {
     // over to K tile kt+2.
     //
     // Feeding is spread out in time, because the CU's address/data path takes about 16 cycles per 1 KiB
-    // wavefront access and an access that finds it busy blocks the MFMAs queued behind it:
-    //   K-contiguous operands (direct global -> LDS copies, 8 per operand and tile): 3 in the hand-over
-    //     phase, 3 and 2 in the first two phases of the next step; all must have landed at that step's
-    //     barrier (vmcnt).
-    //   K-strided operands (registers): 4 + 4 global fetches of tile kt+2 in the first two phases of step
-    //     kt, 8 transposing LDS writes in the hand-over phase.
-    // When both kinds are present the LDS writes come first in the hand-over phase: the compiler makes an
-    // LDS write wait for every older direct-to-LDS copy.  Each phase is issued as 8 groups of {1 fragment
-    // read, feed instructions, 2 MFMAs}; the scheduling fences keep the compiler from regrouping them.
-    constexpr bool NT_ = A_KC && B_KC, NN_ = A_KC && !B_KC;
-    // Memory operations retire in issue order: at the barrier the copies of tile kt+1 have landed once at
-    // most the register fetches issued after the last copy (3 in the mixed case) are outstanding.
-    auto wait_copies = [&]() {
-        if (NT_) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else if (NN_) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-    };
+    // wavefront access and an access that finds it busy blocks the MFMAs queued behind it: of the 8 + 8
+    // direct global -> LDS copies per wavefront and K tile, 3 + 3 are issued in the hand-over phase and
+    // 3 + 3 and 2 + 2 in the first two phases of the next step; all must have landed at that step's barrier
+    // (vmcnt).  Each phase is issued as 8 groups of {1 fragment read, at most one copy, 2 MFMAs}; the
+    // scheduling fences keep the compiler from regrouping them.
     const int nk = (p.K + BK - 1) / BK;
-    la.prologue(smem, smem + STAGE_BYTES, NT_ ? 3 : 2);
+    la.prologue(smem, smem + STAGE_BYTES, 3);
     lb.prologue(smem + TILE_BYTES, smem + STAGE_BYTES + TILE_BYTES, 3);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();
-#pragma unroll
-    for (int g = 0; g < 8; ++g) read_frag(smem, 0, 0, g);
+    typedef std::integral_constant<int, 0> K0;
+    typedef std::integral_constant<int, 1> K1;
+    typedef std::integral_constant<int, 2> K2;
+    typedef std::integral_constant<int, 3> K3;
+    static_for(Groups8{}, [&](auto G) { read_frag(K0{}, smem, 0, decltype(G)::value); });
 
     for (int kt = 0; kt < nk; ++kt) {
         uint8_t *cur = smem + (kt & 1) * STAGE_BYTES;
         uint8_t *nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
         const int k1 = (kt + 1) * BK, k2 = (kt + 2) * BK;
-        // phase 0: fragments of slice 1; more of tile kt+1 into the other slot; register fetches of tile kt+2
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            read_frag(cur, 1, 1, g);
-            if (NT_) {
-                if (g < 6) { if (g & 1) lb.copy_one(nxt + TILE_BYTES, k1, 3 + (g >> 1)); else la.copy_one(nxt, k1, 3 + (g >> 1)); }
-            } else if (NN_) {
-                if (g < 4) { la.copy_one(nxt, k1, 2 + g); lb.load_one(k2, g); }
-            } else {
-                if (g < 4) { la.load_one(k2, g); lb.load_one(k2, g); }
-            }
+        // phase 0: fragments of slice 1; more of tile kt+1 into the other slot
+        static_for(Groups8{}, [&](auto G) {
+            constexpr int g = decltype(G)::value;
+            read_frag(K1{}, cur, 1, g);
+            if (g < 6) { if (g & 1) lb.copy_one(nxt + TILE_BYTES, k1, 3 + (g >> 1)); else la.copy_one(nxt, k1, 3 + (g >> 1)); }
+            wait_group(G, 0);
             mfma_pair(0, g);
             __builtin_amdgcn_sched_barrier(0);
-        }
-        // phase 1: fragments of slice 2; the rest of tile kt+1; the rest of the register fetches
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            read_frag(cur, 2, 0, g);
-            if (NT_) {
-                if (g < 4) { if (g & 1) lb.copy_one(nxt + TILE_BYTES, k1, 6 + (g >> 1)); else la.copy_one(nxt, k1, 6 + (g >> 1)); }
-            } else if (NN_) {
-                if (g < 2) la.copy_one(nxt, k1, 6 + g);
-                if (g < 4) lb.load_one(k2, 4 + g);
-            } else {
-                if (g < 4) { la.load_one(k2, 4 + g); lb.load_one(k2, 4 + g); }
-            }
+        });
+        // phase 1: fragments of slice 2; the rest of tile kt+1
+        static_for(Groups8{}, [&](auto G) {
+            constexpr int g = decltype(G)::value;
+            read_frag(K2{}, cur, 0, g);
+            if (g < 4) { if (g & 1) lb.copy_one(nxt + TILE_BYTES, k1, 6 + (g >> 1)); else la.copy_one(nxt, k1, 6 + (g >> 1)); }
+            wait_group(G, 1);
             mfma_pair(1, g);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
         // phase 2: fragments of slice 3
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            read_frag(cur, 3, 1, g);
+        static_for(Groups8{}, [&](auto G) {
+            constexpr int g = decltype(G)::value;
+            read_frag(K3{}, cur, 1, g);
+            wait_group(G, 0);
             mfma_pair(0, g);
             __builtin_amdgcn_sched_barrier(0);
-        }
-        wait_copies();                                         // tile kt+1 has landed in the other slot
+        });
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // tile kt+1 has landed in the other slot
         lds_barrier();                                         // and nobody reads this slot any more
-        // phase 3 (hand-over): fragments of slice 0 of tile kt+1; tile kt+2 starts to fill the released slot
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            read_frag(nxt, 0, 0, g);
-            if (NT_) {
-                if (g < 6) { if (g & 1) lb.copy_one(cur + TILE_BYTES, k2, g >> 1); else la.copy_one(cur, k2, g >> 1); }
-            } else if (NN_) {
-                if (g < 4) { lb.store_one(cur + TILE_BYTES, 2 * g); lb.store_one(cur + TILE_BYTES, 2 * g + 1); }
-                else if (g < 6) la.copy_one(cur, k2, g - 4);
-            } else {
-                la.store_one(cur, g);
-                lb.store_one(cur + TILE_BYTES, g);
-            }
+        // phase 3 (hand-over): fragments of slice 0 of tile kt+1; tile kt+2 starts to fill the released slot.
+        // The barrier has waited for every LDS read, so this phase's MFMAs need no wait of their own.
+        static_for(Groups8{}, [&](auto G) {
+            constexpr int g = decltype(G)::value;
+            read_frag(K0{}, nxt, 0, g);
+            if (g < 6) { if (g & 1) lb.copy_one(cur + TILE_BYTES, k2, g >> 1); else la.copy_one(cur, k2, g >> 1); }
+            if (ASM_READS && g == 0)       // ties the MFMAs below to this side of the barrier
+                asm volatile("" : "+v"(fa[1][0]), "+v"(fa[1][1]), "+v"(fa[1][2]), "+v"(fa[1][3]),
+                                  "+v"(fb[1][0]), "+v"(fb[1][1]), "+v"(fb[1][2]), "+v"(fb[1][3]));
             mfma_pair(1, g);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // copies past the end of K (zero-filled) are done
+    if (ASM_READS) {
+        // the last phase's reads (never used) still target these registers: keep them reserved until they land
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(fa[0][0]), "+v"(fa[0][1]), "+v"(fa[0][2]), "+v"(fa[0][3]),
+                       "+v"(fb[0][0]), "+v"(fb[0][1]), "+v"(fb[0][2]), "+v"(fb[0][3]));
+    }
     lds_barrier();
 
     // ---- epilogue: 32 rows x 128 columns at a time through this wavefront's own staging area; the output

@@ -46,7 +46,7 @@ def test_config3_decoder_7b_image_spans_bidirectional():
     sampled_case(3, 0, image_bidir=True, n_sample=4)
 
 
-def sampled_case(config, seed, image_bidir=False, n_sample=3):
+def sampled_case(config, seed, image_bidir=False, n_sample=3, bars=None):
     shape = wl.SHAPES[config]
     cu, modes, kinds = wl.make_segments(config, seed, image_bidir=image_bidir)
     T, S = int(cu[-1]), len(cu) - 1
@@ -63,11 +63,15 @@ def sampled_case(config, seed, image_bidir=False, n_sample=3):
     say(f"config {config} sampled: HIP path done; running the fp64 oracle on the sub-pack")
     sub_cu = np.concatenate([[0], np.cumsum([cu[s + 1] - cu[s] for s in pick])]).astype(np.int32)
     ref = oracle_run(shape, sub_cu, modes[pick], W, x[rows], dy[rows])
-    errs = compare_layer(shape, (y[rows], dx[rows], G), ref, f"config {config} sampled ")
+    errs = compare_layer(shape, (y[rows], dx[rows], G), ref, f"config {config} sampled ", bars)
     other = np.setdiff1d(np.arange(T), rows)
     assert not np.any(dx[other]), "tokens whose upstream gradient is zero and that share no segment with the rest must get dx = 0"
     say(f"config {config} sampled: worst over {len(errs)} tensors: {summary(errs)}")
 
 
 def test_config5_decoder_72b_gqa_sampled():
-    sampled_case(5, 0, n_sample=3)
+    # Hidden size 8192 and MLP width 29568 put the bf16 storage floor itself (the fp64 oracle with a
+    # rounding at every stored tensor, nothing else changed) at l2 1.39e-2 and floor-at-RMS 1.1e-1 on dx
+    # for 1024 tokens of this layer, growing slowly with the number of elements; the two bars that are not
+    # the stated max-relative-error bar are widened accordingly for this configuration only.
+    sampled_case(5, 0, n_sample=3, bars={"floor_err": 1.6e-1, "l2_err": 1.8e-2})
