@@ -23,6 +23,17 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published)
 PEAK_F32_TFLOPS = 157.3
+# HBM-side traffic per launch of each GEMM class on workload 3, in bytes, mean over the class's 4 launches per
+# step: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script (KiB per dispatch), each scaled by
+# what the same counter reads for a plain 512 MiB device copy (FETCH_SIZE reads half the bytes copied: x2;
+# WRITE_SIZE reads them all: x1).  FETCH_SIZE counts what the eight L2s request from the fabric, whether it
+# is then served by the memory-side cache or by HBM.  A hardware counter cannot be read from inside this
+# process, so the figures are carried here and re-measured whenever the GEMM kernel changes.
+MEASURED_TRAFFIC_CONFIG3 = {
+    "gemm_nt": (2 * 615295.5 + 169984.0) * 1024,
+    "gemm_nn": (2 * 622388.2 + 93184.0) * 1024,
+    "gemm_tn": (2 * 707181.1 + 98816.0) * 1024,
+}
 PAPER_CONTEXT = "paper: 54.7% MFU, 72B MLLM on 1172 GPUs (abstract; Section 7.1) -- other hardware, whole system"
 
 
@@ -31,6 +42,16 @@ def gemm_flops_by_layout(shape, T):
     per = 2.0 * T * (shape.nqkv * shape.hidden + shape.hidden * shape.nq + shape.fc1_rows * shape.hidden
                      + shape.hidden * shape.ffn_hidden)
     return {"NT": per, "NN": per, "TN": per}
+
+
+def gemm_bytes_by_layout(shape, T):
+    """Algorithmic bytes of one launch class: every operand read once, every output written once (bf16),
+    plus the residual the forward projections add.  The three classes touch the same tensors in different
+    roles, so the sum is the same for each up to the residual reads."""
+    H, F = shape.hidden, shape.ffn_hidden
+    weights = shape.nqkv * H + H * shape.nq + shape.fc1_rows * H + H * F
+    acts = T * (H + shape.nqkv) + T * (shape.nq + H) + T * (H + shape.fc1_rows) + T * (F + H)
+    return 2.0 * (weights + acts)
 
 
 def cpu_baseline(shape, cu, modes, W, seed, target_tokens):
@@ -129,7 +150,9 @@ def main():
                 "frac": (kernels[dom]["tflops"] or 0.0) / peak,
                 "avg_launch_ms": kernels[dom]["ms_per_step"] / dom_launches,
                 "flops_per_launch": gf[{"gemm_nt": "NT", "gemm_nn": "NN", "gemm_tn": "TN"}[dom]] / dom_launches,
-                "traffic": None}
+                "traffic": MEASURED_TRAFFIC_CONFIG3[dom] if args.config == 3 else None,
+                "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+                "algorithmic_bytes_per_launch": gemm_bytes_by_layout(shape, T) / dom_launches}
 
     out = {
         "metric": "layer fwd+bwd TFLOP/s and % bf16 MFMA peak on packed multimodal microbatch",
