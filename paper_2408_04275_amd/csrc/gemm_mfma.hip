@@ -38,8 +38,8 @@ namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int TILE_BYTES = BM * BK * 2;          // 32 KiB per operand tile
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;
-constexpr int SMEM_BYTES = 2 * STAGE_BYTES;      // 128 KiB
+constexpr int N_SLOTS = 5;                       // ring of operand tiles: A0 B0 A1 B1 A2 | B2 A3 ...
+constexpr int SMEM_BYTES = N_SLOTS * TILE_BYTES; // 160 KiB: all of the compute unit's LDS
 constexpr int EPI_PITCH = 128 + 4;               // floats per staged row
 constexpr int GROUP_M = 8;
 
@@ -79,7 +79,9 @@ typedef __attribute__((address_space(3))) void lds_void;
 struct LoaderKC {
     __amdgpu_buffer_rsrc_t rs;
     uint32_t off0, row_step;      // byte offset of this lane's row at i = 0 (without the unit); bytes per 32 rows
+    uint32_t vo_e, vo_o;          // fast path: this lane's byte offset for even / odd i, without k0 and i * row_step
     int kc0, K, slab0;            // unit column (elements) for even i (odd i: kc0 ^ 32); first slab's LDS offset
+    bool full;                    // all 256 rows of the tile exist
     __device__ __forceinline__ void init(const bf16_t *X, int ld, int row0, int nrows, int K_) {
         rs = make_rsrc(X, ((size_t)(nrows - 1) * ld + K_) * 2);
         const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -87,21 +89,31 @@ struct LoaderKC {
         kc0 = (((lane & 7) ^ (lane >> 3) ^ w) & 7) * 8;
         off0 = (uint32_t)((size_t)(row0 + w * 8 + (lane >> 3)) * ld * 2);
         row_step = (uint32_t)ld * 64u;
+        vo_e = off0 + (uint32_t)kc0 * 2u;
+        vo_o = off0 + (uint32_t)(kc0 ^ 32) * 2u;
+        full = row0 + BM <= nrows;
         slab0 = __builtin_amdgcn_readfirstlane(w * 8 * 128);
     }
-    // item i of 8 of the tile at k0: rows 32 i + 8 w .. + 7 -> LDS
+    // item i of 8 of the tile at k0: rows 32 i + 8 w .. + 7 -> LDS.  FAST: the caller guarantees that the
+    // tile lies inside the matrix (all rows, k0 + 64 <= K); then the per-lane offset is a constant and the
+    // rest of the address is a scalar, so no vector instruction precedes the copy (a copy that has to wait
+    // for the vector ALU to deliver its address holds up the MFMAs queued behind it).
+    template <bool FAST>
     __device__ __forceinline__ void copy_one(uint8_t *tile, int k0, int i) const {
-        const int kc = kc0 ^ ((i & 1) * 32);
-        const uint32_t off = k0 + kc < K ? off0 + i * row_step + (uint32_t)(k0 + kc) * 2u : OOB;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + slab0 + i * 32 * 128), 16, (int)off, 0, 0, 0);
+        lds_void *dst = (lds_void *)(tile + slab0 + i * 32 * 128);
+        if (FAST) {
+            const int so = __builtin_amdgcn_readfirstlane(k0 * 2 + i * (int)row_step);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst, 16, (int)((i & 1) ? vo_o : vo_e), so, 0, 0);
+        } else {
+            const int kc = kc0 ^ ((i & 1) * 32);
+            const uint32_t off = k0 + kc < K ? off0 + i * row_step + (uint32_t)(k0 + kc) * 2u : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst, 16, (int)off, 0, 0, 0);
+        }
     }
-    // tile 0 completely, and the items of tile 1 that the K loop does not copy itself (first = how many)
-    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1, int first) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) copy_one(slot0, 0, i);
+    __device__ __forceinline__ void copy_items(uint8_t *tile, int k0, int lo, int hi) const {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            if (i < first) copy_one(slot1, BK, i);
+            if (i >= lo && i < hi) copy_one<false>(tile, k0, i);
     }
 };
 
@@ -119,6 +131,7 @@ struct LoaderKS {
     __amdgpu_buffer_rsrc_t rs;
     uint32_t off_e, off_o, k_step;   // byte offset of this lane's 16 bytes for even / odd i (k0 = 0, i = 0 or 1); bytes per k
     int slab0;
+    bool full;                       // all 256 rows of the tile exist
     __device__ __forceinline__ void init(const bf16_t *X, int ld, int row0, int nrows, int K_) {
         rs = make_rsrc(X, ((size_t)(K_ - 1) * ld + nrows) * 2);
         const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -128,19 +141,26 @@ struct LoaderKS {
         k_step = (uint32_t)ld * 2u;
         off_e = row0 + n_e < nrows ? (uint32_t)(((size_t)(w * 16 + kh) * ld + row0 + n_e) * 2) : OOB;
         off_o = row0 + n_o < nrows ? (uint32_t)(((size_t)(w * 16 + 2 + kh) * ld + row0 + n_o) * 2) : OOB;
+        full = row0 + BM <= nrows;
         slab0 = __builtin_amdgcn_readfirstlane(w * 8 * 1024);
     }
+    // FAST: as for the K-contiguous loader (all rows exist, k0 + 64 <= K).
+    template <bool FAST>
     __device__ __forceinline__ void copy_one(uint8_t *tile, int k0, int i) const {
         const uint32_t base = (i & 1) ? off_o : off_e;
-        const uint32_t off = base == OOB ? OOB : base + (uint32_t)(k0 + 2 * (i & ~1)) * k_step;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + slab0 + i * 1024), 16, (int)off, 0, 0, 0);
+        lds_void *dst = (lds_void *)(tile + slab0 + i * 1024);
+        if (FAST) {
+            const int so = __builtin_amdgcn_readfirstlane((k0 + 2 * (i & ~1)) * (int)k_step);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst, 16, (int)base, so, 0, 0);
+        } else {
+            const uint32_t off = base == OOB ? OOB : base + (uint32_t)(k0 + 2 * (i & ~1)) * k_step;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst, 16, (int)off, 0, 0, 0);
+        }
     }
-    __device__ __forceinline__ void prologue(uint8_t *slot0, uint8_t *slot1, int first) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) copy_one(slot0, 0, i);
+    __device__ __forceinline__ void copy_items(uint8_t *tile, int k0, int lo, int hi) const {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            if (i < first) copy_one(slot1, BK, i);
+            if (i >= lo && i < hi) copy_one<false>(tile, k0, i);
     }
 };
 
@@ -230,16 +250,21 @@ void gemm_mfma_kernel(const GemmP p) {
     // ks*2 + (lane >> 5).  K-strided tile: 16-lane group gq = lane >> 4 forms the fragment of rows
     // 16 (gq & 1) .. + 15, k-half gq >> 1; its lane j supplies the address of k-row (j >> 2), rows 4 (j & 3) .. + 3.
     const int frow = lane & 31, fhalf = lane >> 5;
-    int a_off[4], b_off[4], a_sw[4], b_sw[4];
+    // a_rd[i][ks]: offset inside an A tile of the fragment of row block i, k-slice ks (K-strided tiles need
+    // one per block only: the slice is an immediate offset of the read)
+    int a_rd[4][A_KC ? 4 : 1], b_rd[4][B_KC ? 4 : 1];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int ra = wm * 128 + i * 32 + frow, rb = wn * 128 + i * 32 + frow;
         const int gq = lane >> 4, j = lane & 15;
         const int tr_k = (8 * (gq >> 1) + (j >> 2)) * 512 + (j & 3) * 8;
-        if (A_KC) { a_off[i] = ra * 128; a_sw[i] = swz(ra); }
-        else { a_off[i] = tr_k + ((((wm * 128 + i * 32) >> 4) + (gq & 1)) ^ (j >> 2)) * 32; a_sw[i] = 0; }
-        if (B_KC) { b_off[i] = rb * 128; b_sw[i] = swz(rb); }
-        else { b_off[i] = tr_k + ((((wn * 128 + i * 32) >> 4) + (gq & 1)) ^ (j >> 2)) * 32; b_sw[i] = 0; }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (A_KC) a_rd[i][ks] = ra * 128 + (((ks * 2 + fhalf) ^ swz(ra)) << 4);
+            if (B_KC) b_rd[i][ks] = rb * 128 + (((ks * 2 + fhalf) ^ swz(rb)) << 4);
+        }
+        if (!A_KC) a_rd[i][0] = tr_k + ((((wm * 128 + i * 32) >> 4) + (gq & 1)) ^ (j >> 2)) * 32;
+        if (!B_KC) b_rd[i][0] = tr_k + ((((wn * 128 + i * 32) >> 4) + (gq & 1)) ^ (j >> 2)) * 32;
     }
 
     for (int logical = run_begin + q; logical < run_end; logical += wg_per_xcd) {
@@ -272,22 +297,20 @@ void gemm_mfma_kernel(const GemmP p) {
     // them explicitly; the all-K-contiguous kernel leaves reads and waits to the compiler.
     constexpr bool ASM_READS = !(A_KC && B_KC);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void *)smem;
-    auto read_frag = [&](auto KS, const uint8_t *stage, int buf, int g) {
+    auto read_frag = [&](auto KS, int ta, int tb, int buf, int g) {      // ta, tb: LDS offsets of the A and B tiles
         constexpr int ks = decltype(KS)::value;
-        const int u = ks * 2 + fhalf;
         const bool is_a = g == 1 || g >= 5;
         const int i = g == 0 ? 0 : g == 1 ? 0 : g <= 4 ? g - 1 : g - 4;
         if (!ASM_READS) {
-            if (is_a) fa[buf][i] = *reinterpret_cast<const bf16x8 *>(stage + a_off[i] + ((u ^ a_sw[i]) << 4));
-            else fb[buf][i] = *reinterpret_cast<const bf16x8 *>(stage + TILE_BYTES + b_off[i] + ((u ^ b_sw[i]) << 4));
+            if (is_a) fa[buf][i] = *reinterpret_cast<const bf16x8 *>(smem + ta + a_rd[i][A_KC ? ks : 0]);
+            else fb[buf][i] = *reinterpret_cast<const bf16x8 *>(smem + tb + b_rd[i][B_KC ? ks : 0]);
         } else {
-            const uint32_t base = lds0 + (uint32_t)(stage - smem);
             if (is_a) {
-                if (A_KC) fa[buf][i] = lds_read_b128(base + a_off[i] + ((u ^ a_sw[i]) << 4));
-                else fa[buf][i] = lds_read_tr<ks * 16 * 512>(base + a_off[i]);
+                if (A_KC) fa[buf][i] = lds_read_b128(lds0 + ta + a_rd[i][A_KC ? ks : 0]);
+                else fa[buf][i] = lds_read_tr<ks * 16 * 512>(lds0 + ta + a_rd[i][0]);
             } else {
-                if (B_KC) fb[buf][i] = lds_read_b128(base + TILE_BYTES + b_off[i] + ((u ^ b_sw[i]) << 4));
-                else fb[buf][i] = lds_read_tr<ks * 16 * 512>(base + TILE_BYTES + b_off[i]);
+                if (B_KC) fb[buf][i] = lds_read_b128(lds0 + tb + b_rd[i][B_KC ? ks : 0]);
+                else fb[buf][i] = lds_read_tr<ks * 16 * 512>(lds0 + tb + b_rd[i][0]);
             }
         }
     };
@@ -311,73 +334,83 @@ void gemm_mfma_kernel(const GemmP p) {
         acc[i][j + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j + 1], fa[buf][i], acc[i][j + 1], 0, 0, 0);
     };
 
-    // Software pipeline, one barrier per 64-deep K step, two LDS slots.  Step kt multiplies K tile kt out
-    // of slot kt & 1 in four k-slices (phases); the fragments of a slice are read one slice ahead.  After
-    // the third slice every wavefront has read all of slot kt & 1, so past the barrier the slot is handed
-    // over to K tile kt+2.
-    //
-    // Feeding is spread out in time, because the CU's address/data path takes about 16 cycles per 1 KiB
-    // wavefront access and an access that finds it busy blocks the MFMAs queued behind it: of the 8 + 8
-    // direct global -> LDS copies per wavefront and K tile, 3 + 3 are issued in the hand-over phase and
-    // 3 + 3 and 2 + 2 in the first two phases of the next step; all must have landed at that step's barrier
-    // (vmcnt).  Each phase is issued as 8 groups of {1 fragment read, at most one copy, 2 MFMAs}; the
-    // scheduling fences keep the compiler from regrouping them.
+    // Software pipeline, one barrier per 64-deep K step.  The operand tiles A0 B0 A1 B1 A2 B2 ... go round
+    // a ring of five 32 KiB slots.  Step kt multiplies K tile kt in four k-slices (phases); the fragments of
+    // a slice are read one slice ahead.  After the third phase every wavefront has read all of A(kt) and
+    // B(kt), so past that step's barrier their two slots are handed to B(kt+2) and A(kt+3).  Between two
+    // barriers a wavefront issues the 8 copies of one B tile and then the 8 copies of one A tile, one in
+    // every second MFMA group: the compute unit's address path takes about 20 cycles per 1 KiB copy, and
+    // four wavefronts issuing one in every group (64 cycles) would back it up and stall the MFMAs behind
+    // it.  At the barrier of step kt the tiles A(kt+1) (copied during the previous step) and B(kt+1) (copied
+    // in the first half of this interval) must have landed; the 8 youngest copies (of A(kt+2)) may still be
+    // in flight (vmcnt(8): memory operations retire in issue order).  A copy thus has between two and six
+    // phases to land, against about one phase of L2 latency.
     const int nk = (p.K + BK - 1) / BK;
-    la.prologue(smem, smem + STAGE_BYTES, 3);
-    lb.prologue(smem + TILE_BYTES, smem + STAGE_BYTES + TILE_BYTES, 3);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    lds_barrier();
     typedef std::integral_constant<int, 0> K0;
     typedef std::integral_constant<int, 1> K1;
     typedef std::integral_constant<int, 2> K2;
     typedef std::integral_constant<int, 3> K3;
-    static_for(Groups8{}, [&](auto G) { read_frag(K0{}, smem, 0, decltype(G)::value); });
+    la.copy_items(smem + 0 * TILE_BYTES, 0, 0, 8);
+    lb.copy_items(smem + 1 * TILE_BYTES, 0, 0, 8);
+    la.copy_items(smem + 2 * TILE_BYTES, BK, 0, 8);
+    lb.copy_items(smem + 3 * TILE_BYTES, BK, 0, 4);
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");         // A0 and B0 have landed
+    lds_barrier();
+    static_for(Groups8{}, [&](auto G) { read_frag(K0{}, 0, TILE_BYTES, 0, decltype(G)::value); });
 
-    for (int kt = 0; kt < nk; ++kt) {
-        uint8_t *cur = smem + (kt & 1) * STAGE_BYTES;
-        uint8_t *nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+    // LDS offsets of the slots that hold tiles 2kt .. 2kt+4 of the ring (A(kt), B(kt), A(kt+1), B(kt+1), A(kt+2))
+    int o0 = 0, o1 = TILE_BYTES, o2 = 2 * TILE_BYTES, o3 = 3 * TILE_BYTES, o4 = 4 * TILE_BYTES;
+    const bool full_tiles = la.full && lb.full;
+    auto step = [&](auto FAST_, int kt) {
+        constexpr bool FAST = decltype(FAST_)::value;
         const int k1 = (kt + 1) * BK, k2 = (kt + 2) * BK;
-        // phase 0: fragments of slice 1; more of tile kt+1 into the other slot
+        // phase 0: fragments of slice 1; second half of B(kt+1)
         static_for(Groups8{}, [&](auto G) {
             constexpr int g = decltype(G)::value;
-            read_frag(K1{}, cur, 1, g);
-            if (g < 6) { if (g & 1) lb.copy_one(nxt + TILE_BYTES, k1, 3 + (g >> 1)); else la.copy_one(nxt, k1, 3 + (g >> 1)); }
+            read_frag(K1{}, o0, o1, 1, g);
+            if (!(g & 1)) lb.template copy_one<FAST>(smem + o3, k1, 4 + (g >> 1));
             wait_group(G, 0);
             mfma_pair(0, g);
             __builtin_amdgcn_sched_barrier(0);
         });
-        // phase 1: fragments of slice 2; the rest of tile kt+1
+        // phase 1: fragments of slice 2; first half of A(kt+2)
         static_for(Groups8{}, [&](auto G) {
             constexpr int g = decltype(G)::value;
-            read_frag(K2{}, cur, 0, g);
-            if (g < 4) { if (g & 1) lb.copy_one(nxt + TILE_BYTES, k1, 6 + (g >> 1)); else la.copy_one(nxt, k1, 6 + (g >> 1)); }
+            read_frag(K2{}, o0, o1, 0, g);
+            if (!(g & 1)) la.template copy_one<FAST>(smem + o4, k2, g >> 1);
             wait_group(G, 1);
             mfma_pair(1, g);
             __builtin_amdgcn_sched_barrier(0);
         });
-        // phase 2: fragments of slice 3
+        // phase 2: fragments of slice 3; second half of A(kt+2)
         static_for(Groups8{}, [&](auto G) {
             constexpr int g = decltype(G)::value;
-            read_frag(K3{}, cur, 1, g);
+            read_frag(K3{}, o0, o1, 1, g);
+            if (!(g & 1)) la.template copy_one<FAST>(smem + o4, k2, 4 + (g >> 1));
             wait_group(G, 0);
             mfma_pair(0, g);
             __builtin_amdgcn_sched_barrier(0);
         });
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // tile kt+1 has landed in the other slot
-        lds_barrier();                                         // and nobody reads this slot any more
-        // phase 3 (hand-over): fragments of slice 0 of tile kt+1; tile kt+2 starts to fill the released slot.
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");       // A(kt+1) and B(kt+1) have landed
+        lds_barrier();                                         // and nobody reads A(kt), B(kt) any more
+        // phase 3: fragments of slice 0 of tile kt+1; first half of B(kt+2) into the slot A(kt) had.
         // The barrier has waited for every LDS read, so this phase's MFMAs need no wait of their own.
         static_for(Groups8{}, [&](auto G) {
             constexpr int g = decltype(G)::value;
-            read_frag(K0{}, nxt, 0, g);
-            if (g < 6) { if (g & 1) lb.copy_one(cur + TILE_BYTES, k2, g >> 1); else la.copy_one(cur, k2, g >> 1); }
+            read_frag(K0{}, o2, o3, 0, g);
+            if (!(g & 1)) lb.template copy_one<FAST>(smem + o0, k2, g >> 1);
             if (ASM_READS && g == 0)       // ties the MFMAs below to this side of the barrier
                 asm volatile("" : "+v"(fa[1][0]), "+v"(fa[1][1]), "+v"(fa[1][2]), "+v"(fa[1][3]),
                                   "+v"(fb[1][0]), "+v"(fb[1][1]), "+v"(fb[1][2]), "+v"(fb[1][3]));
             mfma_pair(1, g);
             __builtin_amdgcn_sched_barrier(0);
         });
-    }
+        { const int t0 = o0, t1 = o1; o0 = o2; o1 = o3; o2 = o4; o3 = t0; o4 = t1; }
+    };
+    // copies of a step reach up to K tile kt+2: the unchecked form needs that tile inside the matrix
+    const int nk_fast = full_tiles ? max(p.K / BK - 2, 0) : 0;
+    for (int kt = 0; kt < nk_fast; ++kt) step(std::true_type{}, kt);
+    for (int kt = nk_fast; kt < nk; ++kt) step(std::false_type{}, kt);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // copies past the end of K (zero-filled) are done
     if (ASM_READS) {
         // the last phase's reads (never used) still target these registers: keep them reserved until they land
