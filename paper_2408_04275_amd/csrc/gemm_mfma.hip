@@ -189,32 +189,36 @@ __device__ __forceinline__ bf16x8 lds_read_tr(uint32_t addr) {
     const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return *reinterpret_cast<const bf16x8 *>(&v);
 }
+template <int OFF>
 __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
     bf16x8 v;
-    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
     return v;
 }
-// Fragments of a k-slice are read in the order B0 A0 B1 B2 B3 A1 A2 A3, one per MFMA group, one slice
-// ahead.  MFMA group g needs the previous slice's fragments up to position need[g]; LDS reads return in
-// order, so it may proceed once at most this many LDS instructions are outstanding: the previous slice's
-// reads behind that position plus this slice's reads issued so far (groups 0..g).
+// The 16 fragments of a 32-deep k-slice (8 of A, 8 of B, 16 rows each) are read in the order
+// A0 B0 .. B7 A1 .. A7, one per MFMA group, one slice ahead.  MFMA group g of a slice (row block g >> 1
+// of A against four of the B fragments) needs the fragments up to position need(g); LDS reads return in
+// order, so the group may proceed once at most this many LDS instructions are outstanding: the previous
+// slice's reads behind that position plus this slice's reads issued so far (groups 0..g).  The counter
+// holds 15 at most.
+constexpr int frag_is_a(int f) { return f == 0 || f >= 9; }
+constexpr int frag_index(int f) { return f == 0 ? 0 : f <= 8 ? f - 1 : f - 8; }
 template <bool A_KC, bool B_KC>
 constexpr int lgkm_allowed(int g) {
     const int ca = A_KC ? 1 : 2, cb = B_KC ? 1 : 2;
-    const int cnt[8] = {cb, ca, cb, cb, cb, ca, ca, ca};
-    const int need[8] = {2, 4, 5, 5, 6, 6, 7, 7};
+    const int need = g == 0 ? 4 : g == 1 ? 8 : 8 + (g >> 1);
     int n = 0;
-    for (int i = need[g] + 1; i < 8; ++i) n += cnt[i];
-    for (int i = 0; i <= g; ++i) n += cnt[i];
-    return n;
+    for (int f = need + 1; f < 16; ++f) n += frag_is_a(f) ? ca : cb;
+    for (int f = 0; f <= g; ++f) n += frag_is_a(f) ? ca : cb;
+    return n < 15 ? n : 15;
 }
 template <int N>
-__device__ __forceinline__ void wait_frags(bf16x8 &a, bf16x8 &b, bf16x8 &c) {
-    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(N));
+__device__ __forceinline__ void wait_frags(bf16x8 &a, bf16x8 &b, bf16x8 &c, bf16x8 &d, bf16x8 &e) {
+    asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e) : "n"(N));
 }
 template <int N>
-__device__ __forceinline__ void wait_frags(bf16x8 &a, bf16x8 &b) {
-    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+__device__ __forceinline__ void wait_frags(bf16x8 &a, bf16x8 &b, bf16x8 &c, bf16x8 &d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }
 template <int N>
 __device__ __forceinline__ void wait_frags(bf16x8 &a) {
@@ -224,7 +228,6 @@ template <int... I, class F>
 __device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F &&f) {
     (f(std::integral_constant<int, I>{}), ...);
 }
-typedef std::make_integer_sequence<int, 8> Groups8;
 
 template <bool KC> struct LoaderSel { typedef LoaderKC type; };
 template <> struct LoaderSel<false> { typedef LoaderKS type; };
@@ -246,26 +249,24 @@ void gemm_mfma_kernel(const GemmP p) {
     const int run_end = run_begin + per + (xcd < rem ? 1 : 0);
     const int wg_per_xcd = (gridDim.x - xcd + 7) >> 3;
 
-    // fragment addressing.  K-contiguous tile: lane reads row (lane & 31) of a 32-row block, unit
-    // ks*2 + (lane >> 5).  K-strided tile: 16-lane group gq = lane >> 4 forms the fragment of rows
-    // 16 (gq & 1) .. + 15, k-half gq >> 1; its lane j supplies the address of k-row (j >> 2), rows 4 (j & 3) .. + 3.
-    const int frow = lane & 31, fhalf = lane >> 5;
-    // a_rd[i][ks]: offset inside an A tile of the fragment of row block i, k-slice ks (K-strided tiles need
-    // one per block only: the slice is an immediate offset of the read)
-    int a_rd[4][A_KC ? 4 : 1], b_rd[4][B_KC ? 4 : 1];
+    // fragment addressing (v_mfma_f32_16x16x32_bf16: lane l holds row l & 15, k = 8 (l >> 4) .. + 7 of a
+    // 16-row, 32-deep fragment).  K-contiguous tile: row block i, slice s -> row 16 i + (l & 15), unit
+    // 4 s + (l >> 4); the swizzle of that row is that of row (l & 15) xor (2 i & 7), so 4 x 2 offsets per
+    // operand cover all blocks and slices, the block itself being an immediate offset of the read (for odd
+    // pairs of blocks, where 2 i & 7 repeats, only the immediate differs).  K-strided tile: the 16 lanes with
+    // the same l >> 4 form rows 0..15 of the block at k = 8 (l >> 4) ..; lane j of them supplies the address
+    // of k-row (j >> 2), rows 4 (j & 3) .. + 3, for each of the two transposing reads.
+    const int frow = lane & 15, fq = lane >> 4;
+    int a_rd[4][2], b_rd[4][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int ra = wm * 128 + i * 32 + frow, rb = wn * 128 + i * 32 + frow;
-        const int gq = lane >> 4, j = lane & 15;
-        const int tr_k = (8 * (gq >> 1) + (j >> 2)) * 512 + (j & 3) * 8;
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (A_KC) a_rd[i][ks] = ra * 128 + (((ks * 2 + fhalf) ^ swz(ra)) << 4);
-            if (B_KC) b_rd[i][ks] = rb * 128 + (((ks * 2 + fhalf) ^ swz(rb)) << 4);
+        for (int sl = 0; sl < 2; ++sl) {
+            if (A_KC) a_rd[c][sl] = (wm * 128 + frow) * 128 + (((sl * 4 + fq) ^ swz(wm * 128 + frow) ^ (2 * c)) << 4);
+            else a_rd[c][sl] = (sl * 32 + 8 * fq + (frow >> 2)) * 512 + (frow & 3) * 8 + ((wm * 8 + c) ^ (frow >> 2)) * 32;
+            if (B_KC) b_rd[c][sl] = (wn * 128 + frow) * 128 + (((sl * 4 + fq) ^ swz(wn * 128 + frow) ^ (2 * c)) << 4);
+            else b_rd[c][sl] = (sl * 32 + 8 * fq + (frow >> 2)) * 512 + (frow & 3) * 8 + ((wn * 8 + c) ^ (frow >> 2)) * 32;
         }
-        if (!A_KC) a_rd[i][0] = tr_k + ((((wm * 128 + i * 32) >> 4) + (gq & 1)) ^ (j >> 2)) * 32;
-        if (!B_KC) b_rd[i][0] = tr_k + ((((wn * 128 + i * 32) >> 4) + (gq & 1)) ^ (j >> 2)) * 32;
-    }
 
     for (int logical = run_begin + q; logical < run_end; logical += wg_per_xcd) {
     int tm, tn;
@@ -283,126 +284,115 @@ void gemm_mfma_kernel(const GemmP p) {
     la.init(p.A, p.lda, m0, p.M, p.K);
     lb.init(p.B, p.ldb, n0, p.N, p.K);
 
-    f32x16 acc[4][4];
+    f32x4 acc[8][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-    bf16x8 fa[2][4], fb[2][4];
-    // fragment g of 8 of k-slice ks: B0 A0 B1 B2 B3 A1 A2 A3 (what the first MFMAs of a slice need comes first)
+    bf16x8 fa[2][8], fb[2][8];
     // Kernels with a K-strided operand read all their fragments as assembly (see lds_read_tr) and wait for
     // them explicitly; the all-K-contiguous kernel leaves reads and waits to the compiler.
     constexpr bool ASM_READS = !(A_KC && B_KC);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void *)smem;
-    auto read_frag = [&](auto KS, int ta, int tb, int buf, int g) {      // ta, tb: LDS offsets of the A and B tiles
-        constexpr int ks = decltype(KS)::value;
-        const bool is_a = g == 1 || g >= 5;
-        const int i = g == 0 ? 0 : g == 1 ? 0 : g <= 4 ? g - 1 : g - 4;
-        if (!ASM_READS) {
-            if (is_a) fa[buf][i] = *reinterpret_cast<const bf16x8 *>(smem + ta + a_rd[i][A_KC ? ks : 0]);
-            else fb[buf][i] = *reinterpret_cast<const bf16x8 *>(smem + tb + b_rd[i][B_KC ? ks : 0]);
+    // fragment f of 16 of slice SL (0, 1) of the tiles at LDS offsets ta, tb, into fragment buffer buf
+    auto read_frag = [&](auto SL, auto F, int ta, int tb, int buf) {
+        constexpr int sl = decltype(SL)::value, f = decltype(F)::value;
+        constexpr bool is_a = frag_is_a(f);
+        constexpr int i = frag_index(f);
+        // K-contiguous: blocks i and i ^ 4 share the swizzle term; K-strided: one offset per pair (wave half, block)
+        constexpr int kc_imm = i * 16 * 128, c_kc = i & 3;
+        constexpr int ks_imm = (i >> 2) * 4 * 32, c_ks = i & 3;     // chunk (wm * 8 + i): bits 0..1 in the offset, bit 2 immediate
+        if (is_a) {
+            if (A_KC) {
+                if (!ASM_READS) fa[buf][i] = *reinterpret_cast<const bf16x8 *>(smem + ta + a_rd[c_kc][sl] + kc_imm);
+                else fa[buf][i] = lds_read_b128<kc_imm>(lds0 + ta + a_rd[c_kc][sl]);
+            } else fa[buf][i] = lds_read_tr<ks_imm>(lds0 + ta + a_rd[c_ks][sl]);
         } else {
-            if (is_a) {
-                if (A_KC) fa[buf][i] = lds_read_b128(lds0 + ta + a_rd[i][A_KC ? ks : 0]);
-                else fa[buf][i] = lds_read_tr<ks * 16 * 512>(lds0 + ta + a_rd[i][0]);
-            } else {
-                if (B_KC) fb[buf][i] = lds_read_b128(lds0 + tb + b_rd[i][B_KC ? ks : 0]);
-                else fb[buf][i] = lds_read_tr<ks * 16 * 512>(lds0 + tb + b_rd[i][0]);
-            }
+            if (B_KC) {
+                if (!ASM_READS) fb[buf][i] = *reinterpret_cast<const bf16x8 *>(smem + tb + b_rd[c_kc][sl] + kc_imm);
+                else fb[buf][i] = lds_read_b128<kc_imm>(lds0 + tb + b_rd[c_kc][sl]);
+            } else fb[buf][i] = lds_read_tr<ks_imm>(lds0 + tb + b_rd[c_ks][sl]);
         }
     };
-    // before MFMA group g of a slice held in fragment buffer `buf`
+    // before MFMA group g (0..15) of a slice held in fragment buffer `buf`
     auto wait_group = [&](auto G, int buf) {
         constexpr int g = decltype(G)::value;
         constexpr int n = lgkm_allowed<A_KC, B_KC>(g);
         if (!ASM_READS) return;
-        if (g == 0) wait_frags<n>(fb[buf][0], fa[buf][0], fb[buf][1]);
-        else if (g == 1) wait_frags<n>(fb[buf][2], fb[buf][3]);
-        else if (g == 2) wait_frags<n>(fa[buf][1]);
-        else if (g == 4) wait_frags<n>(fa[buf][2]);
-        else if (g == 6) wait_frags<n>(fa[buf][3]);
+        if (g == 0) wait_frags<n>(fa[buf][0], fb[buf][0], fb[buf][1], fb[buf][2], fb[buf][3]);
+        else if (g == 1) wait_frags<n>(fb[buf][4], fb[buf][5], fb[buf][6], fb[buf][7]);
+        else if (!(g & 1)) wait_frags<n>(fa[buf][g >> 1]);
     };
-    // MFMA pair g of 8 of a k-slice: accumulator tiles (i, j) = (g >> 1, 2 (g & 1)) and (g >> 1, 2 (g & 1) + 1).
+    // MFMA group g of 16 of a k-slice: row block i = g >> 1 of A against B blocks 4 (g & 1) .. + 3.
     // Operands are swapped: the accumulator tile is held transposed (lane = m, registers run over n),
-    // so that each lane owns 4 consecutive n per register quad for the epilogue.
-    auto mfma_pair = [&](int buf, int g) {
-        const int i = g >> 1, j = 2 * (g & 1);
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
-        acc[i][j + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j + 1], fa[buf][i], acc[i][j + 1], 0, 0, 0);
+    // so that each lane owns 4 consecutive n of one row for the epilogue.  The instruction is written out
+    // with the accumulator tied to itself in the accumulation registers: left to the register allocator,
+    // the 64 four-register accumulators are shuffled between registers in every iteration.  An
+    // accumulator is touched again only 64 MFMAs later, and the code after the K loop starts with waits
+    // and a barrier, so none of the software-managed MFMA hazards can occur.
+    auto mfma_group = [&](int buf, int g) {
+        const int i = g >> 1, j = 4 * (g & 1);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j + t]) : "v"(fb[buf][j + t]), "v"(fa[buf][i]));
     };
 
     // Software pipeline, one barrier per 64-deep K step.  The operand tiles A0 B0 A1 B1 A2 B2 ... go round
-    // a ring of five 32 KiB slots.  Step kt multiplies K tile kt in four k-slices (phases); the fragments of
-    // a slice are read one slice ahead.  After the third phase every wavefront has read all of A(kt) and
-    // B(kt), so past that step's barrier their two slots are handed to B(kt+2) and A(kt+3).  Between two
-    // barriers a wavefront issues the 8 copies of one B tile and then the 8 copies of one A tile, one in
-    // every second MFMA group: the compute unit's address path takes about 20 cycles per 1 KiB copy, and
-    // four wavefronts issuing one in every group (64 cycles) would back it up and stall the MFMAs behind
-    // it.  At the barrier of step kt the tiles A(kt+1) (copied during the previous step) and B(kt+1) (copied
-    // in the first half of this interval) must have landed; the 8 youngest copies (of A(kt+2)) may still be
-    // in flight (vmcnt(8): memory operations retire in issue order).  A copy thus has between two and six
-    // phases to land, against about one phase of L2 latency.
+    // a ring of five 32 KiB slots.  Step kt multiplies K tile kt in two 32-deep k-slices of 16 MFMA groups
+    // (4 MFMAs = 64 cycles each); every group also reads one fragment of the following slice, so after the
+    // first slice every wavefront has read all of A(kt) and B(kt): past the barrier in the middle of the
+    // step their two slots are handed to B(kt+2) and A(kt+3), and the second slice's groups read the first
+    // slice of tile kt+1.  Between two barriers a wavefront issues the 8 copies of one B tile and then the 8
+    // copies of one A tile, one in every second MFMA group: the compute unit's address path takes about 20
+    // cycles per 1 KiB copy, and four wavefronts issuing one in every group would back it up and stall
+    // the MFMAs behind it.  At the barrier of step kt the tiles A(kt+1) (copied during the previous step)
+    // and B(kt+1) (copied in the first half of this interval) must have landed; the 8 youngest copies (of
+    // A(kt+2)) may still be in flight (vmcnt(8): memory operations retire in issue order).  A copy thus
+    // has between one and three slices to land, against about half a slice of L2 latency.
     const int nk = (p.K + BK - 1) / BK;
-    typedef std::integral_constant<int, 0> K0;
-    typedef std::integral_constant<int, 1> K1;
-    typedef std::integral_constant<int, 2> K2;
-    typedef std::integral_constant<int, 3> K3;
+    typedef std::integral_constant<int, 0> S0;
+    typedef std::integral_constant<int, 1> S1;
+    typedef std::make_integer_sequence<int, 16> Groups16;
     la.copy_items(smem + 0 * TILE_BYTES, 0, 0, 8);
     lb.copy_items(smem + 1 * TILE_BYTES, 0, 0, 8);
     la.copy_items(smem + 2 * TILE_BYTES, BK, 0, 8);
-    lb.copy_items(smem + 3 * TILE_BYTES, BK, 0, 4);
-    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");         // A0 and B0 have landed
+    lb.copy_items(smem + 3 * TILE_BYTES, BK, 0, 8);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");         // A0 and B0 have landed
     lds_barrier();
-    static_for(Groups8{}, [&](auto G) { read_frag(K0{}, 0, TILE_BYTES, 0, decltype(G)::value); });
+    static_for(Groups16{}, [&](auto G) { read_frag(S0{}, G, 0, TILE_BYTES, 0); });
 
     // LDS offsets of the slots that hold tiles 2kt .. 2kt+4 of the ring (A(kt), B(kt), A(kt+1), B(kt+1), A(kt+2))
     int o0 = 0, o1 = TILE_BYTES, o2 = 2 * TILE_BYTES, o3 = 3 * TILE_BYTES, o4 = 4 * TILE_BYTES;
     const bool full_tiles = la.full && lb.full;
     auto step = [&](auto FAST_, int kt) {
         constexpr bool FAST = decltype(FAST_)::value;
-        const int k1 = (kt + 1) * BK, k2 = (kt + 2) * BK;
-        // phase 0: fragments of slice 1; second half of B(kt+1)
-        static_for(Groups8{}, [&](auto G) {
+        const int k2 = (kt + 2) * BK;
+        // first slice: fragments of the second slice; A(kt+2) into the slot B(kt-1) had
+        static_for(Groups16{}, [&](auto G) {
             constexpr int g = decltype(G)::value;
-            read_frag(K1{}, o0, o1, 1, g);
-            if (!(g & 1)) lb.template copy_one<FAST>(smem + o3, k1, 4 + (g >> 1));
-            wait_group(G, 0);
-            mfma_pair(0, g);
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        // phase 1: fragments of slice 2; first half of A(kt+2)
-        static_for(Groups8{}, [&](auto G) {
-            constexpr int g = decltype(G)::value;
-            read_frag(K2{}, o0, o1, 0, g);
+            read_frag(S1{}, G, o0, o1, 1);
             if (!(g & 1)) la.template copy_one<FAST>(smem + o4, k2, g >> 1);
-            wait_group(G, 1);
-            mfma_pair(1, g);
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        // phase 2: fragments of slice 3; second half of A(kt+2)
-        static_for(Groups8{}, [&](auto G) {
-            constexpr int g = decltype(G)::value;
-            read_frag(K3{}, o0, o1, 1, g);
-            if (!(g & 1)) la.template copy_one<FAST>(smem + o4, k2, 4 + (g >> 1));
             wait_group(G, 0);
-            mfma_pair(0, g);
+            mfma_group(0, g);
             __builtin_amdgcn_sched_barrier(0);
         });
         asm volatile("s_waitcnt vmcnt(8)" ::: "memory");       // A(kt+1) and B(kt+1) have landed
         lds_barrier();                                         // and nobody reads A(kt), B(kt) any more
-        // phase 3: fragments of slice 0 of tile kt+1; first half of B(kt+2) into the slot A(kt) had.
-        // The barrier has waited for every LDS read, so this phase's MFMAs need no wait of their own.
-        static_for(Groups8{}, [&](auto G) {
+        // second slice: fragments of the first slice of tile kt+1; B(kt+2) into the slot A(kt) had.
+        // The barrier has waited for every LDS read, so this slice's MFMAs need no wait of their own.
+        static_for(Groups16{}, [&](auto G) {
             constexpr int g = decltype(G)::value;
-            read_frag(K0{}, o2, o3, 0, g);
+            read_frag(S0{}, G, o2, o3, 0);
             if (!(g & 1)) lb.template copy_one<FAST>(smem + o0, k2, g >> 1);
             if (ASM_READS && g == 0)       // ties the MFMAs below to this side of the barrier
                 asm volatile("" : "+v"(fa[1][0]), "+v"(fa[1][1]), "+v"(fa[1][2]), "+v"(fa[1][3]),
-                                  "+v"(fb[1][0]), "+v"(fb[1][1]), "+v"(fb[1][2]), "+v"(fb[1][3]));
-            mfma_pair(1, g);
+                                  "+v"(fa[1][4]), "+v"(fa[1][5]), "+v"(fa[1][6]), "+v"(fa[1][7]),
+                                  "+v"(fb[1][0]), "+v"(fb[1][1]), "+v"(fb[1][2]), "+v"(fb[1][3]),
+                                  "+v"(fb[1][4]), "+v"(fb[1][5]), "+v"(fb[1][6]), "+v"(fb[1][7]));
+            mfma_group(1, g);
             __builtin_amdgcn_sched_barrier(0);
         });
         { const int t0 = o0, t1 = o1; o0 = o2; o1 = o3; o2 = o4; o3 = t0; o4 = t1; }
@@ -411,12 +401,15 @@ void gemm_mfma_kernel(const GemmP p) {
     const int nk_fast = full_tiles ? max(p.K / BK - 2, 0) : 0;
     for (int kt = 0; kt < nk_fast; ++kt) step(std::true_type{}, kt);
     for (int kt = nk_fast; kt < nk; ++kt) step(std::false_type{}, kt);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // copies past the end of K (zero-filled) are done
+    asm volatile("s_nop 15\n\ts_waitcnt vmcnt(0)" ::: "memory");   // the last MFMAs have written their accumulators;
+                                                                  // copies past the end of K (zero-filled) are done
     if (ASM_READS) {
-        // the last phase's reads (never used) still target these registers: keep them reserved until they land
+        // the last slice's reads (never used) still target these registers: keep them reserved until they land
         asm volatile("s_waitcnt lgkmcnt(0)"
                      : "+v"(fa[0][0]), "+v"(fa[0][1]), "+v"(fa[0][2]), "+v"(fa[0][3]),
-                       "+v"(fb[0][0]), "+v"(fb[0][1]), "+v"(fb[0][2]), "+v"(fb[0][3]));
+                       "+v"(fa[0][4]), "+v"(fa[0][5]), "+v"(fa[0][6]), "+v"(fa[0][7]),
+                       "+v"(fb[0][0]), "+v"(fb[0][1]), "+v"(fb[0][2]), "+v"(fb[0][3]),
+                       "+v"(fb[0][4]), "+v"(fb[0][5]), "+v"(fb[0][6]), "+v"(fb[0][7]));
     }
     lds_barrier();
 
@@ -451,13 +444,13 @@ void gemm_mfma_kernel(const GemmP p) {
     const bool both = HAS_ADD && p.residual && p.accumulate;   // rare: the second addend is read in the store loop
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+        // accumulator tile (2 i + ii, j), register e  <->  m = 16 (2 i + ii) + (lane & 15),  n = 16 j + 4 (lane >> 4) + e
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                // accumulator register 4*gq + e  <->  n = 8*gq + 4*(lane >> 5) + e,  m = lane & 31
-                float4 v = make_float4(acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]);
-                *reinterpret_cast<float4 *>(stg + frow * EPI_PITCH + j * 32 + gq * 8 + fhalf * 4) = v;
+            for (int j = 0; j < 8; ++j) {
+                const f32x4 t = acc[2 * i + ii][j];
+                *reinterpret_cast<float4 *>(stg + (ii * 16 + frow) * EPI_PITCH + j * 16 + fq * 4) = make_float4(t[0], t[1], t[2], t[3]);
             }
         lds_wave_sync();
 #pragma unroll
