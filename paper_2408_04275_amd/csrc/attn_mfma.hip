@@ -24,6 +24,8 @@
 // keys and over the query heads of the key/value head's group, so grouped-query gradients are
 // summed in registers and nothing needs atomics: results are deterministic.
 #include "kernels.h"
+#include <type_traits>
+#include <utility>
 
 namespace mmt {
 
@@ -353,16 +355,79 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// backward: dQ (and D = rowsum(dO * O))
+// backward
+// ------------------------------------------------------------------------------------------
+// Both backward kernels walk 64-row tiles that are copied global -> LDS directly, row-major ([row][D],
+// 16-byte units XOR-swizzled by row), into two slots, the next tile being in flight while the current one
+// is multiplied.  A product whose contraction runs over the tile's rows (dQ^T = K^T dS^T, dV^T = dO^T P,
+// dK^T = Q^T dS) needs the tile transposed as its row operand; that fragment is formed from the same
+// row-major tile by the transposing LDS read (ds_read_b64_tr_b16), with the rows taken in the order in
+// which the accumulator registers of the score tile hold them.
+constexpr int BT2 = 64;
+
+typedef __attribute__((ext_vector_type(4))) short shortx4;
+typedef __attribute__((ext_vector_type(8))) short shortx8;
+
+// One wavefront's share of the copy of a [64][D] tile: copies i = 0 .. N-1 of 1 KiB each, copy (first + i)
+// of the tile covering rows (first + i) * 512 / D ...  Rows at or beyond the end of the tensor read as zero.
+template <int D, int N>
+__device__ __forceinline__ void copy_rows(__amdgpu_buffer_rsrc_t rs, uint8_t *tile, int first, long row0, long ld, long col0) {
+    constexpr int UPR = D / 8, ROWS_PER_COPY = 1024 / (2 * D);
+    const int lane = threadIdx.x & 63;
+    const int lrow = lane / UPR, pos = lane % UPR;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int r0 = (first + i) * ROWS_PER_COPY, row = r0 + lrow;
+        const int unit = (pos & ~7) | ((pos & 7) ^ swz(row));
+        const uint32_t off = (uint32_t)(((size_t)(row0 + row) * ld + col0 + unit * 8) * 2);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + r0 * 2 * D), 16, (int)off, 0, 0, 0);
+    }
+}
+
+// Transposing reads.  Lane constants: 16-lane group gq = lane >> 4 forms the fragment rows (features)
+// 16 (gq & 1) .. + 15 for lane half h = gq >> 1; as a source, lane j = lane & 15 of the group supplies
+// the address of tile row 4 h + (j >> 2) (+ a multiple of 8), features 4 (j & 3) .. + 3 of the group's 16.
+// tr_off[X] holds that address for each value X of the compile-time part of the swizzled unit position.
+template <int D>
+struct TrReader {
+    uint32_t off[8];
+    __device__ __forceinline__ void init(uint32_t lds_base) {
+        const int lane = threadIdx.x & 63, gq = lane >> 4, j = lane & 15, qd = j & 3, t = j >> 2, h = gq >> 1;
+        const int L = ((2 * (gq & 1) + (qd >> 1)) ^ (4 * h + t)) & 7;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) off[x] = lds_base + (4 * h + t) * 2 * D + (qd & 1) * 8 + ((x ^ L) << 4);
+    }
+    // half SEC (elements 4 SEC .. 4 SEC + 3) of the fragment of 32-row block B, MFMA M of the block, feature
+    // block C of a tile at byte offset `tile` from lds_base: rows 32 B + 16 M + 8 SEC + 4 h + (0..3)
+    template <int B, int M, int C, int SEC>
+    __device__ __forceinline__ shortx4 read(uint32_t tile) const {
+        constexpr int CST = (4 * B + 2 * M + SEC) & 7, X = (4 * (C & 1)) ^ CST;
+        constexpr int IMM = (32 * B + 16 * M + 8 * SEC) * 2 * D + (C >> 1) * 128;
+        shortx4 v;
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(off[X] + tile), "n"(IMM));
+        return v;
+    }
+};
+__device__ __forceinline__ bf16x8 join(shortx4 lo, shortx4 hi) {
+    const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return *reinterpret_cast<const bf16x8 *>(&v);
+}
+// The transposing reads are written as assembly because the compiler makes the builtin wait for every
+// direct-to-LDS copy in flight; their results may be used only after this wait, which names them.
+#define TR_WAIT4(x) "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])
+
+// ------------------------------------------------------------------------------------------
+// backward: dQ (and D = rowsum(dO * O)).  Same roles as the forward kernel: 8 wavefronts x 32 queries.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void attn_dq_kernel(AttnArgs a) {
+__global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     constexpr int KS = D / 16, CB = D / 32;
+    constexpr int TILE = BT2 * D * 2, SLOT = 2 * TILE;             // K tile, then V tile
+    constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                 // per wavefront (4 wavefronts per tile)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    uint8_t *sK = smem, *sKT = smem + BT * D * 2, *sV = smem + 2 * BT * D * 2;
 
     const int head = blockIdx.y, g = head / (a.nh / a.nkv);
-    const int q0 = blockIdx.x * BQ;
+    const int q0 = blockIdx.x * FQ;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
@@ -374,7 +439,7 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(AttnArgs a) {
     const bool valid = q < T;
     const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
     const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
-    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + BQ, T) - 1, T);
+    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
     const int kbeg = first.lo, kend = last.hi;
 
     bf16x8 qf[KS], dof[KS];
@@ -407,28 +472,47 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(AttnArgs a) {
     for (int c = 0; c < CB; ++c) dq[c] = zero16();
     const float sl2 = a.scale * LOG2E;
 
-    TileLoader<D> lk, lv;
-    lk.load(qkv + nq + g * D, ld, kbeg, T);
-    lv.load(qkv + nq + nk + g * D, ld, kbeg, T);
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
+    // wavefronts 4..7 copy the K tile, wavefronts 0..3 the V tile
+    auto copy_kv = [&](uint8_t *slot, int kt) {
+        if (wave >= 4) copy_rows<D, COPIES>(rs, slot, (wave - 4) * COPIES, kt, ld, nq + g * D);
+        else copy_rows<D, COPIES>(rs, slot + TILE, wave * COPIES, kt, ld, nq + nk + g * D);
+    };
+    TrReader<D> tr;
+    tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
 
-    for (int kt = kbeg; kt < kend; kt += BT) {
-        lk.store_rows(sK);
-        lk.store_transposed(sKT);
-        lv.store_rows(sV);
-        __syncthreads();
-        if (kt + BT < kend) {
-            lk.load(qkv + nq + g * D, ld, kt + BT, T);
-            lv.load(qkv + nq + nk + g * D, ld, kt + BT, T);
-        }
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
+    copy_kv(smem, kbeg);
+    int slot = 0;
+    for (int kt = kbeg; kt < kend; kt += BT2, slot ^= 1) {
+        const uint8_t *sK = smem + slot * SLOT, *sV = sK + TILE;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // this step's tiles have landed
+        lds_barrier();                                               // ... and everyone is done with the other slot
+        if (kt + BT2 < kend) copy_kv(smem + (slot ^ 1) * SLOT, kt + BT2);
+        auto block = [&](auto B_) {
+            constexpr int b = decltype(B_)::value;
             const int kb = kt + 32 * b;
-            if (!((kb < w_hi_max) && (kb + 32 > w_lo_min))) continue;
+            if (!((kb < w_hi_max) && (kb + 32 > w_lo_min))) return;
             f32x16 s = zero16(), dp = zero16();
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                s = MFMA(frag_rows<D>(sK, 32 * b + l32, ks, half), qf[ks], s);
-                dp = MFMA(frag_rows<D>(sV, 32 * b + l32, ks, half), dof[ks], dp);
+                s = MFMA(frag_k<D>(sK, 32 * b + l32, ks, half), qf[ks], s);
+                dp = MFMA(frag_k<D>(sV, 32 * b + l32, ks, half), dof[ks], dp);
+            }
+            // K^T fragments of this block: [MFMA m][feature block c], two halves each
+            shortx4 t0[4], t1[4], t2[4], t3[4];                      // (m, sec) = (0,0), (0,1), (1,0), (1,1)
+            const uint32_t tile = slot * SLOT;
+            t0[0] = tr.template read<b, 0, 0, 0>(tile); t1[0] = tr.template read<b, 0, 0, 1>(tile);
+            t2[0] = tr.template read<b, 1, 0, 0>(tile); t3[0] = tr.template read<b, 1, 0, 1>(tile);
+            t0[1] = tr.template read<b, 0, 1, 0>(tile); t1[1] = tr.template read<b, 0, 1, 1>(tile);
+            t2[1] = tr.template read<b, 1, 1, 0>(tile); t3[1] = tr.template read<b, 1, 1, 1>(tile);
+            if (CB > 2) {
+                t0[2] = tr.template read<b, 0, 2, 0>(tile); t1[2] = tr.template read<b, 0, 2, 1>(tile);
+                t2[2] = tr.template read<b, 1, 2, 0>(tile); t3[2] = tr.template read<b, 1, 2, 1>(tile);
+                t0[3] = tr.template read<b, 0, 3, 0>(tile); t1[3] = tr.template read<b, 0, 3, 1>(tile);
+                t2[3] = tr.template read<b, 1, 3, 0>(tile); t3[3] = tr.template read<b, 1, 3, 1>(tile);
+            } else {
+                t0[2] = t0[3] = t1[2] = t1[3] = t2[2] = t2[3] = t3[2] = t3[3] = shortx4{0, 0, 0, 0};
             }
             const bool inside = kb >= w_lo_max && kb + 32 <= w_hi_min;
             const unsigned span = (unsigned)(me.hi - me.lo);
@@ -440,15 +524,16 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(AttnArgs a) {
                 if (!inside) p = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? p : 0.f;
                 ds[i] = p * (dp[i] - Dq);
             }
+            asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT4(t0), TR_WAIT4(t1), TR_WAIT4(t2), TR_WAIT4(t3));
+            const bf16x8 ds0 = pack8(ds), ds1 = pack8(ds + 8);
 #pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                const bf16x8 dsf = pack8(ds + 8 * m);
-                const int u = b * 4 + m * 2 + half;
-#pragma unroll
-                for (int c = 0; c < CB; ++c) dq[c] = MFMA(frag_tr(sKT, 32 * c + l32, u), dsf, dq[c]);
+            for (int c = 0; c < CB; ++c) {
+                dq[c] = MFMA(join(t0[c], t1[c]), ds0, dq[c]);
+                dq[c] = MFMA(join(t2[c], t3[c]), ds1, dq[c]);
             }
-        }
-        __syncthreads();
+        };
+        block(std::integral_constant<int, 0>{});
+        block(std::integral_constant<int, 1>{});
     }
     if (valid) {
         bf16_t *out = (bf16_t *)a.d_qkv + (long)q * ld + head * D;
@@ -465,14 +550,15 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// backward: dK, dV.  One key per lane; loop over the query heads of the group and the query tiles.
+// backward: dK, dV.  One key per lane (4 wavefronts x 32 keys); loop over the query heads of the group and
+// over the 64-query tiles that can see the workgroup's keys.
 // ------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     constexpr int KS = D / 16, CB = D / 32;
+    constexpr int TILE = BT2 * D * 2, SLOT = 2 * TILE + 2 * BT2 * 4;   // Q tile, dO tile, lse[64], D[64]
+    constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                     // per wavefront and tile
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    uint8_t *sQ = smem, *sQT = smem + BT * D * 2, *sdO = smem + 2 * BT * D * 2, *sdOT = smem + 3 * BT * D * 2;
-    float *sLse = reinterpret_cast<float *>(smem + 4 * BT * D * 2), *sD = sLse + BT;
 
     const int g = blockIdx.y, group = a.nh / a.nkv;
     const int k0 = blockIdx.x * BQ;
@@ -507,69 +593,119 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     for (int c = 0; c < CB; ++c) { dk[c] = zero16(); dv[c] = zero16(); }
     const float sl2 = a.scale * LOG2E;
 
-    TileLoader<D> lq, ld_o;
-    for (int hh = 0; hh < group; ++hh) {
-        const int head = g * group + hh;
-        lq.load(qkv + head * D, ld, qbeg, T);
-        ld_o.load(dO + head * D, nq, qbeg, T);
-        for (int qt = qbeg; qt < qend; qt += BT) {
-            lq.store_rows(sQ);
-            lq.store_transposed(sQT);
-            ld_o.store_rows(sdO);
-            ld_o.store_transposed(sdOT);
-            if (threadIdx.x < BT) {
-                const int qq = qt + threadIdx.x;
-                sLse[threadIdx.x] = qq < T ? a.lse[(long)head * T + qq] * LOG2E : 0.f;
-                sD[threadIdx.x] = qq < T ? a.Dsum[(long)head * T + qq] : 0.f;
-            }
-            __syncthreads();
-            if (qt + BT < qend) {
-                lq.load(qkv + head * D, ld, qt + BT, T);
-                ld_o.load(dO + head * D, nq, qt + BT, T);
-            }
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int qb = qt + 32 * b;
-                if (!((qb < w_hi_max) && (qb + 32 > w_lo_min))) continue;
-                // S[q, key] and dP[q, key]: rows = queries (registers), columns = keys (lanes)
-                f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    s = MFMA(frag_rows<D>(sQ, 32 * b + l32, ks, half), kf[ks], s);
-                    dp = MFMA(frag_rows<D>(sdO, 32 * b + l32, ks, half), vf[ks], dp);
-                }
-                const bool inside = qb >= w_lo_max && qb + 32 <= w_hi_min;
-                const unsigned span = (unsigned)(me.hi - me.lo);
-                float p[16], ds[16];
-#pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    const int r0 = 32 * b + 8 * gq + 4 * half;            // 4 consecutive queries
-                    const float4 l4 = *reinterpret_cast<const float4 *>(sLse + r0);
-                    const float4 d4 = *reinterpret_cast<const float4 *>(sD + r0);
-                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int i = 4 * gq + e;
-                        float pv = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lv[e]));
-                        if (!inside) pv = (unsigned)(qt + r0 + e - me.lo) < span ? pv : 0.f;
-                        p[i] = pv;
-                        ds[i] = pv * (dp[i] - dvv[e]);
-                    }
-                }
-#pragma unroll
-                for (int m = 0; m < 2; ++m) {
-                    const bf16x8 pf = pack8(p + 8 * m), dsf = pack8(ds + 8 * m);
-                    const int u = b * 4 + m * 2 + half;
-#pragma unroll
-                    for (int c = 0; c < CB; ++c) {
-                        dv[c] = MFMA(frag_tr(sdOT, 32 * c + l32, u), pf, dv[c]);
-                        dk[c] = MFMA(frag_tr(sQT, 32 * c + l32, u), dsf, dk[c]);
-                    }
-                }
-            }
-            __syncthreads();
+    const __amdgpu_buffer_rsrc_t rs_q =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_do =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dO), 0, (int)(uint32_t)((size_t)T * nq * 2), 0x00020000);
+    // every wavefront copies a quarter of the Q tile and of the dO tile; wavefronts 0 and 1 also fetch the
+    // 64 log-sum-exps and the 64 D values of the tile's queries (4 bytes per lane; queries >= T read as 0)
+    auto copy_tile = [&](uint8_t *slot, int head, int qt) {
+        copy_rows<D, COPIES>(rs_q, slot, wave * COPIES, qt, ld, head * D);
+        copy_rows<D, COPIES>(rs_do, slot + TILE, wave * COPIES, qt, nq, head * D);
+        if (wave < 2) {
+            const float *src = (wave == 0 ? a.lse : a.Dsum) + (long)head * T;
+            const __amdgpu_buffer_rsrc_t rs_f =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(src), 0, (int)(uint32_t)((size_t)T * 4), 0x00020000);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_f, (lds_void *)(slot + 2 * TILE + wave * BT2 * 4), 4,
+                                                     (int)((qt + lane) * 4), 0, 0, 0);
         }
+    };
+    TrReader<D> tr;
+    tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
+
+    if (qbeg >= qend) goto done;      // no query sees these keys (cannot happen for a key of a segment: it sees itself)
+    {
+    // the (head, query tile) pairs form one sequence; the copy of the next pair is in flight during this one
+    const int tiles_per_head = (qend - qbeg + BT2 - 1) / BT2, n_steps = group * tiles_per_head;
+    copy_tile(smem, g * group, qbeg);
+    int slot = 0;
+    for (int step = 0; step < n_steps; ++step, slot ^= 1) {
+        const int hh = step / tiles_per_head, qt = qbeg + (step % tiles_per_head) * BT2;
+        const uint8_t *sQ = smem + slot * SLOT, *sdO = sQ + TILE;
+        const float *sLse = reinterpret_cast<const float *>(sQ + 2 * TILE), *sD = sLse + BT2;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // this step's tiles have landed
+        lds_barrier();                                               // ... and everyone is done with the other slot
+        if (step + 1 < n_steps) {
+            const int nh2 = (step + 1) / tiles_per_head, nqt = qbeg + ((step + 1) % tiles_per_head) * BT2;
+            copy_tile(smem + (slot ^ 1) * SLOT, g * group + nh2, nqt);
+        }
+        (void)hh;
+        auto block = [&](auto B_) {
+            constexpr int b = decltype(B_)::value;
+            const int qb = qt + 32 * b;
+            if (!((qb < w_hi_max) && (qb + 32 > w_lo_min))) return;
+            // S[q, key] and dP[q, key]: rows = queries (registers), columns = keys (lanes)
+            f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                s = MFMA(frag_k<D>(sQ, 32 * b + l32, ks, half), kf[ks], s);
+                dp = MFMA(frag_k<D>(sdO, 32 * b + l32, ks, half), vf[ks], dp);
+            }
+            const uint32_t tq = slot * SLOT, tdo = tq + TILE;
+            // dO^T and Q^T fragments of MFMA 0 of the block
+            shortx4 o0[4], o1[4], q0f[4], q1f[4];
+            auto read_m = [&](auto M_) {
+                constexpr int m = decltype(M_)::value;
+                o0[0] = tr.template read<b, m, 0, 0>(tdo); o1[0] = tr.template read<b, m, 0, 1>(tdo);
+                q0f[0] = tr.template read<b, m, 0, 0>(tq); q1f[0] = tr.template read<b, m, 0, 1>(tq);
+                o0[1] = tr.template read<b, m, 1, 0>(tdo); o1[1] = tr.template read<b, m, 1, 1>(tdo);
+                q0f[1] = tr.template read<b, m, 1, 0>(tq); q1f[1] = tr.template read<b, m, 1, 1>(tq);
+                if (CB > 2) {
+                    o0[2] = tr.template read<b, m, 2, 0>(tdo); o1[2] = tr.template read<b, m, 2, 1>(tdo);
+                    q0f[2] = tr.template read<b, m, 2, 0>(tq); q1f[2] = tr.template read<b, m, 2, 1>(tq);
+                    o0[3] = tr.template read<b, m, 3, 0>(tdo); o1[3] = tr.template read<b, m, 3, 1>(tdo);
+                    q0f[3] = tr.template read<b, m, 3, 0>(tq); q1f[3] = tr.template read<b, m, 3, 1>(tq);
+                } else {
+                    o0[2] = o0[3] = o1[2] = o1[3] = q0f[2] = q0f[3] = q1f[2] = q1f[3] = shortx4{0, 0, 0, 0};
+                }
+            };
+            read_m(std::integral_constant<int, 0>{});
+            const bool inside = qb >= w_lo_max && qb + 32 <= w_hi_min;
+            const unsigned span = (unsigned)(me.hi - me.lo);
+            float p[16], ds[16];
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int r0 = 32 * b + 8 * gq + 4 * half;            // 4 consecutive queries
+                const float4 l4 = *reinterpret_cast<const float4 *>(sLse + r0);
+                const float4 d4 = *reinterpret_cast<const float4 *>(sD + r0);
+                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = 4 * gq + e;
+                    float pv = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lv[e] * LOG2E));
+                    if (!inside) pv = (unsigned)(qt + r0 + e - me.lo) < span ? pv : 0.f;
+                    p[i] = pv;
+                    ds[i] = pv * (dp[i] - dvv[e]);
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT4(o0), TR_WAIT4(o1), TR_WAIT4(q0f), TR_WAIT4(q1f));
+            bf16x8 fo[4], fq[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { fo[c] = join(o0[c], o1[c]); fq[c] = join(q0f[c], q1f[c]); }
+            read_m(std::integral_constant<int, 1>{});                 // in flight during the next 2 CB MFMAs
+            {
+                const bf16x8 pf = pack8(p), dsf = pack8(ds);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) {
+                    dv[c] = MFMA(fo[c], pf, dv[c]);
+                    dk[c] = MFMA(fq[c], dsf, dk[c]);
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT4(o0), TR_WAIT4(o1), TR_WAIT4(q0f), TR_WAIT4(q1f));
+            {
+                const bf16x8 pf = pack8(p + 8), dsf = pack8(ds + 8);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) {
+                    dv[c] = MFMA(join(o0[c], o1[c]), pf, dv[c]);
+                    dk[c] = MFMA(join(q0f[c], q1f[c]), dsf, dk[c]);
+                }
+            }
+        };
+        block(std::integral_constant<int, 0>{});
+        block(std::integral_constant<int, 1>{});
     }
+    }
+done:
     if (valid) {
         bf16_t *okp = (bf16_t *)a.d_qkv + (long)key * ld + nq + g * D;
         bf16_t *ovp = okp + nk;
@@ -609,7 +745,7 @@ hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
 template <int D>
 hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
-    const int smem_dq = 3 * BT * D * 2, smem_dkv = 4 * BT * D * 2 + 2 * BT * 4;
+    const int smem_dq = 2 * 2 * BT2 * D * 2, smem_dkv = 2 * (2 * BT2 * D * 2 + 2 * BT2 * 4);
     if (!configured) {
         hipError_t e = set_smem(attn_dq_kernel<D>, smem_dq);
         if (e != hipSuccess) return e;
@@ -617,7 +753,7 @@ hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    attn_dq_kernel<D><<<dim3(ceil_div(a.T, BQ), a.nh), 256, smem_dq, st>>>(a);
+    attn_dq_kernel<D><<<dim3(ceil_div(a.T, FQ), a.nh), 512, smem_dq, st>>>(a);
     attn_dkv_kernel<D><<<dim3(ceil_div(a.T, BQ), a.nkv), 256, smem_dkv, st>>>(a);
     return hipGetLastError();
 }
