@@ -478,7 +478,9 @@ void gemm_mfma_kernel(const GemmP p) {
                 uint4 o;
                 o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
                 o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
-                *reinterpret_cast<uint4 *>(p.C + off) = o;
+                // streaming store: the output is not read again by this kernel, so it should not displace
+                // operand panels from the L2
+                __builtin_nontemporal_store(*reinterpret_cast<const rawx4 *>(&o), reinterpret_cast<rawx4 *>(p.C + off));
             }
         }
         lds_wave_sync();
