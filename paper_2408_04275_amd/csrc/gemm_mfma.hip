@@ -461,8 +461,10 @@ void gemm_mfma_kernel(const GemmP p) {
                 const float4 v0 = *reinterpret_cast<const float4 *>(stg + r * EPI_PITCH + ec);
                 const float4 v1 = *reinterpret_cast<const float4 *>(stg + r * EPI_PITCH + ec + 4);
                 float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+                if (p.bias) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] += bv[e];
+                    for (int e = 0; e < 8; ++e) v[e] += bv[e];
+                }
                 const size_t off = (size_t)gm * p.ldc + gn;
                 if (HAS_ADD) {
                     const uint32_t w[4] = {add[i][pass].x, add[i][pass].y, add[i][pass].z, add[i][pass].w};
