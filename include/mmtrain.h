@@ -198,6 +198,21 @@ MMTRAIN_API int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_b
                      const void *o, const float *lse, const void *d_o, void *d_qkv,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Intra-microbatch reordering (Algorithm 1, Section "Intra-microbatch Reordering"): greedy multiway
+ * partitioning of n samples over m data-parallel groups.  The samples are sorted by size in descending
+ * order (equal sizes keep their original order) and handed out one by one to the group whose load is
+ * currently the smallest (the lowest index among equals, which is what the paper's worked example
+ * 1 2 3 4 -> 1 3 2 4 requires); the groups are then concatenated.
+ *   sizes        host, [n]: cost of each sample, finite and >= 0 (tokens, or a time from a cost model such
+ *                as a * tokens + b * attention pairs fitted to this library's measured step time)
+ *   order        host, [n], out: order[p] = index of the sample at position p of the reordered batch
+ *   group_begin  host, [m + 1], out, may be NULL: group j holds positions group_begin[j] .. group_begin[j+1]-1
+ *   group_load   host, [m], out, may be NULL: sum of the sizes in each group
+ * Host memory only, no GPU call, no allocation retained.  Returns MMTRAIN_OK, or MMTRAIN_ERR_INVALID_ARG
+ * (n < 0, m <= 0, NULL sizes / order with n > 0, a negative, infinite or NaN size); nothing is written then. */
+MMTRAIN_API int mmtrain_intra_reorder(const double *sizes, int32_t n, int32_t m, int32_t *order,
+                                      int32_t *group_begin, double *group_load);
+
 #ifdef __cplusplus
 }
 #endif

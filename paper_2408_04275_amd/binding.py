@@ -25,7 +25,7 @@ GEMM_ACCUMULATE = 1
 
 EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_layer_fwd", "mmtrain_layer_bwd",
            "mmtrain_status_string", "mmtrain_gemm", "mmtrain_attn_workspace_bytes", "mmtrain_attn_fwd",
-           "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read")
+           "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read", "mmtrain_intra_reorder")
 PROF_GEMM_NT, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD = range(5)
 
 WEIGHT_FIELDS = ("norm1_w", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
@@ -88,6 +88,8 @@ def load_library() -> C.CDLL:
     lib.mmtrain_profile_enable.argtypes = [C.c_int]
     lib.mmtrain_profile_read.restype = C.c_int
     lib.mmtrain_profile_read.argtypes = [I, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+    lib.mmtrain_intra_reorder.restype = C.c_int
+    lib.mmtrain_intra_reorder.argtypes = [P, I, I, P, P, P]
     _lib = lib
     return lib
 
@@ -157,6 +159,19 @@ def make_grads(tensors: Dict[str, object]) -> Grads:
 # ----------------------------------------------------------------------------
 def mmtrain_status_string(status: int) -> str:
     return load_library().mmtrain_status_string(status).decode()
+
+
+def mmtrain_intra_reorder(sizes, m: int):
+    """Algorithm 1 through the C ABI.  Returns (status, order[n], group_begin[m+1], group_load[m]) as numpy arrays."""
+    import numpy as np
+    sizes = np.ascontiguousarray(sizes, dtype=np.float64)
+    n = int(sizes.shape[0])
+    order = np.full(n, -1, dtype=np.int32)
+    begin = np.full(max(m, 0) + 1, -1, dtype=np.int32)
+    load = np.zeros(max(m, 0), dtype=np.float64)
+    rc = load_library().mmtrain_intra_reorder(sizes.ctypes.data if n else None, n, m, order.ctypes.data if n else None,
+                                              begin.ctypes.data, load.ctypes.data if m > 0 else None)
+    return rc, order, begin, load
 
 
 def mmtrain_layer_ctx_bytes(desc: Optional[LayerDesc], total_tokens: int) -> int:

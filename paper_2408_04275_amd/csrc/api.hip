@@ -144,6 +144,7 @@ AttnArgs mk_attn(const Dims &D, const mmtrain_batch *b, const Ctx &c) {
     a.T = b->total_tokens; a.S = b->n_segments; a.nh = D.nh; a.nkv = D.nkv; a.d = D.d; a.scale = D.scale;
     a.cu = b->cu_seqlens_dev; a.modes = b->seg_mask_dev; a.default_mode = b->mask_mode;
     a.tok_seg = c.tok_seg; a.tok_info = c.tok_info; a.qkv = c.qkv; a.ld_qkv = D.nqkv; a.o = c.o; a.lse = c.lse;
+    attn_tile_order(b->cu_seqlens_host, b->seg_mask_host, b->mask_mode, b->n_segments, b->total_tokens, a);
     return a;
 }
 
@@ -432,6 +433,7 @@ static int attn_common(const mmtrain_layer_desc *desc, const mmtrain_batch *batc
     a.T = T; a.S = batch->n_segments; a.nh = D.nh; a.nkv = D.nkv; a.d = D.d; a.scale = D.scale;
     a.cu = batch->cu_seqlens_dev; a.modes = batch->seg_mask_dev; a.default_mode = batch->mask_mode;
     a.tok_seg = tok_seg; a.tok_info = tok_info; a.ld_qkv = D.nqkv; a.Dsum = Dsum;
+    attn_tile_order(batch->cu_seqlens_host, batch->seg_mask_host, batch->mask_mode, batch->n_segments, T, a);
     HIP_TRY(prep_tokens(batch->cu_seqlens_dev, batch->seg_mask_dev, batch->mask_mode, batch->n_segments, T, tok_seg, tok_info,
                         D.d, 0.f, nullptr, st));
     return MMTRAIN_OK;
@@ -461,6 +463,15 @@ int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch,
     if (!qkv || !o || !lse || !d_o || !d_qkv) return MMTRAIN_ERR_INVALID_ARG;
     a.qkv = qkv; a.o = const_cast<void *>(o); a.lse = const_cast<float *>(lse); a.d_o = d_o; a.d_qkv = d_qkv;
     HIP_TRY(attn_bwd(D.dtype, a, st));
+    return MMTRAIN_OK;
+}
+
+int mmtrain_intra_reorder(const double *sizes, int32_t n, int32_t m, int32_t *order, int32_t *group_begin,
+                          double *group_load) {
+    if (n < 0 || m <= 0 || (n > 0 && (!sizes || !order))) return MMTRAIN_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i)
+        if (!(sizes[i] >= 0.0) || sizes[i] > 1e300) return MMTRAIN_ERR_INVALID_ARG;     // also rejects NaN
+    intra_reorder(sizes, n, m, order, group_begin, group_load);
     return MMTRAIN_OK;
 }
 

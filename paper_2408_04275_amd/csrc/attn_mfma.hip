@@ -188,8 +188,9 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     constexpr int V_TASKS = 8 * UPR * 2;                            // (unit, 8-feature block, half of the unit's keys)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
-    const int head = blockIdx.y, g = head / (a.nh / a.nkv);
-    const int q0 = blockIdx.x * FQ;
+    // grid: x = head, y = position in the dispatch order of the query tiles (heaviest first)
+    const int head = blockIdx.x, g = head / (a.nh / a.nkv);
+    const int q0 = (a.use_order ? a.order_q[blockIdx.y] : blockIdx.y) * FQ;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
@@ -426,8 +427,9 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                 // per wavefront (4 wavefronts per tile)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
-    const int head = blockIdx.y, g = head / (a.nh / a.nkv);
-    const int q0 = blockIdx.x * FQ;
+    // grid: x = head, y = position in the dispatch order of the query tiles (heaviest first)
+    const int head = blockIdx.x, g = head / (a.nh / a.nkv);
+    const int q0 = (a.use_order ? a.order_q[blockIdx.y] : blockIdx.y) * FQ;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
@@ -560,8 +562,9 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                     // per wavefront and tile
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
-    const int g = blockIdx.y, group = a.nh / a.nkv;
-    const int k0 = blockIdx.x * BQ;
+    // grid: x = key/value head, y = position in the dispatch order of the key tiles (heaviest first)
+    const int g = blockIdx.x, group = a.nh / a.nkv;
+    const int k0 = (a.use_order ? a.order_k[blockIdx.y] : blockIdx.y) * BQ;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
@@ -738,7 +741,7 @@ hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    attn_fwd_kernel<D><<<dim3(ceil_div(a.T, FQ), a.nh), 512, smem, st>>>(a);
+    attn_fwd_kernel<D><<<dim3(a.nh, ceil_div(a.T, FQ)), 512, smem, st>>>(a);
     return hipGetLastError();
 }
 
@@ -753,8 +756,8 @@ hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    attn_dq_kernel<D><<<dim3(ceil_div(a.T, FQ), a.nh), 512, smem_dq, st>>>(a);
-    attn_dkv_kernel<D><<<dim3(ceil_div(a.T, BQ), a.nkv), 256, smem_dkv, st>>>(a);
+    attn_dq_kernel<D><<<dim3(a.nh, ceil_div(a.T, FQ)), 512, smem_dq, st>>>(a);
+    attn_dkv_kernel<D><<<dim3(a.nkv, ceil_div(a.T, BQ)), 256, smem_dkv, st>>>(a);
     return hipGetLastError();
 }
 

@@ -44,7 +44,15 @@ struct AttnArgs {
     float *Dsum;                // bwd scratch: [nh, T]
     // MFMA path: tok_info[t] = {segment start, segment end | (bidirectional ? 1 << 30 : 0)}
     const int2 *tok_info;
+    // MFMA path: dispatch order of the query tiles (256 queries: forward, dQ) and of the key tiles (128
+    // keys: dK/dV), heaviest first; use_order = 0 means index order (more tiles than the tables hold)
+    int use_order;
+    uint8_t order_q[64];
+    uint8_t order_k[128];
 };
+// reorder.hip (host): Algorithm 1 and the tile orders above
+int intra_reorder(const double *sizes, int n, int m, int32_t *order, int32_t *group_begin, double *group_load);
+void attn_tile_order(const int32_t *cu_host, const uint8_t *modes_host, int default_mode, int S, int T, AttnArgs &a);
 // attn_simple.hip: fp32 arithmetic on the vector ALUs, any storage dtype
 hipError_t attn_simple_fwd(int dtype, const AttnArgs &a, hipStream_t st);
 hipError_t attn_simple_bwd(int dtype, const AttnArgs &a, hipStream_t st);
