@@ -342,11 +342,13 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     }
     AttnArgs a = mk_attn(D, batch, c);
     a.d_o = w.d_o; a.d_qkv = w.d_qkv; a.Dsum = w.Dsum;
+    const bool fused_unrotate = !enc && D.dtype == DT_BF16;       // the matrix-core kernels rotate dQ, dK back themselves
+    if (fused_unrotate) a.rope_cs = c.rope_cs;
     {
         ProfScope ps(MMTRAIN_PROF_ATTN_BWD, st);
         HIP_TRY(attn_bwd(D.dtype, a, st));
     }
-    if (!enc) HIP_TRY(rope_inplace(D.dtype, w.d_qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, true, st));
+    if (!enc && !fused_unrotate) HIP_TRY(rope_inplace(D.dtype, w.d_qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, true, st));
     if (enc && G.b_qkv) {
         HIP_TRY(colsum_partials(D.dtype, w.d_qkv, T, D.nqkv, D.nqkv, w.part_c, st));
         HIP_TRY(reduce_partials(D.dtype, w.part_c, ns, D.nqkv, G.b_qkv, accum, st));

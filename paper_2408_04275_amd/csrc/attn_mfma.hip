@@ -417,6 +417,27 @@ __device__ __forceinline__ bf16x8 join(shortx4 lo, shortx4 hi) {
 // direct-to-LDS copy in flight; their results may be used only after this wait, which names them.
 #define TR_WAIT4(x) "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])
 
+// Inverse rotary embedding of a gradient held in accumulator layout (the backward pass of the rotation that
+// was applied to q and k before the attention): feature f < D/2 pairs with f + D/2, which sit in the same
+// lane and register index of accumulators c and c + CB/2.  cs = the (cos, sin) row of this lane's token.
+template <int CB>
+__device__ __forceinline__ void unrotate(f32x16 (&g)[CB], const float2 *cs, int half) {
+#pragma unroll
+    for (int c = 0; c < CB / 2; ++c)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const float4 *p4 = reinterpret_cast<const float4 *>(cs + 32 * c + 8 * gq + 4 * half);
+            const float4 a = p4[0], b = p4[1];
+            const float co[4] = {a.x, a.z, b.x, b.z}, si[4] = {a.y, a.w, b.y, b.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = g[c][4 * gq + e], hi = g[c + CB / 2][4 * gq + e];
+                g[c][4 * gq + e] = lo * co[e] + hi * si[e];
+                g[c + CB / 2][4 * gq + e] = hi * co[e] - lo * si[e];
+            }
+        }
+}
+
 // ------------------------------------------------------------------------------------------
 // backward: dQ (and D = rowsum(dO * O)).  Same roles as the forward kernel: 8 wavefronts x 32 queries.
 // ------------------------------------------------------------------------------------------
@@ -538,6 +559,7 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
         block(std::integral_constant<int, 1>{});
     }
     if (valid) {
+        if (a.rope_cs) unrotate<CB>(dq, a.rope_cs + (long)q * (D / 2), half);
         bf16_t *out = (bf16_t *)a.d_qkv + (long)q * ld + head * D;
 #pragma unroll
         for (int c = 0; c < CB; ++c)
@@ -710,6 +732,7 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     }
 done:
     if (valid) {
+        if (a.rope_cs) unrotate<CB>(dk, a.rope_cs + (long)key * (D / 2), half);
         bf16_t *okp = (bf16_t *)a.d_qkv + (long)key * ld + nq + g * D;
         bf16_t *ovp = okp + nk;
 #pragma unroll

@@ -44,6 +44,9 @@ struct AttnArgs {
     float *Dsum;                // bwd scratch: [nh, T]
     // MFMA path: tok_info[t] = {segment start, segment end | (bidirectional ? 1 << 30 : 0)}
     const int2 *tok_info;
+    // MFMA path, backward: when not null, the [T, d/2] (cos, sin) table of the rotary embedding; dQ and dK are
+    // then rotated back in the kernels' epilogues (otherwise the caller does it afterwards)
+    const float2 *rope_cs;
     // MFMA path: dispatch order of the query tiles (256 queries: forward, dQ) and of the key tiles (128
     // keys: dK/dV), heaviest first; use_order = 0 means index order (more tiles than the tables hold)
     int use_order;
