@@ -123,6 +123,11 @@ typedef struct {
  * property Section 5.2 relies on for reordering): matrix and bias and gain
  * gradients are added to the buffers' contents instead of overwriting them. */
 #define MMTRAIN_BWD_ACCUMULATE_WGRAD 1u
+/* fp32 main-gradient buffers: every non-NULL member of mmtrain_layer_grads points to fp32 storage of the
+ * parameter's shape, whatever desc->dtype is (mixed-precision training, Section 3, keeps the accumulated
+ * gradients of bf16 parameters in fp32).  The products are accumulated in fp32 as always and are then
+ * written, or added with MMTRAIN_BWD_ACCUMULATE_WGRAD, without the rounding to the storage dtype. */
+#define MMTRAIN_BWD_WGRAD_F32 2u
 
 /* Bytes of `ctx` for a pack of total_tokens tokens.  0 on invalid desc. */
 MMTRAIN_API size_t mmtrain_layer_ctx_bytes(const mmtrain_layer_desc *desc, int32_t total_tokens);

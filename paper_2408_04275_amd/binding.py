@@ -21,6 +21,7 @@ DECODER, ENCODER = 0, 1
 MASK_CAUSAL, MASK_BIDIR = 0, 1
 GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
 BWD_ACCUMULATE_WGRAD = 1
+BWD_WGRAD_F32 = 2
 GEMM_ACCUMULATE = 1
 
 EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_layer_fwd", "mmtrain_layer_bwd",

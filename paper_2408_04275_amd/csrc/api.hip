@@ -131,6 +131,8 @@ hipError_t attn_bwd(int dtype, const AttnArgs &a, hipStream_t st) {
     return dtype == DT_BF16 ? attn_mfma_bwd(a, st) : attn_simple_bwd(dtype, a, st);
 }
 
+GemmArgs f32out(GemmArgs g, bool on) { g.c_f32 = on; return g; }
+
 GemmArgs mk(int layout, int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
             const void *bias = nullptr, const void *residual = nullptr, bool accumulate = false) {
     GemmArgs g;
@@ -282,21 +284,23 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     if (rc) return rc;
     if ((rc = check_batch(batch))) return rc;
     if ((rc = check_weights(D, W))) return rc;
-    if (flags & ~MMTRAIN_BWD_ACCUMULATE_WGRAD) return MMTRAIN_ERR_INVALID_ARG;
+    if (flags & ~(MMTRAIN_BWD_ACCUMULATE_WGRAD | MMTRAIN_BWD_WGRAD_F32)) return MMTRAIN_ERR_INVALID_ARG;
     const int T = batch->total_tokens;
     const bool accum = flags & MMTRAIN_BWD_ACCUMULATE_WGRAD;
+    const bool g32 = flags & MMTRAIN_BWD_WGRAD_F32;          // gradient buffers hold fp32
+    const int gdt = g32 ? DT_F32 : D.dtype;                   // dtype of the gradient buffers
     const bool enc = D.kind == MMTRAIN_ENCODER;
     hipStream_t st = (hipStream_t)hip_stream;
     mmtrain_layer_grads G = {};
     if (grads) G = *grads;
     if (T == 0) {                                   // an empty pack contributes zero gradients
         if (!accum) {
-            HIP_TRY(fill_zero(G.norm1_w, D.H, D.dtype, st)); HIP_TRY(fill_zero(G.norm1_b, D.H, D.dtype, st));
-            HIP_TRY(fill_zero(G.w_qkv, (size_t)D.nqkv * D.H, D.dtype, st)); HIP_TRY(fill_zero(G.b_qkv, D.nqkv, D.dtype, st));
-            HIP_TRY(fill_zero(G.w_o, (size_t)D.H * D.nq, D.dtype, st)); HIP_TRY(fill_zero(G.b_o, D.H, D.dtype, st));
-            HIP_TRY(fill_zero(G.norm2_w, D.H, D.dtype, st)); HIP_TRY(fill_zero(G.norm2_b, D.H, D.dtype, st));
-            HIP_TRY(fill_zero(G.w_fc1, (size_t)D.F1 * D.H, D.dtype, st)); HIP_TRY(fill_zero(G.b_fc1, D.F1, D.dtype, st));
-            HIP_TRY(fill_zero(G.w_fc2, (size_t)D.H * D.F, D.dtype, st)); HIP_TRY(fill_zero(G.b_fc2, D.H, D.dtype, st));
+            HIP_TRY(fill_zero(G.norm1_w, D.H, gdt, st)); HIP_TRY(fill_zero(G.norm1_b, D.H, gdt, st));
+            HIP_TRY(fill_zero(G.w_qkv, (size_t)D.nqkv * D.H, gdt, st)); HIP_TRY(fill_zero(G.b_qkv, D.nqkv, gdt, st));
+            HIP_TRY(fill_zero(G.w_o, (size_t)D.H * D.nq, gdt, st)); HIP_TRY(fill_zero(G.b_o, D.H, gdt, st));
+            HIP_TRY(fill_zero(G.norm2_w, D.H, gdt, st)); HIP_TRY(fill_zero(G.norm2_b, D.H, gdt, st));
+            HIP_TRY(fill_zero(G.w_fc1, (size_t)D.F1 * D.H, gdt, st)); HIP_TRY(fill_zero(G.b_fc1, D.F1, gdt, st));
+            HIP_TRY(fill_zero(G.w_fc2, (size_t)D.H * D.F, gdt, st)); HIP_TRY(fill_zero(G.b_fc2, D.H, gdt, st));
         }
         return MMTRAIN_OK;
     }
@@ -314,31 +318,31 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
 
     // ---- MLP block:  y = y1 + m . Wfc2^T (+ b_fc2)
     HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), st));
-    if (G.w_fc2) HIP_TRY(gemm(D.dtype, mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), st));
+    if (G.w_fc2) HIP_TRY(gemm(D.dtype, f32out(mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), g32), st));
     if (enc && G.b_fc2) {
         HIP_TRY(colsum_partials(D.dtype, dy, T, D.H, D.H, w.part_c, st));
-        HIP_TRY(reduce_partials(D.dtype, w.part_c, ns, D.H, G.b_fc2, accum, st));
+        HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.H, G.b_fc2, accum, st));
     }
     if (enc) HIP_TRY(gelu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, (long)T * D.F, st));
     else HIP_TRY(swiglu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F, st));
     if (enc && G.b_fc1) {
         HIP_TRY(colsum_partials(D.dtype, w.d_pre, T, D.F1, D.F1, w.part_c, st));
-        HIP_TRY(reduce_partials(D.dtype, w.part_c, ns, D.F1, G.b_fc1, accum, st));
+        HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.F1, G.b_fc1, accum, st));
     }
     HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.H, D.F1, w.d_pre, D.F1, W->w_fc1, D.H, w.d_h, D.H), st));
-    if (G.w_fc1) HIP_TRY(gemm(D.dtype, mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), st));
+    if (G.w_fc1) HIP_TRY(gemm(D.dtype, f32out(mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), g32), st));
     // d_y1 = dy + norm2_bwd(d_h2)
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
                      G.norm2_w ? w.part_g : nullptr, (enc && G.norm2_b) ? w.part_b : nullptr, T, D.H, st));
-    if (G.norm2_w) HIP_TRY(reduce_partials(D.dtype, w.part_g, nb, D.H, G.norm2_w, accum, st));
-    if (enc && G.norm2_b) HIP_TRY(reduce_partials(D.dtype, w.part_b, nb, D.H, G.norm2_b, accum, st));
+    if (G.norm2_w) HIP_TRY(reduce_partials(gdt, w.part_g, nb, D.H, G.norm2_w, accum, st));
+    if (enc && G.norm2_b) HIP_TRY(reduce_partials(gdt, w.part_b, nb, D.H, G.norm2_b, accum, st));
 
     // ---- attention block:  y1 = x + o . Wo^T (+ b_o)
     HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.nq, D.H, w.d_y1, D.H, W->w_o, D.nq, w.d_o, D.nq), st));
-    if (G.w_o) HIP_TRY(gemm(D.dtype, mk(GEMM_TN, D.H, D.nq, T, w.d_y1, D.H, c.o, D.nq, G.w_o, D.nq, nullptr, nullptr, accum), st));
+    if (G.w_o) HIP_TRY(gemm(D.dtype, f32out(mk(GEMM_TN, D.H, D.nq, T, w.d_y1, D.H, c.o, D.nq, G.w_o, D.nq, nullptr, nullptr, accum), g32), st));
     if (enc && G.b_o) {
         HIP_TRY(colsum_partials(D.dtype, w.d_y1, T, D.H, D.H, w.part_c, st));
-        HIP_TRY(reduce_partials(D.dtype, w.part_c, ns, D.H, G.b_o, accum, st));
+        HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.H, G.b_o, accum, st));
     }
     AttnArgs a = mk_attn(D, batch, c);
     a.d_o = w.d_o; a.d_qkv = w.d_qkv; a.Dsum = w.Dsum;
@@ -351,15 +355,15 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     if (!enc && !fused_unrotate) HIP_TRY(rope_inplace(D.dtype, w.d_qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, true, st));
     if (enc && G.b_qkv) {
         HIP_TRY(colsum_partials(D.dtype, w.d_qkv, T, D.nqkv, D.nqkv, w.part_c, st));
-        HIP_TRY(reduce_partials(D.dtype, w.part_c, ns, D.nqkv, G.b_qkv, accum, st));
+        HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.nqkv, G.b_qkv, accum, st));
     }
     HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.H, D.nqkv, w.d_qkv, D.nqkv, W->w_qkv, D.H, w.d_h, D.H), st));
-    if (G.w_qkv) HIP_TRY(gemm(D.dtype, mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), st));
+    if (G.w_qkv) HIP_TRY(gemm(D.dtype, f32out(mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), g32), st));
     // dx = d_y1 + norm1_bwd(d_h1)
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
                      G.norm1_w ? w.part_g : nullptr, (enc && G.norm1_b) ? w.part_b : nullptr, T, D.H, st));
-    if (G.norm1_w) HIP_TRY(reduce_partials(D.dtype, w.part_g, nb, D.H, G.norm1_w, accum, st));
-    if (enc && G.norm1_b) HIP_TRY(reduce_partials(D.dtype, w.part_b, nb, D.H, G.norm1_b, accum, st));
+    if (G.norm1_w) HIP_TRY(reduce_partials(gdt, w.part_g, nb, D.H, G.norm1_w, accum, st));
+    if (enc && G.norm1_b) HIP_TRY(reduce_partials(gdt, w.part_b, nb, D.H, G.norm1_b, accum, st));
     return MMTRAIN_OK;
 }
 

@@ -51,6 +51,7 @@ struct GemmP {
     const bf16_t *bias;
     const bf16_t *residual;
     int accumulate;
+    int c_f32;                 // C holds fp32 (weight gradients into fp32 main-gradient buffers)
     int tiles_m, tiles_n;
 };
 
@@ -232,7 +233,7 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F &
 template <bool KC> struct LoaderSel { typedef LoaderKC type; };
 template <> struct LoaderSel<false> { typedef LoaderKS type; };
 
-template <bool A_KC, bool B_KC, bool HAS_ADD>
+template <bool A_KC, bool B_KC, bool HAS_ADD, bool OUT_F32>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mfma_kernel(const GemmP p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -477,6 +478,18 @@ void gemm_mfma_kernel(const GemmP p) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(w[e] << 16); v[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u); }
                 }
+                if (OUT_F32) {
+                    // fp32 output (never together with bias or residual): previous contents are read here
+                    float *cf = reinterpret_cast<float *>(p.C) + off;
+                    if (p.accumulate) {
+                        const float4 c0 = *reinterpret_cast<const float4 *>(cf), c1 = *reinterpret_cast<const float4 *>(cf + 4);
+                        v[0] += c0.x; v[1] += c0.y; v[2] += c0.z; v[3] += c0.w;
+                        v[4] += c1.x; v[5] += c1.y; v[6] += c1.z; v[7] += c1.w;
+                    }
+                    __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f32x4 *>(cf));
+                    __builtin_nontemporal_store(f32x4{v[4], v[5], v[6], v[7]}, reinterpret_cast<f32x4 *>(cf + 4));
+                    continue;
+                }
                 uint4 o;
                 o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
                 o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
@@ -491,10 +504,10 @@ void gemm_mfma_kernel(const GemmP p) {
     }   // tiles of this workgroup
 }
 
-template <bool A_KC, bool B_KC, bool HAS_ADD>
+template <bool A_KC, bool B_KC, bool HAS_ADD, bool OUT_F32 = false>
 hipError_t launch(const GemmP &p, hipStream_t st) {
     static bool configured = false;
-    auto kern = gemm_mfma_kernel<A_KC, B_KC, HAS_ADD>;
+    auto kern = gemm_mfma_kernel<A_KC, B_KC, HAS_ADD, OUT_F32>;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
@@ -521,6 +534,7 @@ hipError_t launch(const GemmP &p, hipStream_t st) {
 
 bool gemm_mfma_supported(const GemmArgs &g) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return false;
+    if (g.c_f32 && (g.layout != GEMM_TN || g.bias || g.residual)) return false;   // fp32 output: weight gradients only
     if ((g.lda | g.ldb | g.ldc | g.N) & 7) return false;
     const bool a_kc = g.layout != GEMM_TN, b_kc = g.layout == GEMM_NT;
     if ((a_kc || b_kc) && (g.K & 7)) return false;
@@ -544,6 +558,8 @@ hipError_t gemm_mfma(const GemmArgs &g, hipStream_t st) {
     p.accumulate = g.accumulate ? 1 : 0;
     p.tiles_m = ceil_div(g.M, BM);
     p.tiles_n = ceil_div(g.N, BN);
+    p.c_f32 = g.c_f32 ? 1 : 0;
+    if (g.c_f32) return launch<false, false, false, true>(p, st);
     const bool add = p.residual || p.accumulate;
     switch (g.layout) {
         case GEMM_NT: return add ? launch<true, true, true>(p, st) : launch<true, true, false>(p, st);

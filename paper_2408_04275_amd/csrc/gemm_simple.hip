@@ -8,10 +8,10 @@ namespace mmt {
 
 constexpr int SB = 64, SK = 16;
 
-template <typename T>
+template <typename T, typename TC>
 __global__ __launch_bounds__(256) void gemm_simple_kernel(int M, int N, int K, const T *__restrict__ A, long sam,
                                                           long sak, const T *__restrict__ B, long sbn, long sbk,
-                                                          T *__restrict__ C, int ldc, const T *__restrict__ bias,
+                                                          TC *__restrict__ C, int ldc, const T *__restrict__ bias,
                                                           const T *__restrict__ residual, bool accumulate) {
     __shared__ float As[SK][SB + 4], Bs[SK][SB + 4];
     const int m0 = blockIdx.y * SB, n0 = blockIdx.x * SB;
@@ -57,14 +57,14 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(int M, int N, int K, c
             float v = acc[i][j];
             if (bias) v += Elem<T>::load(bias + n);
             if (residual) v += Elem<T>::load(residual + (long)m * ldc + n);
-            if (accumulate) v += Elem<T>::load(C + (long)m * ldc + n);
-            Elem<T>::store(C + (long)m * ldc + n, v);
+            if (accumulate) v += Elem<TC>::load(C + (long)m * ldc + n);
+            Elem<TC>::store(C + (long)m * ldc + n, v);
         }
     }
 }
 
-template <typename T>
-__global__ void gemm_k0_kernel(int M, int N, T *__restrict__ C, int ldc, const T *__restrict__ bias,
+template <typename T, typename TC>
+__global__ void gemm_k0_kernel(int M, int N, TC *__restrict__ C, int ldc, const T *__restrict__ bias,
                                const T *__restrict__ residual) {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long)M * N) return;
@@ -72,15 +72,15 @@ __global__ void gemm_k0_kernel(int M, int N, T *__restrict__ C, int ldc, const T
     float v = 0.f;
     if (bias) v += Elem<T>::load(bias + n);
     if (residual) v += Elem<T>::load(residual + (long)m * ldc + n);
-    Elem<T>::store(C + (long)m * ldc + n, v);
+    Elem<TC>::store(C + (long)m * ldc + n, v);
 }
 
-template <typename T>
+template <typename T, typename TC>
 static hipError_t launch(const GemmArgs &g, hipStream_t st) {
     if (g.M == 0 || g.N == 0) return hipSuccess;
     if (g.K == 0) {                       // empty contraction: C = bias + residual (or unchanged)
         if (g.accumulate) return hipSuccess;
-        gemm_k0_kernel<T><<<ceil_div((long)g.M * g.N, 256), 256, 0, st>>>(g.M, g.N, (T *)g.C, g.ldc, (const T *)g.bias,
+        gemm_k0_kernel<T, TC><<<ceil_div((long)g.M * g.N, 256), 256, 0, st>>>(g.M, g.N, (TC *)g.C, g.ldc, (const T *)g.bias,
                                                                           (const T *)g.residual);
         return hipGetLastError();
     }
@@ -88,13 +88,14 @@ static hipError_t launch(const GemmArgs &g, hipStream_t st) {
     if (g.layout == GEMM_TN) { sam = 1; sak = g.lda; } else { sam = g.lda; sak = 1; }
     if (g.layout == GEMM_NT) { sbn = g.ldb; sbk = 1; } else { sbn = 1; sbk = g.ldb; }
     dim3 grid(ceil_div(g.N, SB), ceil_div(g.M, SB));
-    gemm_simple_kernel<T><<<grid, 256, 0, st>>>(g.M, g.N, g.K, (const T *)g.A, sam, sak, (const T *)g.B, sbn, sbk,
-                                                (T *)g.C, g.ldc, (const T *)g.bias, (const T *)g.residual, g.accumulate);
+    gemm_simple_kernel<T, TC><<<grid, 256, 0, st>>>(g.M, g.N, g.K, (const T *)g.A, sam, sak, (const T *)g.B, sbn, sbk,
+                                                    (TC *)g.C, g.ldc, (const T *)g.bias, (const T *)g.residual, g.accumulate);
     return hipGetLastError();
 }
 
 hipError_t gemm_simple(int dtype, const GemmArgs &g, hipStream_t st) {
-    return dtype == DT_F32 ? launch<float>(g, st) : launch<bf16_t>(g, st);
+    if (dtype == DT_F32) return launch<float, float>(g, st);
+    return g.c_f32 ? launch<bf16_t, float>(g, st) : launch<bf16_t, bf16_t>(g, st);
 }
 
 }  // namespace mmt

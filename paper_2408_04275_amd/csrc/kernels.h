@@ -18,6 +18,7 @@ struct GemmArgs {
     const void *bias;           // [N] or null
     const void *residual;       // [M, ldc] or null
     bool accumulate;            // C += result
+    bool c_f32 = false;         // C is fp32 whatever the operands' dtype (bias / residual are not combined with it)
 };
 
 // gemm_simple.hip: any dtype, any shape, LDS-tiled FMA kernel (the fp32 path).

@@ -37,7 +37,7 @@ class LayerRunner:
 
     def __init__(self, shape: LayerShape, weights: Dict[str, np.ndarray], cu: np.ndarray,
                  modes: Optional[np.ndarray] = None, mask_mode: int = mm.MASK_CAUSAL, device="cuda",
-                 grad_names=None):
+                 grad_names=None, grads_f32: bool = False):
         self.shape, self.device = shape, device
         self.desc = mm.make_desc(shape.kind, shape.dtype, shape.hidden, shape.n_heads, shape.n_kv_heads,
                                  shape.head_dim, shape.ffn_hidden, shape.norm_eps, shape.rope_base)
@@ -47,7 +47,9 @@ class LayerRunner:
         dt = torch_dtype(shape.dtype)
         self.w = {k: to_device(v, shape.dtype, device) for k, v in weights.items()}
         names = list(weight_shapes(shape)) if grad_names is None else list(grad_names)
-        self.g = {k: torch.zeros(weight_shapes(shape)[k], dtype=dt, device=device) for k in names}
+        # gradient buffers: the storage dtype, or fp32 main-gradient buffers (then pass BWD_WGRAD_F32 to backward)
+        self.g = {k: torch.zeros(weight_shapes(shape)[k], dtype=torch.float32 if grads_f32 else dt, device=device)
+                  for k in names}
         self.weights = mm.make_weights(self.w)
         self.grads = mm.make_grads(self.g)
         self.ctx_bytes = mm.mmtrain_layer_ctx_bytes(self.desc, self.T)

@@ -114,3 +114,47 @@ def test_segment_order_invariance_on_gpu():
     bars("dx", dxp, np.concatenate([dx[a:b] for a, b in blocks]), wl.BF16)
     for k in G:
         bars(k, Gp[k], G[k], wl.BF16)
+
+
+@pytest.mark.parametrize("kind", [wl.DECODER, wl.ENCODER])
+def test_fp32_main_gradient_buffers(kind):
+    # mixed-precision training keeps accumulated gradients of bf16 parameters in fp32: with BWD_WGRAD_F32 the
+    # gradient buffers are fp32, are written without the rounding to bf16, and accumulate exactly
+    shape = wl.LayerShape("g32", kind, wl.BF16, 512, 8, 8 if kind == wl.ENCODER else 2, 64, 1024, 1300)
+    rng = np.random.default_rng(31)
+    cu, modes = wl.random_segments(rng, 1300, 6)
+    W = wl.make_weights(shape, 7, std=0.05)
+    x, dy = wl.make_activations(shape, 1300, 7)
+    ref = oracle_run(shape, cu, modes, W, x, dy)
+    r16 = LayerRunner(shape, W, cu, modes); r16.set_inputs(x, dy); r16.step()
+    y16, dx16, G16 = r16.results()
+    r32 = LayerRunner(shape, W, cu, modes, grads_f32=True); r32.set_inputs(x, dy)
+    check(r32.forward(), "fwd"); check(r32.backward(mm.BWD_WGRAD_F32), "bwd, fp32 gradients")
+    y32, dx32, G32 = r32.results()
+    assert np.array_equal(y16, y32) and np.array_equal(dx16, dx32)
+    errs = compare_layer(shape, (y32, dx32, G32), ref, f"fp32 gradients kind={kind} ")
+    for k in G32:
+        # same products, one rounding fewer: rounding the fp32 result to bf16 gives the bf16 run's bits
+        assert np.array_equal(wl.round_bf16(G32[k]), G16[k]), k
+        e16 = np.linalg.norm(G16[k] - ref[2][k]) / np.linalg.norm(ref[2][k])
+        assert errs[k]["l2_err"] <= e16 * 1.001 + 1e-7, (k, errs[k]["l2_err"], e16)
+    # accumulation in fp32 is exact for a repeated microbatch: g + g = 2 g
+    check(r32.backward(mm.BWD_WGRAD_F32 | mm.BWD_ACCUMULATE_WGRAD), "bwd, fp32 gradients, accumulate")
+    G2 = r32.results()[2]
+    for k in G32:
+        assert np.array_equal(G2[k], 2.0 * G32[k]), k
+
+
+def test_fp32_main_gradient_flag_with_fp32_storage():
+    shape = wl.LayerShape("g32f", wl.DECODER, wl.F32, 128, 4, 2, 64, 352, 300)
+    rng = np.random.default_rng(32)
+    cu, modes = wl.random_segments(rng, 300, 4)
+    W = wl.make_weights(shape, 8, std=0.05)
+    x, dy = wl.make_activations(shape, 300, 8)
+    a = gpu_run(shape, cu, modes, W, x, dy)
+    r = LayerRunner(shape, W, cu, modes, grads_f32=True); r.set_inputs(x, dy)
+    check(r.forward(), "fwd"); check(r.backward(mm.BWD_WGRAD_F32), "bwd")
+    b = r.results()
+    assert np.array_equal(a[1], b[1])
+    for k in a[2]:
+        assert np.array_equal(a[2][k], b[2][k]), k
