@@ -73,7 +73,8 @@ typedef enum {
     MMTRAIN_MASK_BIDIR = 1          /* every key of the same segment  */
 } mmtrain_mask_mode;
 
-/* Layer description.  Supported: head_dim in {64, 128}; n_heads % n_kv_heads == 0
+/* Layer description.  Supported: head_dim in {64, 128}, and with bf16 storage also every other multiple of
+ * 16 below 128 (80 is the ViT-Huge head; such heads are zero-padded to 64 or 128 inside the kernels); n_heads % n_kv_heads == 0
  * (encoder: n_kv_heads == n_heads); hidden, ffn_hidden and n_heads*head_dim
  * multiples of 16.  Anything else: MMTRAIN_ERR_UNSUPPORTED. */
 typedef struct {

@@ -40,6 +40,7 @@ struct Ctx {
 struct BwdWs {
     void *d_m, *d_pre, *d_h, *d_y1, *d_o, *d_qkv;
     float *Dsum, *part_g, *part_b, *part_c;
+    void *split_ws; size_t split_bytes;     // fp32 partial products of split weight-gradient GEMMs
 };
 
 int check_desc(const mmtrain_layer_desc *desc, Dims &D) {
@@ -50,7 +51,11 @@ int check_desc(const mmtrain_layer_desc *desc, Dims &D) {
         return MMTRAIN_ERR_INVALID_ARG;
     if (!(desc->norm_eps > 0.f) || desc->softmax_scale < 0.f) return MMTRAIN_ERR_INVALID_ARG;
     if (desc->kind == MMTRAIN_DECODER && !(desc->rope_base > 1.f)) return MMTRAIN_ERR_INVALID_ARG;
-    if (desc->head_dim != 64 && desc->head_dim != 128) return MMTRAIN_ERR_UNSUPPORTED;
+    // 64 and 128 are the kernels' native tile widths; other multiples of 16 up to 128 (80: ViT-Huge) run on
+    // the matrix-core kernels with the head zero-padded in LDS and registers (bf16 storage only)
+    if (desc->head_dim != 64 && desc->head_dim != 128 &&
+        !(desc->dtype == MMTRAIN_BF16 && desc->head_dim >= 16 && desc->head_dim < 128 && desc->head_dim % 16 == 0))
+        return MMTRAIN_ERR_UNSUPPORTED;
     if (desc->n_heads % desc->n_kv_heads) return MMTRAIN_ERR_UNSUPPORTED;
     if (desc->kind == MMTRAIN_ENCODER && desc->n_kv_heads != desc->n_heads) return MMTRAIN_ERR_UNSUPPORTED;
     if ((desc->hidden % 16) || (desc->ffn_hidden % 16)) return MMTRAIN_ERR_UNSUPPORTED;
@@ -119,6 +124,21 @@ void carve_bwd(Bump &b, const Dims &D, size_t T, BwdWs &w) {
     w.part_b = b.take<float>((size_t)norm_bwd_blocks((int)T) * D.H);
     const int maxn = D.nqkv > D.F1 ? (D.nqkv > D.H ? D.nqkv : D.H) : (D.F1 > D.H ? D.F1 : D.H);
     w.part_c = b.take<float>((size_t)colsum_slabs((int)T) * maxn);
+    // scratch for the weight-gradient GEMMs whose output has few tiles (see gemm_mfma_splits): up to 256 / tiles
+    // partial products of M x N fp32
+    auto need = [](size_t M, size_t N) -> size_t {
+        const size_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+        if (tiles > 128) return 0;
+        const size_t s = 256 / tiles < 32 ? 256 / tiles : 32;
+        return s * M * N * 4;
+    };
+    size_t sb = 0;
+    if (D.dtype == DT_BF16) {
+        const size_t c[4] = {need(D.H, D.F), need(D.F1, D.H), need(D.H, D.nq), need(D.nqkv, D.H)};
+        for (size_t v : c) sb = v > sb ? v : sb;
+    }
+    w.split_bytes = sb;
+    w.split_ws = sb ? (void *)b.take<float>(sb / 4) : nullptr;
 }
 
 hipError_t gemm(int dtype, const GemmArgs &g, hipStream_t st);
@@ -132,6 +152,7 @@ hipError_t attn_bwd(int dtype, const AttnArgs &a, hipStream_t st) {
 }
 
 GemmArgs f32out(GemmArgs g, bool on) { g.c_f32 = on; return g; }
+GemmArgs splittable(GemmArgs g, void *ws, size_t bytes) { g.split_ws = ws; g.split_ws_bytes = bytes; return g; }
 
 GemmArgs mk(int layout, int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
             const void *bias = nullptr, const void *residual = nullptr, bool accumulate = false) {
@@ -318,7 +339,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
 
     // ---- MLP block:  y = y1 + m . Wfc2^T (+ b_fc2)
     HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), st));
-    if (G.w_fc2) HIP_TRY(gemm(D.dtype, f32out(mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), g32), st));
+    if (G.w_fc2) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     if (enc && G.b_fc2) {
         HIP_TRY(colsum_partials(D.dtype, dy, T, D.H, D.H, w.part_c, st));
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.H, G.b_fc2, accum, st));
@@ -330,7 +351,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.F1, G.b_fc1, accum, st));
     }
     HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.H, D.F1, w.d_pre, D.F1, W->w_fc1, D.H, w.d_h, D.H), st));
-    if (G.w_fc1) HIP_TRY(gemm(D.dtype, f32out(mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), g32), st));
+    if (G.w_fc1) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     // d_y1 = dy + norm2_bwd(d_h2)
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
                      G.norm2_w ? w.part_g : nullptr, (enc && G.norm2_b) ? w.part_b : nullptr, T, D.H, st));
@@ -339,14 +360,14 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
 
     // ---- attention block:  y1 = x + o . Wo^T (+ b_o)
     HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.nq, D.H, w.d_y1, D.H, W->w_o, D.nq, w.d_o, D.nq), st));
-    if (G.w_o) HIP_TRY(gemm(D.dtype, f32out(mk(GEMM_TN, D.H, D.nq, T, w.d_y1, D.H, c.o, D.nq, G.w_o, D.nq, nullptr, nullptr, accum), g32), st));
+    if (G.w_o) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.nq, T, w.d_y1, D.H, c.o, D.nq, G.w_o, D.nq, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     if (enc && G.b_o) {
         HIP_TRY(colsum_partials(D.dtype, w.d_y1, T, D.H, D.H, w.part_c, st));
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.H, G.b_o, accum, st));
     }
     AttnArgs a = mk_attn(D, batch, c);
     a.d_o = w.d_o; a.d_qkv = w.d_qkv; a.Dsum = w.Dsum;
-    const bool fused_unrotate = !enc && D.dtype == DT_BF16;       // the matrix-core kernels rotate dQ, dK back themselves
+    const bool fused_unrotate = !enc && D.dtype == DT_BF16 && (D.d == 64 || D.d == 128);       // the matrix-core kernels rotate dQ, dK back themselves
     if (fused_unrotate) a.rope_cs = c.rope_cs;
     {
         ProfScope ps(MMTRAIN_PROF_ATTN_BWD, st);
@@ -358,7 +379,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.nqkv, G.b_qkv, accum, st));
     }
     HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.H, D.nqkv, w.d_qkv, D.nqkv, W->w_qkv, D.H, w.d_h, D.H), st));
-    if (G.w_qkv) HIP_TRY(gemm(D.dtype, f32out(mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), g32), st));
+    if (G.w_qkv) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     // dx = d_y1 + norm1_bwd(d_h1)
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
                      G.norm1_w ? w.part_g : nullptr, (enc && G.norm1_b) ? w.part_b : nullptr, T, D.H, st));

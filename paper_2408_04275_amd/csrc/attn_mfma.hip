@@ -195,7 +195,8 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
     const long ld = a.ld_qkv;
-    const int nq = a.nh * D, nk = a.nkv * D;
+    const int dh = a.d;                                 // head dimension in memory (<= D: LDS tiles and fragments are zero-padded to D)
+    const int nq = a.nh * dh, nk = a.nkv * dh;
 
     const int q = q0 + wave * 32 + l32;
     const RowInfo me = query_range(a.tok_info, q, T);
@@ -209,7 +210,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (valid) v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * D + ks * 16 + half * 8);
+        if (valid && ks * 16 + half * 8 < dh) v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * dh + ks * 16 + half * 8);
         qf[ks] = *reinterpret_cast<bf16x8 *>(&v);
     }
     f32x16 oacc[CB];
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
         for (int i = 0; i < COPIES; ++i) {
             const int r0 = (cw * COPIES + i) * ROWS_PER_COPY, row = r0 + k_lrow;
             const int unit = (k_pos & ~7) | ((k_pos & 7) ^ swz(row));
-            const uint32_t off = (uint32_t)(((size_t)(kt + row) * ld + nq + g * D + unit * 8) * 2);
+            const uint32_t off = unit * 8 < dh ? (uint32_t)(((size_t)(kt + row) * ld + nq + g * dh + unit * 8) * 2) : 0xfffffff0u;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(slot + r0 * 2 * D), 16, (int)off, 0, 0, 0);
         }
     };
@@ -242,8 +243,9 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
         if (!v_thread) return;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
+            if (v_cb * 8 >= dh) { vr[j] = make_uint4(0, 0, 0, 0); continue; }
             const int key = kt + 32 * (v_u >> 2) + 16 * ((v_u >> 1) & 1) + 8 * v_part + 4 * (v_u & 1) + j;
-            const uint32_t off = (uint32_t)(((size_t)key * ld + nq + nk + g * D + v_cb * 8) * 2);
+            const uint32_t off = (uint32_t)(((size_t)key * ld + nq + nk + g * dh + v_cb * 8) * 2);
             const rawx4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
             vr[j] = make_uint4(v[0], v[1], v[2], v[3]);
         }
@@ -341,7 +343,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (valid) {
         const float inv = 1.f / l_tot;
-        bf16_t *o = (bf16_t *)a.o + (long)q * nq + head * D;
+        bf16_t *o = (bf16_t *)a.o + (long)q * nq + head * dh;
 #pragma unroll
         for (int c = 0; c < CB; ++c)
 #pragma unroll
@@ -349,7 +351,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
                 uint2 w;
                 w.x = pack_bf16x2(oacc[c][4 * gq] * inv, oacc[c][4 * gq + 1] * inv);
                 w.y = pack_bf16x2(oacc[c][4 * gq + 2] * inv, oacc[c][4 * gq + 3] * inv);
-                *reinterpret_cast<uint2 *>(o + 32 * c + 8 * gq + 4 * half) = w;
+                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(o + 32 * c + 8 * gq + 4 * half) = w;
             }
         if (half == 0) a.lse[(long)head * T + q] = (m_run * sl2 + __builtin_amdgcn_logf(l_tot)) * LN2;
     }
@@ -370,9 +372,11 @@ typedef __attribute__((ext_vector_type(4))) short shortx4;
 typedef __attribute__((ext_vector_type(8))) short shortx8;
 
 // One wavefront's share of the copy of a [64][D] tile: copies i = 0 .. N-1 of 1 KiB each, copy (first + i)
-// of the tile covering rows (first + i) * 512 / D ...  Rows at or beyond the end of the tensor read as zero.
+// of the tile covering rows (first + i) * 512 / D ...  Rows at or beyond the end of the tensor read as zero,
+// and so do the columns from row_elems on (a head narrower than the tile).
 template <int D, int N>
-__device__ __forceinline__ void copy_rows(__amdgpu_buffer_rsrc_t rs, uint8_t *tile, int first, long row0, long ld, long col0) {
+__device__ __forceinline__ void copy_rows(__amdgpu_buffer_rsrc_t rs, uint8_t *tile, int first, long row0, long ld, long col0,
+                                          int row_elems) {
     constexpr int UPR = D / 8, ROWS_PER_COPY = 1024 / (2 * D);
     const int lane = threadIdx.x & 63;
     const int lrow = lane / UPR, pos = lane % UPR;
@@ -380,7 +384,7 @@ __device__ __forceinline__ void copy_rows(__amdgpu_buffer_rsrc_t rs, uint8_t *ti
     for (int i = 0; i < N; ++i) {
         const int r0 = (first + i) * ROWS_PER_COPY, row = r0 + lrow;
         const int unit = (pos & ~7) | ((pos & 7) ^ swz(row));
-        const uint32_t off = (uint32_t)(((size_t)(row0 + row) * ld + col0 + unit * 8) * 2);
+        const uint32_t off = unit * 8 < row_elems ? (uint32_t)(((size_t)(row0 + row) * ld + col0 + unit * 8) * 2) : 0xfffffff0u;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + r0 * 2 * D), 16, (int)off, 0, 0, 0);
     }
 }
@@ -455,7 +459,8 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
     const long ld = a.ld_qkv;
-    const int nq = a.nh * D, nk = a.nkv * D;
+    const int dh = a.d;                                 // head dimension in memory (<= D: LDS tiles and fragments are zero-padded to D)
+    const int nq = a.nh * dh, nk = a.nkv * dh;
 
     const int q = q0 + wave * 32 + l32;
     const RowInfo me = query_range(a.tok_info, q, T);
@@ -470,10 +475,10 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
         uint4 v = make_uint4(0, 0, 0, 0), w = v, x = v;
-        if (valid) {
-            v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * D + ks * 16 + half * 8);
-            w = *reinterpret_cast<const uint4 *>((const bf16_t *)a.d_o + (long)q * nq + head * D + ks * 16 + half * 8);
-            x = *reinterpret_cast<const uint4 *>((const bf16_t *)a.o + (long)q * nq + head * D + ks * 16 + half * 8);
+        if (valid && ks * 16 + half * 8 < dh) {
+            v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * dh + ks * 16 + half * 8);
+            w = *reinterpret_cast<const uint4 *>((const bf16_t *)a.d_o + (long)q * nq + head * dh + ks * 16 + half * 8);
+            x = *reinterpret_cast<const uint4 *>((const bf16_t *)a.o + (long)q * nq + head * dh + ks * 16 + half * 8);
         }
         qf[ks] = *reinterpret_cast<bf16x8 *>(&v);
         dof[ks] = *reinterpret_cast<bf16x8 *>(&w);
@@ -499,8 +504,8 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
     // wavefronts 4..7 copy the K tile, wavefronts 0..3 the V tile
     auto copy_kv = [&](uint8_t *slot, int kt) {
-        if (wave >= 4) copy_rows<D, COPIES>(rs, slot, (wave - 4) * COPIES, kt, ld, nq + g * D);
-        else copy_rows<D, COPIES>(rs, slot + TILE, wave * COPIES, kt, ld, nq + nk + g * D);
+        if (wave >= 4) copy_rows<D, COPIES>(rs, slot, (wave - 4) * COPIES, kt, ld, nq + g * dh, dh);
+        else copy_rows<D, COPIES>(rs, slot + TILE, wave * COPIES, kt, ld, nq + nk + g * dh, dh);
     };
     TrReader<D> tr;
     tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
@@ -560,7 +565,7 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     }
     if (valid) {
         if (a.rope_cs) unrotate<CB>(dq, a.rope_cs + (long)q * (D / 2), half);
-        bf16_t *out = (bf16_t *)a.d_qkv + (long)q * ld + head * D;
+        bf16_t *out = (bf16_t *)a.d_qkv + (long)q * ld + head * dh;
 #pragma unroll
         for (int c = 0; c < CB; ++c)
 #pragma unroll
@@ -568,7 +573,7 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
                 uint2 w;
                 w.x = pack_bf16x2(dq[c][4 * gq] * a.scale, dq[c][4 * gq + 1] * a.scale);
                 w.y = pack_bf16x2(dq[c][4 * gq + 2] * a.scale, dq[c][4 * gq + 3] * a.scale);
-                *reinterpret_cast<uint2 *>(out + 32 * c + 8 * gq + 4 * half) = w;
+                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(out + 32 * c + 8 * gq + 4 * half) = w;
             }
     }
 }
@@ -592,7 +597,8 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     const bf16_t *qkv = (const bf16_t *)a.qkv;
     const bf16_t *dO = (const bf16_t *)a.d_o;
     const long ld = a.ld_qkv;
-    const int nq = a.nh * D, nk = a.nkv * D;
+    const int dh = a.d;                                 // head dimension in memory (<= D: LDS tiles and fragments are zero-padded to D)
+    const int nq = a.nh * dh, nk = a.nkv * dh;
 
     const int key = k0 + wave * 32 + l32;
     const RowInfo me = key_range(a.tok_info, key, T);       // queries [lo, hi) see this key
@@ -606,9 +612,9 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
         uint4 v = make_uint4(0, 0, 0, 0), w = v;
-        if (valid) {
-            v = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + g * D + ks * 16 + half * 8);
-            w = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + nk + g * D + ks * 16 + half * 8);
+        if (valid && ks * 16 + half * 8 < dh) {
+            v = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + g * dh + ks * 16 + half * 8);
+            w = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + nk + g * dh + ks * 16 + half * 8);
         }
         kf[ks] = *reinterpret_cast<bf16x8 *>(&v);
         vf[ks] = *reinterpret_cast<bf16x8 *>(&w);
@@ -625,8 +631,8 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     // every wavefront copies a quarter of the Q tile and of the dO tile; wavefronts 0 and 1 also fetch the
     // 64 log-sum-exps and the 64 D values of the tile's queries (4 bytes per lane; queries >= T read as 0)
     auto copy_tile = [&](uint8_t *slot, int head, int qt) {
-        copy_rows<D, COPIES>(rs_q, slot, wave * COPIES, qt, ld, head * D);
-        copy_rows<D, COPIES>(rs_do, slot + TILE, wave * COPIES, qt, nq, head * D);
+        copy_rows<D, COPIES>(rs_q, slot, wave * COPIES, qt, ld, head * dh, dh);
+        copy_rows<D, COPIES>(rs_do, slot + TILE, wave * COPIES, qt, nq, head * dh, dh);
         if (wave < 2) {
             const float *src = (wave == 0 ? a.lse : a.Dsum) + (long)head * T;
             const __amdgpu_buffer_rsrc_t rs_f =
@@ -733,7 +739,7 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
 done:
     if (valid) {
         if (a.rope_cs) unrotate<CB>(dk, a.rope_cs + (long)key * (D / 2), half);
-        bf16_t *okp = (bf16_t *)a.d_qkv + (long)key * ld + nq + g * D;
+        bf16_t *okp = (bf16_t *)a.d_qkv + (long)key * ld + nq + g * dh;
         bf16_t *ovp = okp + nk;
 #pragma unroll
         for (int c = 0; c < CB; ++c)
@@ -742,10 +748,10 @@ done:
                 uint2 w;
                 w.x = pack_bf16x2(dk[c][4 * gq] * a.scale, dk[c][4 * gq + 1] * a.scale);
                 w.y = pack_bf16x2(dk[c][4 * gq + 2] * a.scale, dk[c][4 * gq + 3] * a.scale);
-                *reinterpret_cast<uint2 *>(okp + 32 * c + 8 * gq + 4 * half) = w;
+                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(okp + 32 * c + 8 * gq + 4 * half) = w;
                 w.x = pack_bf16x2(dv[c][4 * gq], dv[c][4 * gq + 1]);
                 w.y = pack_bf16x2(dv[c][4 * gq + 2], dv[c][4 * gq + 3]);
-                *reinterpret_cast<uint2 *>(ovp + 32 * c + 8 * gq + 4 * half) = w;
+                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(ovp + 32 * c + 8 * gq + 4 * half) = w;
             }
     }
 }
@@ -788,12 +794,12 @@ hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
 
 hipError_t attn_mfma_fwd(const AttnArgs &a, hipStream_t st) {
     if (a.T == 0) return hipSuccess;
-    return a.d == 64 ? launch_fwd<64>(a, st) : launch_fwd<128>(a, st);
+    return a.d <= 64 ? launch_fwd<64>(a, st) : launch_fwd<128>(a, st);
 }
 
 hipError_t attn_mfma_bwd(const AttnArgs &a, hipStream_t st) {
     if (a.T == 0) return hipSuccess;
-    return a.d == 64 ? launch_bwd<64>(a, st) : launch_bwd<128>(a, st);
+    return a.d <= 64 ? launch_bwd<64>(a, st) : launch_bwd<128>(a, st);
 }
 
 }  // namespace mmt

@@ -53,6 +53,10 @@ struct GemmP {
     int accumulate;
     int c_f32;                 // C holds fp32 (weight gradients into fp32 main-gradient buffers)
     int tiles_m, tiles_n;
+    // split K (fp32 output only): the K range is cut into `splits` chunks of k_chunk (a multiple of 64); chunk s of
+    // every tile is a work item of its own and writes the partial product to C + s * split_stride (fp32 elements)
+    int splits, k_chunk;
+    long split_stride;
 };
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
@@ -243,7 +247,8 @@ void gemm_mfma_kernel(const GemmP p) {
 
     // ---- persistent workgroup -> tiles.  Workgroup b runs on XCD b % 8 (round-robin dispatch); XCD x
     // owns a contiguous run of the tile order, and its workgroups stride through that run together.
-    const int ntiles = p.tiles_m * p.tiles_n;
+    const int tiles_mn = p.tiles_m * p.tiles_n;
+    const int ntiles = tiles_mn * (OUT_F32 ? p.splits : 1);   // work items: (K chunk, tile), chunk-major
     const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
     const int per = ntiles >> 3, rem = ntiles & 7;
     const int run_begin = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
@@ -271,19 +276,24 @@ void gemm_mfma_kernel(const GemmP p) {
 
     for (int logical = run_begin + q; logical < run_end; logical += wg_per_xcd) {
     int tm, tn;
+    const int chunk = OUT_F32 ? logical / tiles_mn : 0;
     {
+        const int t = logical - chunk * tiles_mn;
         const int width = GROUP_M * p.tiles_n;
-        const int group = logical / width, first_m = group * GROUP_M;
+        const int group = t / width, first_m = group * GROUP_M;
         const int gsize = min(p.tiles_m - first_m, GROUP_M);
-        tm = first_m + (logical % width) % gsize;
-        tn = (logical % width) / gsize;
+        tm = first_m + (t % width) % gsize;
+        tn = (t % width) / gsize;
     }
     const int m0 = tm * BM, n0 = tn * BN;
+    // this work item's K range (only the fp32-output kernel, whose operands are both K-strided, is ever split)
+    const int k_begin = OUT_F32 ? chunk * p.k_chunk : 0;
+    const int Kc = OUT_F32 ? min(p.k_chunk, p.K - k_begin) : p.K;
 
     typename LoaderSel<A_KC>::type la;
     typename LoaderSel<B_KC>::type lb;
-    la.init(p.A, p.lda, m0, p.M, p.K);
-    lb.init(p.B, p.ldb, n0, p.N, p.K);
+    la.init(p.A + (size_t)k_begin * (A_KC ? 1 : p.lda), p.lda, m0, p.M, Kc);
+    lb.init(p.B + (size_t)k_begin * (B_KC ? 1 : p.ldb), p.ldb, n0, p.N, Kc);
 
     f32x4 acc[8][8];
 #pragma unroll
@@ -353,7 +363,7 @@ void gemm_mfma_kernel(const GemmP p) {
     // and B(kt+1) (copied in the first half of this interval) must have landed; the 8 youngest copies (of
     // A(kt+2)) may still be in flight (vmcnt(8): memory operations retire in issue order).  A copy thus
     // has between one and three slices to land, against about half a slice of L2 latency.
-    const int nk = (p.K + BK - 1) / BK;
+    const int nk = (Kc + BK - 1) / BK;
     typedef std::integral_constant<int, 0> S0;
     typedef std::integral_constant<int, 1> S1;
     typedef std::make_integer_sequence<int, 16> Groups16;
@@ -399,7 +409,7 @@ void gemm_mfma_kernel(const GemmP p) {
         { const int t0 = o0, t1 = o1; o0 = o2; o1 = o3; o2 = o4; o3 = t0; o4 = t1; }
     };
     // copies of a step reach up to K tile kt+2: the unchecked form needs that tile inside the matrix
-    const int nk_fast = full_tiles ? max(p.K / BK - 2, 0) : 0;
+    const int nk_fast = full_tiles ? max(Kc / BK - 2, 0) : 0;
     for (int kt = 0; kt < nk_fast; ++kt) step(std::true_type{}, kt);
     for (int kt = nk_fast; kt < nk; ++kt) step(std::false_type{}, kt);
     asm volatile("s_nop 15\n\ts_waitcnt vmcnt(0)" ::: "memory");   // the last MFMAs have written their accumulators;
@@ -480,7 +490,7 @@ void gemm_mfma_kernel(const GemmP p) {
                 }
                 if (OUT_F32) {
                     // fp32 output (never together with bias or residual): previous contents are read here
-                    float *cf = reinterpret_cast<float *>(p.C) + off;
+                    float *cf = reinterpret_cast<float *>(p.C) + (size_t)chunk * p.split_stride + off;
                     if (p.accumulate) {
                         const float4 c0 = *reinterpret_cast<const float4 *>(cf), c1 = *reinterpret_cast<const float4 *>(cf + 4);
                         v[0] += c0.x; v[1] += c0.y; v[2] += c0.z; v[3] += c0.w;
@@ -525,7 +535,7 @@ hipError_t launch(const GemmP &p, hipStream_t st) {
         n_cu &= ~7;
         if (n_cu == 0) n_cu = 8;
     }
-    const int tiles = p.tiles_m * p.tiles_n;
+    const int tiles = p.tiles_m * p.tiles_n * (OUT_F32 ? p.splits : 1);
     kern<<<tiles < n_cu ? tiles : n_cu, 256, SMEM_BYTES, st>>>(p);
     return hipGetLastError();
 }
@@ -547,8 +557,66 @@ bool gemm_mfma_supported(const GemmArgs &g) {
     return (bits & 15) == 0;
 }
 
+// C (+)= sum over the K chunks of the fp32 partial products; C is bf16 or fp32.  4 elements per thread.
+template <typename TC>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int splits, long stride, int M, int N,
+                                                            TC *__restrict__ C, int ldc, int accumulate) {
+    const long idx = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (idx >= (long)M * N) return;
+    const int m = (int)(idx / N), n = (int)(idx % N);                 // N is a multiple of 8
+    f32x4 v = *reinterpret_cast<const f32x4 *>(part + idx);
+    for (int sp = 1; sp < splits; ++sp) v += *reinterpret_cast<const f32x4 *>(part + sp * stride + idx);
+    TC *c = C + (long)m * ldc + n;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float r = v[e];
+        if (accumulate) r += Elem<TC>::load(c + e);
+        Elem<TC>::store(c + e, r);
+    }
+}
+
+// How many K chunks for a weight-gradient GEMM: enough to give every compute unit a work item when the
+// output has few tiles (a ViT-sized layer: 16 to 64 tiles against 256 compute units, K = all tokens of the
+// pack), chunks of at least 512, and the partial products must fit the scratch buffer.
+int gemm_mfma_splits(const GemmArgs &g) {
+    if (g.layout != GEMM_TN || !g.split_ws || g.bias || g.residual) return 1;
+    const long tiles = (long)ceil_div(g.M, BM) * ceil_div(g.N, BN);
+    if (tiles > 128) return 1;
+    long s = 256 / tiles;
+    s = s < g.K / 512 ? s : g.K / 512;
+    const long fit = (long)(g.split_ws_bytes / ((size_t)g.M * g.N * 4));
+    s = s < fit ? s : fit;
+    s = s < 32 ? s : 32;
+    return s >= 2 ? (int)s : 1;
+}
+
 hipError_t gemm_mfma(const GemmArgs &g, hipStream_t st) {
+    const int splits = gemm_mfma_splits(g);
+    if (splits > 1) {
+        GemmP p;
+        p.M = g.M; p.N = g.N; p.K = g.K;
+        p.A = (const bf16_t *)g.A; p.lda = g.lda;
+        p.B = (const bf16_t *)g.B; p.ldb = g.ldb;
+        p.C = (bf16_t *)g.split_ws; p.ldc = g.N;
+        p.bias = nullptr; p.residual = nullptr; p.accumulate = 0; p.c_f32 = 1;
+        p.tiles_m = ceil_div(g.M, BM); p.tiles_n = ceil_div(g.N, BN);
+        p.splits = splits;
+        p.k_chunk = ceil_div(ceil_div(g.K, splits), BK) * BK;
+        p.splits = ceil_div(g.K, p.k_chunk);                          // no empty chunk
+        p.split_stride = (long)g.M * g.N;
+        hipError_t e = launch<false, false, false, true>(p, st);
+        if (e != hipSuccess) return e;
+        const long quads = ((long)g.M * g.N + 3) / 4;
+        if (g.c_f32)
+            splitk_reduce_kernel<float><<<ceil_div(quads, 256), 256, 0, st>>>((const float *)g.split_ws, p.splits, p.split_stride,
+                                                                            g.M, g.N, (float *)g.C, g.ldc, g.accumulate ? 1 : 0);
+        else
+            splitk_reduce_kernel<bf16_t><<<ceil_div(quads, 256), 256, 0, st>>>((const float *)g.split_ws, p.splits, p.split_stride,
+                                                                             g.M, g.N, (bf16_t *)g.C, g.ldc, g.accumulate ? 1 : 0);
+        return hipGetLastError();
+    }
     GemmP p;
+    p.splits = 1; p.k_chunk = g.K; p.split_stride = 0;
     p.M = g.M; p.N = g.N; p.K = g.K;
     p.A = (const bf16_t *)g.A; p.lda = g.lda;
     p.B = (const bf16_t *)g.B; p.ldb = g.ldb;

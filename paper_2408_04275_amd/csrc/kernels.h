@@ -19,6 +19,9 @@ struct GemmArgs {
     const void *residual;       // [M, ldc] or null
     bool accumulate;            // C += result
     bool c_f32 = false;         // C is fp32 whatever the operands' dtype (bias / residual are not combined with it)
+    // optional scratch for split-K (TN on the matrix cores only): fp32 partial products, 256-byte aligned
+    void *split_ws = nullptr;
+    size_t split_ws_bytes = 0;
 };
 
 // gemm_simple.hip: any dtype, any shape, LDS-tiled FMA kernel (the fp32 path).

@@ -68,6 +68,9 @@ SHAPES: Dict[int, LayerShape] = {
     3: LayerShape("7b-decoder-bf16", DECODER, BF16, 4096, 32, 32, 128, 11008, 8192),
     4: LayerShape("7b-decoder-bf16-longtail", DECODER, BF16, 4096, 32, 32, 128, 11008, 8192),
     5: LayerShape("72b-decoder-bf16-gqa", DECODER, BF16, 8192, 64, 8, 128, 29568, 8192),
+    # 6 is not one of the benchmark's five workloads: the published ViT-Huge encoder shape (the paper names its
+    # encoder "ViT-Huge (0.63B)" without dimensions): hidden 1280, 16 heads of 80, MLP 5120; packs as for 2
+    6: LayerShape("vit-huge-encoder-bf16", ENCODER, BF16, 1280, 16, 16, 80, 5120, 16384),
 }
 
 
@@ -153,7 +156,7 @@ def make_segments(config: int, seed: int = 0, image_bidir: bool = False):
     rng = np.random.default_rng(seed)
     if config == 1:
         lengths, kinds = [128, 96, 160, 128], ["text", "text", "text", "image"]
-    elif config == 2:
+    elif config in (2, 6):
         lengths = [int(v) for v in rng.choice([256, 576, 1024], size=16)]
         kinds = ["image"] * 16
     elif config in (3, 5):

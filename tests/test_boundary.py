@@ -54,7 +54,7 @@ def test_size_queries():
     bad = good_desc()
     bad.struct_size = 12
     assert mm.mmtrain_layer_ctx_bytes(bad, 512) == 0
-    assert mm.mmtrain_layer_workspace_bytes(good_desc(head_dim=80), 512, 4, 1) == 0
+    assert mm.mmtrain_layer_workspace_bytes(good_desc(head_dim=72), 512, 4, 1) == 0
 
 
 def fwd(desc, batch, weights=None, x=FAKE, y=FAKE + 256, ctx=FAKE, ws=FAKE, ws_bytes=1 << 40):
@@ -69,7 +69,9 @@ def batch(cu, modes=None, T=None, dev=True, mode=mm.MASK_CAUSAL):
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(head_dim=80), mm.ERR_UNSUPPORTED),
+    (dict(head_dim=72), mm.ERR_UNSUPPORTED),
+    (dict(head_dim=80, dtype=mm.F32), mm.ERR_UNSUPPORTED),
+    (dict(head_dim=256), mm.ERR_UNSUPPORTED),
     (dict(n_heads=4, n_kv_heads=3), mm.ERR_UNSUPPORTED),
     (dict(hidden=250), mm.ERR_UNSUPPORTED),
     (dict(ffn_hidden=100), mm.ERR_UNSUPPORTED),

@@ -32,6 +32,11 @@ def test_config2_encoder_full():
     full_case(2, 0)
 
 
+def test_vit_huge_encoder_full():
+    # not one of the five benchmark workloads: the ViT-Huge shape (head dimension 80) on a workload-2 pack
+    full_case(6, 1)
+
+
 def test_config3_decoder_7b_full():
     full_case(3, 0)
 

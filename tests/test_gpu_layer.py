@@ -158,3 +158,15 @@ def test_fp32_main_gradient_flag_with_fp32_storage():
     assert np.array_equal(a[1], b[1])
     for k in a[2]:
         assert np.array_equal(a[2][k], b[2][k]), k
+
+
+@pytest.mark.parametrize("kind", [wl.ENCODER, wl.DECODER])
+def test_head_dim_80(kind):
+    # ViT-Huge-like proportions at reduced width (4 heads of 80); the decoder variant exercises the rotary
+    # embedding on a head dimension that the attention kernels pad (separate rotation pass in backward)
+    shape = wl.LayerShape("hd80", kind, wl.BF16, 320, 4, 4 if kind == wl.ENCODER else 2, 80, 1280, 900)
+    rng = np.random.default_rng(41)
+    cu, modes = wl.random_segments(rng, 900, 5)
+    if kind == wl.ENCODER:
+        modes[:] = wl.BIDIR
+    run_case(shape, cu, modes, seed=9, what=f"head_dim 80 kind={kind} ")

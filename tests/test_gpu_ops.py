@@ -119,3 +119,9 @@ def test_attention_ragged(dtype, nh, nkv, d):
 def test_attention_one_long_segment(mode):
     attn_case(mm.BF16, 2, 1, 128, np.array([0, 1100], dtype=np.int32), np.array([mode], dtype=np.uint8), seed=3)
     attn_case(mm.BF16, 2, 2, 64, np.array([0, 777], dtype=np.int32), np.array([mode], dtype=np.uint8), seed=4)
+
+
+@pytest.mark.parametrize("nh,nkv,d", [(4, 4, 80), (4, 2, 80), (2, 2, 96), (4, 1, 32)])
+def test_attention_padded_head_dim(nh, nkv, d):
+    # head dimensions that are not a native tile width run zero-padded in LDS and registers (80 = ViT-Huge)
+    attn_case(mm.BF16, nh, nkv, d, RAGGED_CU, RAGGED_MODES, std=1.0, seed=7)
