@@ -170,3 +170,42 @@ def test_head_dim_80(kind):
     if kind == wl.ENCODER:
         modes[:] = wl.BIDIR
     run_case(shape, cu, modes, seed=9, what=f"head_dim 80 kind={kind} ")
+
+
+def test_hip_graph_capture_and_replay():
+    # the library neither allocates nor synchronises, so a caller may capture forward + backward in a HIP graph;
+    # every replay (with new inputs, and eager work between replays) must reproduce the eager result bit for bit
+    shape = wl.LayerShape("graph", wl.ENCODER, wl.BF16, 512, 8, 8, 64, 1024, 1400)
+    rng = np.random.default_rng(51)
+    cu, modes = wl.random_segments(rng, 1400, 6)
+    W = wl.make_weights(shape, 10, std=0.05)
+    r = LayerRunner(shape, W, cu, modes)
+    inputs = [wl.make_activations(shape, 1400, 20 + i) for i in range(3)]
+    eager = []
+    for x, dy in inputs:
+        r.set_inputs(x, dy)
+        r.step()
+        eager.append(r.results())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on the capture stream (one-time kernel attributes)
+        check(r.forward(side.cuda_stream), "fwd warm-up")
+        check(r.backward(0, side.cuda_stream), "bwd warm-up")
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        st = torch.cuda.current_stream().cuda_stream
+        check(r.forward(st), "fwd under capture")
+        check(r.backward(0, st), "bwd under capture")
+    for (x, dy), want in zip(inputs, eager):
+        r.set_inputs(x, dy)
+        torch.cuda.synchronize()
+        g.replay()
+        got = r.results()
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+        for k in want[2]:
+            assert np.array_equal(got[2][k], want[2][k]), k
+        # eager work between replays
+        r.step()
+        torch.cuda.synchronize()
