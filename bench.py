@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5, 6])
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of a HIP graph that holds one forward + backward (no per-kernel figures)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -115,6 +117,26 @@ def main():
     for _ in range(args.warmup):
         runner.step()
     torch.cuda.synchronize()
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            st = torch.cuda.current_stream().cuda_stream
+            check(runner.forward(st), "mmtrain_layer_fwd")
+            check(runner.backward(0, st), "mmtrain_layer_bwd")
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ms_per_step = dt * 1e3 / args.steps
+        print(json.dumps({"metric": "layer fwd+bwd TFLOP/s (HIP graph replay)", "value": flops["fwd_bwd"] / (ms_per_step * 1e-3) / 1e12,
+                          "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+                          "higher_is_better": True, "dtype": "bf16" if shape.dtype == wl.BF16 else "f32", "data": "synthetic",
+                          "config": {"workload": f"config {args.config}: {shape.name}", "graph": True}}))
+        return
     mm.mmtrain_profile_enable(True)
     for k in range(5):
         mm.mmtrain_profile_read(k, reset=True)

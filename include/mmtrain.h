@@ -219,6 +219,30 @@ MMTRAIN_API int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_b
 MMTRAIN_API int mmtrain_intra_reorder(const double *sizes, int32_t n, int32_t m, int32_t *order,
                                       int32_t *group_begin, double *group_load);
 
+/* Optimizer step of mixed-precision training with sharded optimizer state (Section 3: ZeRO-1 and mixed
+ * precision for the LLM backbone; Section 4.2's memory constraint counts the optimizer state of one shard
+ * per GPU).  One AdamW step, all in one pass over the shard:
+ *     g = grad * grad_scale;  m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2
+ *     master -= lr * ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps) + weight_decay * master )
+ *     param_out = master rounded to param_dtype;  grad = 0 if zero_grad
+ * (the published Adam update with decoupled weight decay).  `grad` is the fp32 main-gradient buffer that
+ * mmtrain_layer_bwd fills with MMTRAIN_BWD_WGRAD_F32 | MMTRAIN_BWD_ACCUMULATE_WGRAD.
+ *   n                 elements in the shard (any value; 0 is a no-op)
+ *   master, grad, exp_avg, exp_avg_sq   device, fp32 [n], 16-byte aligned, updated in place
+ *   param_out         device, [n] of param_dtype (MMTRAIN_BF16 or MMTRAIN_F32), 16-byte aligned, may be NULL
+ * Arithmetic in fp32; 1 - beta and the two bias corrections are evaluated in double on the host.  Enqueues one kernel on
+ * hip_stream, allocates nothing, does not synchronise.  MMTRAIN_ERR_INVALID_ARG for a bad description
+ * (struct_size, lr < 0, beta outside [0,1), eps <= 0, weight_decay < 0, step < 1), NULL or misaligned buffers. */
+typedef struct {
+    uint32_t struct_size;      /* sizeof(mmtrain_adam_desc) */
+    float lr, beta1, beta2, eps, weight_decay;
+    float grad_scale;          /* 1 / (number of microbatches accumulated), or an unscaling factor */
+    int32_t step;              /* t >= 1, the step being taken */
+    int32_t zero_grad;         /* non-zero: clear grad for the next accumulation */
+} mmtrain_adam_desc;
+MMTRAIN_API int mmtrain_adam_step(const mmtrain_adam_desc *desc, int64_t n, float *master, float *grad, float *exp_avg,
+                                  float *exp_avg_sq, void *param_out, int32_t param_dtype, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ GEMM_ACCUMULATE = 1
 
 EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_layer_fwd", "mmtrain_layer_bwd",
            "mmtrain_status_string", "mmtrain_gemm", "mmtrain_attn_workspace_bytes", "mmtrain_attn_fwd",
-           "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read", "mmtrain_intra_reorder")
+           "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read", "mmtrain_intra_reorder", "mmtrain_adam_step")
 PROF_GEMM_NT, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD = range(5)
 
 WEIGHT_FIELDS = ("norm1_w", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
@@ -38,6 +38,16 @@ class LayerDesc(C.Structure):
                 ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("ffn_hidden", C.c_int32), ("norm_eps", C.c_float), ("rope_base", C.c_float),
                 ("softmax_scale", C.c_float)]
+
+
+class AdamDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float), ("grad_scale", C.c_float), ("step", C.c_int32),
+                ("zero_grad", C.c_int32)]
+
+
+def make_adam_desc(lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, grad_scale=1.0, step=1, zero_grad=False):
+    return AdamDesc(C.sizeof(AdamDesc), lr, beta1, beta2, eps, weight_decay, grad_scale, step, 1 if zero_grad else 0)
 
 
 class Batch(C.Structure):
@@ -89,6 +99,8 @@ def load_library() -> C.CDLL:
     lib.mmtrain_profile_enable.argtypes = [C.c_int]
     lib.mmtrain_profile_read.restype = C.c_int
     lib.mmtrain_profile_read.argtypes = [I, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+    lib.mmtrain_adam_step.restype = C.c_int
+    lib.mmtrain_adam_step.argtypes = [P, C.c_int64, P, P, P, P, P, I, P]
     lib.mmtrain_intra_reorder.restype = C.c_int
     lib.mmtrain_intra_reorder.argtypes = [P, I, I, P, P, P]
     _lib = lib
@@ -160,6 +172,11 @@ def make_grads(tensors: Dict[str, object]) -> Grads:
 # ----------------------------------------------------------------------------
 def mmtrain_status_string(status: int) -> str:
     return load_library().mmtrain_status_string(status).decode()
+
+
+def mmtrain_adam_step(desc, n, master, grad, exp_avg, exp_avg_sq, param_out, param_dtype, stream=None) -> int:
+    return load_library().mmtrain_adam_step(_ref(desc), n, _ptr(master), _ptr(grad), _ptr(exp_avg), _ptr(exp_avg_sq),
+                                            _ptr(param_out), param_dtype, _stream(stream))
 
 
 def mmtrain_intra_reorder(sizes, m: int):

@@ -2,6 +2,7 @@
 // carving of ctx / workspace, and the launch sequence of one layer forward / backward.
 #include "../../include/mmtrain.h"
 #include "kernels.h"
+#include <cmath>
 #include <vector>
 
 using namespace mmt;
@@ -499,6 +500,30 @@ int mmtrain_intra_reorder(const double *sizes, int32_t n, int32_t m, int32_t *or
     for (int32_t i = 0; i < n; ++i)
         if (!(sizes[i] >= 0.0) || sizes[i] > 1e300) return MMTRAIN_ERR_INVALID_ARG;     // also rejects NaN
     intra_reorder(sizes, n, m, order, group_begin, group_load);
+    return MMTRAIN_OK;
+}
+
+int mmtrain_adam_step(const mmtrain_adam_desc *d, int64_t n, float *master, float *grad, float *exp_avg,
+                      float *exp_avg_sq, void *param_out, int32_t param_dtype, void *hip_stream) {
+    if (!d || d->struct_size != sizeof(mmtrain_adam_desc) || n < 0) return MMTRAIN_ERR_INVALID_ARG;
+    if (param_dtype != MMTRAIN_F32 && param_dtype != MMTRAIN_BF16) return MMTRAIN_ERR_INVALID_ARG;
+    if (!(d->lr >= 0.f) || !(d->beta1 >= 0.f && d->beta1 < 1.f) || !(d->beta2 >= 0.f && d->beta2 < 1.f) || !(d->eps > 0.f) ||
+        !(d->weight_decay >= 0.f) || !(d->grad_scale == d->grad_scale) || d->step < 1)
+        return MMTRAIN_ERR_INVALID_ARG;
+    if (n == 0) return MMTRAIN_OK;
+    if (!master || !grad || !exp_avg || !exp_avg_sq) return MMTRAIN_ERR_INVALID_ARG;
+    if (((uintptr_t)master | (uintptr_t)grad | (uintptr_t)exp_avg | (uintptr_t)exp_avg_sq | (uintptr_t)param_out) & 15)
+        return MMTRAIN_ERR_INVALID_ARG;
+    AdamArgs a;
+    a.lr = d->lr; a.beta1 = d->beta1; a.beta2 = d->beta2; a.eps = d->eps; a.weight_decay = d->weight_decay;
+    a.grad_scale = d->grad_scale;
+    // 1 - beta and the bias corrections in double on the host: in fp32, 1 - 0.999 is off by 5e-5 and 1 - beta^t
+    // loses most of its digits for small t
+    a.omb1 = (float)(1.0 - (double)d->beta1); a.omb2 = (float)(1.0 - (double)d->beta2);
+    a.inv_bias1 = (float)(1.0 / (1.0 - pow((double)d->beta1, (double)d->step)));
+    a.inv_bias2 = (float)(1.0 / (1.0 - pow((double)d->beta2, (double)d->step)));
+    a.zero_grad = d->zero_grad ? 1 : 0;
+    HIP_TRY(adam_step(param_dtype, (size_t)n, master, grad, exp_avg, exp_avg_sq, param_out, a, (hipStream_t)hip_stream));
     return MMTRAIN_OK;
 }
 

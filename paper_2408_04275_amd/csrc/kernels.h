@@ -91,4 +91,14 @@ hipError_t swiglu_bwd(int dtype, const void *d_m, const void *gu, void *d_gu, in
 hipError_t gelu_fwd(int dtype, const void *z, void *a, long n, hipStream_t st);
 hipError_t gelu_bwd(int dtype, const void *d_a, const void *z, void *d_z, long n, hipStream_t st);
 
+
+// optimizer.hip: one AdamW step on fp32 master weights; omb = 1 - beta, inv_bias1 = 1 / (1 - beta1^t),
+// inv_bias2 = 1 / (1 - beta2^t), all four evaluated in double by the caller
+struct AdamArgs {
+    float lr, beta1, beta2, omb1, omb2, eps, weight_decay, grad_scale, inv_bias1, inv_bias2;
+    int zero_grad;
+};
+hipError_t adam_step(int param_dtype, size_t n, float *w, float *g, float *m, float *v, void *p, const AdamArgs &a,
+                     hipStream_t st);
+
 }  // namespace mmt

@@ -73,6 +73,22 @@ def bench_attn(a):
                       "fwd_tflops": fl / ms_f / 1e9, "bwd_tflops": 2 * fl / ms_b / 1e9}))
 
 
+def bench_adam(a):
+    """One AdamW step over n fp32 master weights (+ bf16 working copy, gradient cleared): bytes moved per second."""
+    n = a.mparams * 1_000_000
+    g = torch.Generator(device="cuda").manual_seed(0)
+    w = torch.randn(n, device="cuda", generator=g)
+    gr = torch.randn(n, device="cuda", generator=g)
+    m = torch.zeros(n, device="cuda")
+    v = torch.zeros(n, device="cuda")
+    out = torch.empty(n, device="cuda", dtype=torch.bfloat16)
+    desc = mm.make_adam_desc(1e-4, 0.9, 0.95, 1e-8, 0.1, 1.0, 1, zero_grad=True)
+    ms = _time(lambda: check(mm.mmtrain_adam_step(desc, n, w, gr, m, v, out, mm.BF16), "adam"), a.iters)
+    nbytes = n * (16 + 12 + 2 + 4)
+    print(json.dumps({"op": "adam", "n": n, "ms": ms, "GB_per_s": nbytes / ms / 1e6, "bytes_per_element": 34,
+                      "frac_of_8TBps": nbytes / ms / 1e6 / 8000.0}))
+
+
 def bench_copy(a):
     n = a.mb * (1 << 20)
     src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
@@ -94,12 +110,15 @@ def main(argv=None):
     t = sub.add_parser("attn")
     t.add_argument("--config", type=int, default=3)
     t.add_argument("--iters", type=int, default=20)
+    ad = sub.add_parser("adam")
+    ad.add_argument("--mparams", type=int, default=202, help="millions of parameters (202 = one 7B layer)")
+    ad.add_argument("--iters", type=int, default=20)
     c = sub.add_parser("copy")
     c.add_argument("--mb", type=int, default=512)
     c.add_argument("--iters", type=int, default=10)
     a = ap.parse_args(argv)
     mm.load_library()
-    {"gemm": bench_gemm, "attn": bench_attn, "copy": bench_copy}[a.op](a)
+    {"gemm": bench_gemm, "attn": bench_attn, "copy": bench_copy, "adam": bench_adam}[a.op](a)
 
 
 if __name__ == "__main__":
