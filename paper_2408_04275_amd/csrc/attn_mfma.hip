@@ -1,28 +1,35 @@
 // Segment-masked flash attention on the gfx950 matrix cores (bf16 in, fp32 accumulate),
 // forward and backward, for packed variable-length segments.
 //
-// Tiling is on the GLOBAL token index, not per segment: workgroup (t, head) owns queries
-// [128 t, 128 t + 128), one query per lane (4 wavefronts x 32 queries, both lane halves of a
-// wavefront mirror the same 32 queries).  Every query carries its own key range
+// Tiling is on the GLOBAL token index, not per segment: a workgroup owns a run of consecutive queries
+// (256 in the forward and dQ kernels, one query per lane of 8 wavefronts; both lane halves of a wavefront
+// mirror the same 32 queries) or keys (128 in the dK/dV kernel).  Every query carries its own key range
 // [lo, hi) = [segment start, causal ? q + 1 : segment end), so a tile may straddle any number of
 // segment boundaries and a pack of many short segments still fills whole tiles.  The key loop of
 // a workgroup runs over [lo(first query), hi(last query)) only: tiles that are fully masked for
 // the workgroup are never loaded, and 32-key blocks that are fully masked for one wavefront are
-// skipped by that wavefront (causal lower triangle, other segments).
+// skipped by that wavefront (causal lower triangle, other segments).  The tiles of a launch differ a lot
+// in work (a query tile at the end of a long causal segment walks many more keys than one at its start):
+// they are dispatched heaviest first, with the head index fastest, from a table the host computes
+// (longest-first scheduling as in the paper's Algorithm 1, applied to the GPU's work items).
 //
 // All score tiles are computed TRANSPOSED (keys x queries): S^T = K . Q^T with the MFMA's row
 // operand = keys and column operand = queries.  A lane then holds 16 keys of ONE query per
 // 32-key block, so the softmax row reductions are in-lane plus one cross-half exchange, the
 // running max / sum / log-sum-exp / D are per-lane scalars, and P^T (or dS^T) is already laid
 // out as the column operand of the next MFMA: O^T = V^T . P^T, dQ^T = K^T . dS^T.  The row
-// operand of those products needs the K or V tile transposed ([feature][key]); tiles are
-// transposed in registers (8x8 blocks, byte permutes) on their way from global memory to LDS,
-// with the 128 keys of a row stored in the order in which the accumulator registers hold them.
+// operand of those products is the K or V tile transposed ([feature][key]), its keys in the order in
+// which the accumulator registers hold them: the forward kernel transposes V in registers on its way to
+// LDS, the backward kernels form the transposed fragments with the transposing LDS read.
 //
 // The backward pass is two kernels: dQ (same roles as forward; also writes D = rowsum(dO * O)),
 // then dK/dV with one KEY per lane, looping over the query tiles that can see the workgroup's
 // keys and over the query heads of the key/value head's group, so grouped-query gradients are
 // summed in registers and nothing needs atomics: results are deterministic.
+//
+// Head dimensions: the kernels are instantiated for 64 and 128 features; a head of another width (a
+// multiple of 16, e.g. 80) uses the next instantiation with the missing features read as zero and never
+// stored.
 #include "kernels.h"
 #include <type_traits>
 #include <utility>
@@ -31,8 +38,7 @@ namespace mmt {
 
 namespace {
 
-constexpr int BQ = 128;        // queries (or keys, in the dK/dV kernel) per workgroup
-constexpr int BT = 128;        // rows of the tile walked by the inner loop
+constexpr int BQ = 128;        // keys per workgroup of the dK/dV kernel
 constexpr int END_MASK = 0x3fffffff;
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
 
@@ -54,68 +60,6 @@ __device__ __forceinline__ bf16x8 pack8(const float *v) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) r[i] = (__bf16)v[i];
     return r;
-}
-
-// Row r (0..127) of a tile whose rows are visited in accumulator order: unit u = (block b, mfma m, half hh)
-// holds rows 32 b + 16 m + 8 (kk >> 2) + 4 hh + (kk & 3), kk = 0..7.
-__device__ __forceinline__ int unit_row(int u, int kk) {
-    return 32 * (u >> 2) + 16 * ((u >> 1) & 1) + 8 * (kk >> 2) + 4 * (u & 1) + (kk & 3);
-}
-
-// One thread's share of a [128 rows][D] tile: the 8 rows of unit u, 8 features (16 bytes) of each.
-// From the same registers the tile can be written row-major ([row][D]) and transposed ([feature][128]).
-template <int D>
-struct TileLoader {
-    static constexpr int UPR = D / 8;          // 16-byte units per row
-    uint4 r[8];
-    __device__ __forceinline__ bool active() const { return threadIdx.x < 16 * UPR; }
-    // base: element pointer to (row 0, feature 0) of the packed tensor; ld in elements; rows >= nrows read as 0
-    __device__ __forceinline__ void load(const bf16_t *base, long ld, int row0, int nrows) {
-        if (!active()) return;
-        const int cb = threadIdx.x % UPR, u = threadIdx.x / UPR;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const int row = row0 + unit_row(u, kk);
-            r[kk] = make_uint4(0, 0, 0, 0);
-            if (row < nrows) r[kk] = *reinterpret_cast<const uint4 *>(base + (long)row * ld + cb * 8);
-        }
-    }
-    __device__ __forceinline__ void store_rows(uint8_t *tile) const {
-        if (!active()) return;
-        const int cb = threadIdx.x % UPR, u = threadIdx.x / UPR;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const int row = unit_row(u, kk);
-            *reinterpret_cast<uint4 *>(tile + (row * UPR + (cb ^ swz(row))) * 16) = r[kk];
-        }
-    }
-    __device__ __forceinline__ void store_transposed(uint8_t *tile) const {
-        if (!active()) return;
-        const int cb = threadIdx.x % UPR, u = threadIdx.x / UPR;
-        const uint32_t *w = reinterpret_cast<const uint32_t *>(r);
-#pragma unroll
-        for (int rr = 0; rr < 8; ++rr) {
-            const uint32_t sel = (rr & 1) ? 0x07060302u : 0x05040100u;
-            uint4 o;
-            o.x = __builtin_amdgcn_perm(w[1 * 4 + (rr >> 1)], w[0 * 4 + (rr >> 1)], sel);
-            o.y = __builtin_amdgcn_perm(w[3 * 4 + (rr >> 1)], w[2 * 4 + (rr >> 1)], sel);
-            o.z = __builtin_amdgcn_perm(w[5 * 4 + (rr >> 1)], w[4 * 4 + (rr >> 1)], sel);
-            o.w = __builtin_amdgcn_perm(w[7 * 4 + (rr >> 1)], w[6 * 4 + (rr >> 1)], sel);
-            const int c = cb * 8 + rr;
-            *reinterpret_cast<uint4 *>(tile + (c * 16 + (u ^ swz(c))) * 16) = o;
-        }
-    }
-};
-
-// fragment of a row-major [128][D] tile: row, k-slice ks (16 features), lane half
-template <int D>
-__device__ __forceinline__ bf16x8 frag_rows(const uint8_t *tile, int row, int ks, int half) {
-    constexpr int UPR = D / 8;
-    return *reinterpret_cast<const bf16x8 *>(tile + (row * UPR + ((ks * 2 + half) ^ swz(row))) * 16);
-}
-// fragment of a transposed [D][128] tile: feature row c, unit u
-__device__ __forceinline__ bf16x8 frag_tr(const uint8_t *tile, int c, int u) {
-    return *reinterpret_cast<const bf16x8 *>(tile + (c * 16 + (u ^ swz(c))) * 16);
 }
 
 __device__ __forceinline__ f32x16 zero16() {
