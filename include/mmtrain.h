@@ -184,10 +184,19 @@ typedef enum {
 /* C = op(A).op(B) (+ bias[N] broadcast over rows) (+ residual[M,N], leading dimension ldc).
  * Row-major with leading dimensions lda/ldb/ldc in elements.  fp32 accumulation.
  * bf16: K-contiguous operands need K % 8 == 0, strided ones N (or M) % 8 == 0, and
- * lda, ldb, ldc multiples of 8; otherwise MMTRAIN_ERR_UNSUPPORTED. */
+ * lda, ldb, ldc multiples of 8; otherwise MMTRAIN_ERR_UNSUPPORTED.
+ * workspace (device memory, 256-byte aligned, caller-owned, may be NULL with 0 bytes) is
+ * scratch for fp32 partial products.  With it, a bf16 NN or TN product without bias or
+ * residual may be cut along K where that fills the chip better: a weight gradient whose
+ * output has few 256 x 256 tiles, or the partly filled last round of tiles of a large
+ * product.  mmtrain_gemm_workspace_bytes() returns a size that allows every such cut; a
+ * smaller workspace only restricts them, and the result does not depend on timing (the
+ * partial products are added in a fixed order). */
+MMTRAIN_API size_t mmtrain_gemm_workspace_bytes(int32_t layout, int32_t M, int32_t N);
 MMTRAIN_API int mmtrain_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K,
                  const void *A, int32_t lda, const void *B, int32_t ldb, void *C, int32_t ldc,
-                 const void *bias, const void *residual, uint32_t flags, void *hip_stream);
+                 const void *bias, const void *residual, uint32_t flags,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Bytes of workspace for the two attention operators below. */
 MMTRAIN_API size_t mmtrain_attn_workspace_bytes(int32_t total_tokens, int32_t n_segments, int32_t n_heads);

@@ -25,7 +25,7 @@ BWD_WGRAD_F32 = 2
 GEMM_ACCUMULATE = 1
 
 EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_layer_fwd", "mmtrain_layer_bwd",
-           "mmtrain_status_string", "mmtrain_gemm", "mmtrain_attn_workspace_bytes", "mmtrain_attn_fwd",
+           "mmtrain_status_string", "mmtrain_gemm", "mmtrain_gemm_workspace_bytes", "mmtrain_attn_workspace_bytes", "mmtrain_attn_fwd",
            "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read", "mmtrain_intra_reorder", "mmtrain_adam_step")
 PROF_GEMM_NT, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD = range(5)
 
@@ -88,7 +88,9 @@ def load_library() -> C.CDLL:
     lib.mmtrain_status_string.restype = C.c_char_p
     lib.mmtrain_status_string.argtypes = [C.c_int]
     lib.mmtrain_gemm.restype = C.c_int
-    lib.mmtrain_gemm.argtypes = [I, I, I, I, I, P, I, P, I, P, I, P, P, U, P]
+    lib.mmtrain_gemm.argtypes = [I, I, I, I, I, P, I, P, I, P, I, P, P, U, P, S, P]
+    lib.mmtrain_gemm_workspace_bytes.restype = S
+    lib.mmtrain_gemm_workspace_bytes.argtypes = [I, I, I]
     lib.mmtrain_attn_workspace_bytes.restype = S
     lib.mmtrain_attn_workspace_bytes.argtypes = [I, I, I]
     lib.mmtrain_attn_fwd.restype = C.c_int
@@ -219,10 +221,15 @@ def mmtrain_layer_bwd(desc, batch, weights, x, dy, ctx, dx, grads, flags, worksp
                                             _stream(stream))
 
 
+def mmtrain_gemm_workspace_bytes(layout: int, M: int, N: int) -> int:
+    return load_library().mmtrain_gemm_workspace_bytes(layout, M, N)
+
+
 def mmtrain_gemm(dtype, layout, M, N, K, A, lda, B, ldb, Cmat, ldc, bias=None, residual=None, flags=0,
-                 stream=None) -> int:
+                 workspace=None, workspace_bytes=0, stream=None) -> int:
     return load_library().mmtrain_gemm(dtype, layout, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cmat), ldc,
-                                       _ptr(bias), _ptr(residual), flags, _stream(stream))
+                                       _ptr(bias), _ptr(residual), flags, _ptr(workspace), workspace_bytes,
+                                       _stream(stream))
 
 
 def mmtrain_attn_workspace_bytes(total_tokens: int, n_segments: int, n_heads: int) -> int:

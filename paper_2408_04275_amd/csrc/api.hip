@@ -113,6 +113,16 @@ void carve_ctx(Bump &b, const Dims &D, size_t T, Ctx &c) {
     c.m = b.take_elems(T * D.F, D.dtype);
 }
 
+// Scratch that lets an M x N gradient GEMM be cut along K in both ways the bf16 kernel knows: few output tiles
+// (gemm_mfma_splits: up to 256 / tiles products of M x N, 32 at most), or a partly filled last round of tiles
+// (gemm_mfma_tail_splits: never more than 256 blocks of 256 x 256).
+size_t gemm_scratch_bytes(size_t M, size_t N) {
+    const size_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    if (tiles > 128) return tiles % 256 && tiles % 256 <= 128 ? size_t(256) * 256 * 256 * 4 : 0;
+    const size_t s = 256 / tiles < 32 ? 256 / tiles : 32;
+    return s >= 2 ? s * M * N * 4 : 0;
+}
+
 void carve_bwd(Bump &b, const Dims &D, size_t T, BwdWs &w) {
     w.d_m = b.take_elems(T * D.F, D.dtype);
     w.d_pre = b.take_elems(T * D.F1, D.dtype);
@@ -125,17 +135,12 @@ void carve_bwd(Bump &b, const Dims &D, size_t T, BwdWs &w) {
     w.part_b = b.take<float>((size_t)norm_bwd_blocks((int)T) * D.H);
     const int maxn = D.nqkv > D.F1 ? (D.nqkv > D.H ? D.nqkv : D.H) : (D.F1 > D.H ? D.F1 : D.H);
     w.part_c = b.take<float>((size_t)colsum_slabs((int)T) * maxn);
-    // scratch for the weight-gradient GEMMs whose output has few tiles (see gemm_mfma_splits): up to 256 / tiles
-    // partial products of M x N fp32
-    auto need = [](size_t M, size_t N) -> size_t {
-        const size_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
-        if (tiles > 128) return 0;
-        const size_t s = 256 / tiles < 32 ? 256 / tiles : 32;
-        return s * M * N * 4;
-    };
+    // scratch for the fp32 partial products of GEMMs that are cut along K (see gemm_scratch_bytes)
+    auto need = [](size_t M, size_t N) -> size_t { return gemm_scratch_bytes(M, N); };
     size_t sb = 0;
     if (D.dtype == DT_BF16) {
-        const size_t c[4] = {need(D.H, D.F), need(D.F1, D.H), need(D.H, D.nq), need(D.nqkv, D.H)};
+        const size_t c[8] = {need(D.H, D.F), need(D.F1, D.H), need(D.H, D.nq), need(D.nqkv, D.H),
+                             need(T, D.F), need(T, D.H), need(T, D.nq), 0};
         for (size_t v : c) sb = v > sb ? v : sb;
     }
     w.split_bytes = sb;
@@ -143,6 +148,7 @@ void carve_bwd(Bump &b, const Dims &D, size_t T, BwdWs &w) {
 }
 
 hipError_t gemm(int dtype, const GemmArgs &g, hipStream_t st);
+
 
 // bf16 storage runs on the matrix cores; fp32 storage on the vector ALUs
 hipError_t attn_fwd(int dtype, const AttnArgs &a, hipStream_t st) {
@@ -339,7 +345,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     const int nb = norm_bwd_blocks(T), ns = colsum_slabs(T);
 
     // ---- MLP block:  y = y1 + m . Wfc2^T (+ b_fc2)
-    HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), st));
+    HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), w.split_ws, w.split_bytes), st));
     if (G.w_fc2) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     if (enc && G.b_fc2) {
         HIP_TRY(colsum_partials(D.dtype, dy, T, D.H, D.H, w.part_c, st));
@@ -351,7 +357,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
         HIP_TRY(colsum_partials(D.dtype, w.d_pre, T, D.F1, D.F1, w.part_c, st));
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.F1, G.b_fc1, accum, st));
     }
-    HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.H, D.F1, w.d_pre, D.F1, W->w_fc1, D.H, w.d_h, D.H), st));
+    HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.H, D.F1, w.d_pre, D.F1, W->w_fc1, D.H, w.d_h, D.H), w.split_ws, w.split_bytes), st));
     if (G.w_fc1) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     // d_y1 = dy + norm2_bwd(d_h2)
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
@@ -360,7 +366,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     if (enc && G.norm2_b) HIP_TRY(reduce_partials(gdt, w.part_b, nb, D.H, G.norm2_b, accum, st));
 
     // ---- attention block:  y1 = x + o . Wo^T (+ b_o)
-    HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.nq, D.H, w.d_y1, D.H, W->w_o, D.nq, w.d_o, D.nq), st));
+    HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.nq, D.H, w.d_y1, D.H, W->w_o, D.nq, w.d_o, D.nq), w.split_ws, w.split_bytes), st));
     if (G.w_o) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.nq, T, w.d_y1, D.H, c.o, D.nq, G.w_o, D.nq, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     if (enc && G.b_o) {
         HIP_TRY(colsum_partials(D.dtype, w.d_y1, T, D.H, D.H, w.part_c, st));
@@ -379,7 +385,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
         HIP_TRY(colsum_partials(D.dtype, w.d_qkv, T, D.nqkv, D.nqkv, w.part_c, st));
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.nqkv, G.b_qkv, accum, st));
     }
-    HIP_TRY(gemm(D.dtype, mk(GEMM_NN, T, D.H, D.nqkv, w.d_qkv, D.nqkv, W->w_qkv, D.H, w.d_h, D.H), st));
+    HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.H, D.nqkv, w.d_qkv, D.nqkv, W->w_qkv, D.H, w.d_h, D.H), w.split_ws, w.split_bytes), st));
     if (G.w_qkv) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     // dx = d_y1 + norm1_bwd(d_h1)
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
@@ -420,7 +426,7 @@ int mmtrain_profile_read(int32_t kind, double *total_ms, int64_t *launches, int 
 
 int mmtrain_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, int32_t lda,
                  const void *B, int32_t ldb, void *C, int32_t ldc, const void *bias, const void *residual,
-                 uint32_t flags, void *hip_stream) {
+                 uint32_t flags, void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (dtype != MMTRAIN_F32 && dtype != MMTRAIN_BF16) return MMTRAIN_ERR_INVALID_ARG;
     if (layout < MMTRAIN_GEMM_NT || layout > MMTRAIN_GEMM_TN) return MMTRAIN_ERR_INVALID_ARG;
     if (M < 0 || N < 0 || K < 0 || (flags & ~MMTRAIN_GEMM_ACCUMULATE)) return MMTRAIN_ERR_INVALID_ARG;
@@ -428,10 +434,19 @@ int mmtrain_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K,
     if (!C || (K > 0 && (!A || !B))) return MMTRAIN_ERR_INVALID_ARG;
     const int min_lda = layout == MMTRAIN_GEMM_TN ? M : K, min_ldb = layout == MMTRAIN_GEMM_NT ? K : N;
     if (lda < min_lda || ldb < min_ldb || ldc < N) return MMTRAIN_ERR_INVALID_ARG;
+    if ((workspace_bytes && !workspace) || ((uintptr_t)workspace & 255)) return MMTRAIN_ERR_INVALID_ARG;
     GemmArgs g = mk(layout, M, N, K, A, lda, B, ldb, C, ldc, bias, residual, flags & MMTRAIN_GEMM_ACCUMULATE);
+    if (workspace_bytes) g = splittable(g, workspace, workspace_bytes);
     if (dtype == MMTRAIN_BF16 && !gemm_mfma_supported(g) && K > 0) return MMTRAIN_ERR_UNSUPPORTED;
     HIP_TRY(gemm(dtype, g, (hipStream_t)hip_stream));
     return MMTRAIN_OK;
+}
+
+size_t mmtrain_gemm_workspace_bytes(int32_t layout, int32_t M, int32_t N) {
+    if (M <= 0 || N <= 0 || (layout != MMTRAIN_GEMM_NN && layout != MMTRAIN_GEMM_TN)) return 0;
+    const size_t tiles = (((size_t)M + 255) / 256) * (((size_t)N + 255) / 256);
+    if (layout == MMTRAIN_GEMM_NN && tiles <= 128) return 0;       // only weight gradients are cut when tiles are few
+    return gemm_scratch_bytes((size_t)M, (size_t)N);
 }
 
 size_t mmtrain_attn_workspace_bytes(int32_t total_tokens, int32_t n_segments, int32_t n_heads) {

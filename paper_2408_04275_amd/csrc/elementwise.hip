@@ -157,14 +157,23 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ d_o
     for (size_t row = blockIdx.x; row < (size_t)nrows; row += gridDim.x) {
         const float r = rstd[row];
         const float mu = LN ? mean[row] : 0.f;
-        float dv[NORM_BWD_MAXC][8], xh[NORM_BWD_MAXC][8];
+        float dv[NORM_BWD_MAXC][8], xh[NORM_BWD_MAXC][8], rv[NORM_BWD_MAXC][8];
         float s0 = 0.f, s1 = 0.f;
+        // all three inputs of the row are requested before the first use: the gradient that is added at the end
+        // would otherwise be fetched only after the row reductions, a second exposed memory latency per row
 #pragma unroll
         for (int i = 0; i < NORM_BWD_MAXC; ++i) {
             const int c = (threadIdx.x + i * 256) * 8;
             if (c < H) {
                 load8(d_out + row * H + c, dv[i]);
                 load8(x + row * H + c, xh[i]);
+                load8(d_res + row * H + c, rv[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NORM_BWD_MAXC; ++i) {
+            const int c = (threadIdx.x + i * 256) * 8;
+            if (c < H) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     xh[i][j] = (xh[i][j] - mu) * r;
@@ -182,11 +191,9 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ d_o
         for (int i = 0; i < NORM_BWD_MAXC; ++i) {
             const int c = (threadIdx.x + i * 256) * 8;
             if (c < H) {
-                float rv[8];
-                load8(d_res + row * H + c, rv);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) rv[j] += r * (dv[i][j] - s0 - xh[i][j] * s1);
-                store8(d_in + row * H + c, rv);
+                for (int j = 0; j < 8; ++j) rv[i][j] += r * (dv[i][j] - s0 - xh[i][j] * s1);
+                store8(d_in + row * H + c, rv[i]);
             }
         }
     }
@@ -214,7 +221,9 @@ hipError_t norm_bwd(int dtype, bool layernorm, const void *d_out, const void *x,
 }
 
 // ---- partial-sum reduction -----------------------------------------------------------
-// 32 columns per workgroup; 8 row lanes per column walk the partial rows, then combine through LDS.
+// 32 columns per workgroup.  Vector form (N a multiple of 4): 8 lanes cover the 32 columns with 16 bytes each and
+// 32 row lanes walk the partial rows; scalar form: 32 column lanes, 8 row lanes.  Both combine through LDS in a
+// fixed order.
 template <typename T>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int rows, int N,
                                                               T *__restrict__ out, bool accumulate) {
@@ -234,11 +243,38 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     }
 }
 
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_partials_vec_kernel(const float *__restrict__ part, int rows, int N,
+                                                                  T *__restrict__ out, bool accumulate) {
+    __shared__ float red[32][36];
+    const int cl = threadIdx.x & 7, rl = threadIdx.x >> 3;
+    const int c = blockIdx.x * 32 + cl * 4;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (c < N)
+        for (int r = rl; r < rows; r += 32) s += *reinterpret_cast<const f32x4 *>(part + (size_t)r * N + c);
+    *reinterpret_cast<f32x4 *>(&red[rl][cl * 4]) = s;
+    __syncthreads();
+    const int oc = blockIdx.x * 32 + threadIdx.x;
+    if (threadIdx.x < 32 && oc < N) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) t += red[i][threadIdx.x];
+        if (accumulate) t += Elem<T>::load(out + oc);
+        Elem<T>::store(out + oc, t);
+    }
+}
+
 hipError_t reduce_partials(int dtype, const float *part, int rows, int N, void *out, bool accumulate,
                            hipStream_t st) {
     if (N == 0) return hipSuccess;
-    if (dtype == DT_F32) reduce_partials_kernel<float><<<ceil_div(N, 32), 256, 0, st>>>(part, rows, N, (float *)out, accumulate);
-    else reduce_partials_kernel<bf16_t><<<ceil_div(N, 32), 256, 0, st>>>(part, rows, N, (bf16_t *)out, accumulate);
+    const int grid = ceil_div(N, 32);
+    if (N % 4 == 0) {
+        if (dtype == DT_F32) reduce_partials_vec_kernel<float><<<grid, 256, 0, st>>>(part, rows, N, (float *)out, accumulate);
+        else reduce_partials_vec_kernel<bf16_t><<<grid, 256, 0, st>>>(part, rows, N, (bf16_t *)out, accumulate);
+    } else {
+        if (dtype == DT_F32) reduce_partials_kernel<float><<<grid, 256, 0, st>>>(part, rows, N, (float *)out, accumulate);
+        else reduce_partials_kernel<bf16_t><<<grid, 256, 0, st>>>(part, rows, N, (bf16_t *)out, accumulate);
+    }
     return hipGetLastError();
 }
 

@@ -1,11 +1,11 @@
-// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_16x16x32_bf16), fp32 accumulation.
 //
 //   C[M,N] (+)= opA(A) . opB(B) (+ bias[N]) (+ residual[M,N])
 //
 // Tiling.  One 256-thread workgroup (4 wavefronts, one per SIMD) owns a 256x256 tile of C;
-// each wavefront owns a 128x128 quadrant as 4x4 MFMA tiles of 32x32 (256 accumulator
-// registers per lane).  K advances in slices of 64 through a double-buffered LDS stage of
-// 2 x (256x64 A + 256x64 B) bf16 = 128 KiB of the CU's 160 KiB.
+// each wavefront owns a 128x128 quadrant as 8x8 MFMA tiles of 16x16 (256 accumulator
+// registers per lane).  K advances in steps of 64; the 32 KiB operand tiles (256 rows x 64 k) of
+// successive steps go round a ring of five LDS slots, which is all of the CU's 160 KiB.
 //
 // Global -> LDS.  Every operand tile is copied 16 bytes per lane directly into LDS (buffer_load ... lds:
 // no register staging, no LDS write instructions), in the operand's own memory order, so weight- and
@@ -57,7 +57,20 @@ struct GemmP {
     // every tile is a work item of its own and writes the partial product to C + s * split_stride (fp32 elements)
     int splits, k_chunk;
     long split_stride;
+    // A launch covers tiles [tile_begin, tile_begin + tile_count) of the tile order.  With `compact` (fp32 output)
+    // the partial product of chunk s of the launch's tile j is a dense 256 x 256 block at
+    // C + (s * tile_count + j) * 65536 instead of a window of an M x N matrix.
+    int tile_begin, tile_count, compact;
 };
+
+// position t of the tile order -> tile coordinates: column-major inside groups of GROUP_M tile-rows
+__device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int &tm, int &tn) {
+    const int width = GROUP_M * tiles_n;
+    const int group = t / width, first_m = group * GROUP_M;
+    const int gsize = min(tiles_m - first_m, GROUP_M);
+    tm = first_m + (t % width) % gsize;
+    tn = (t % width) / gsize;
+}
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
@@ -247,8 +260,7 @@ void gemm_mfma_kernel(const GemmP p) {
 
     // ---- persistent workgroup -> tiles.  Workgroup b runs on XCD b % 8 (round-robin dispatch); XCD x
     // owns a contiguous run of the tile order, and its workgroups stride through that run together.
-    const int tiles_mn = p.tiles_m * p.tiles_n;
-    const int ntiles = tiles_mn * (OUT_F32 ? p.splits : 1);   // work items: (K chunk, tile), chunk-major
+    const int ntiles = p.tile_count * (OUT_F32 ? p.splits : 1);   // work items: (K chunk, tile), chunk-major
     const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
     const int per = ntiles >> 3, rem = ntiles & 7;
     const int run_begin = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
@@ -276,17 +288,11 @@ void gemm_mfma_kernel(const GemmP p) {
 
     for (int logical = run_begin + q; logical < run_end; logical += wg_per_xcd) {
     int tm, tn;
-    const int chunk = OUT_F32 ? logical / tiles_mn : 0;
-    {
-        const int t = logical - chunk * tiles_mn;
-        const int width = GROUP_M * p.tiles_n;
-        const int group = t / width, first_m = group * GROUP_M;
-        const int gsize = min(p.tiles_m - first_m, GROUP_M);
-        tm = first_m + (t % width) % gsize;
-        tn = (t % width) / gsize;
-    }
+    const int chunk = OUT_F32 ? logical / p.tile_count : 0;
+    const int tl = logical - chunk * p.tile_count;             // tile within this launch
+    tile_coords(p.tile_begin + tl, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
-    // this work item's K range (only the fp32-output kernel, whose operands are both K-strided, is ever split)
+    // this work item's K range (only the fp32-output kernels are ever split)
     const int k_begin = OUT_F32 ? chunk * p.k_chunk : 0;
     const int Kc = OUT_F32 ? min(p.k_chunk, p.K - k_begin) : p.K;
 
@@ -490,7 +496,9 @@ void gemm_mfma_kernel(const GemmP p) {
                 }
                 if (OUT_F32) {
                     // fp32 output (never together with bias or residual): previous contents are read here
-                    float *cf = reinterpret_cast<float *>(p.C) + (size_t)chunk * p.split_stride + off;
+                    float *cf = reinterpret_cast<float *>(p.C) +
+                                (p.compact ? ((size_t)(chunk * p.tile_count + tl) << 16) + (size_t)(gm - m0) * BN + (gn - n0)
+                                           : (size_t)chunk * p.split_stride + off);
                     if (p.accumulate) {
                         const float4 c0 = *reinterpret_cast<const float4 *>(cf), c1 = *reinterpret_cast<const float4 *>(cf + 4);
                         v[0] += c0.x; v[1] += c0.y; v[2] += c0.z; v[3] += c0.w;
@@ -514,6 +522,22 @@ void gemm_mfma_kernel(const GemmP p) {
     }   // tiles of this workgroup
 }
 
+// compute units of the current device, rounded down to whole XCD octets (one persistent workgroup each)
+hipError_t compute_units(int &n) {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (v <= 0) v = 256;
+        v &= ~7;
+        n_cu = v ? v : 8;
+    }
+    n = n_cu;
+    return hipSuccess;
+}
+
 template <bool A_KC, bool B_KC, bool HAS_ADD, bool OUT_F32 = false>
 hipError_t launch(const GemmP &p, hipStream_t st) {
     static bool configured = false;
@@ -525,36 +549,13 @@ hipError_t launch(const GemmP &p, hipStream_t st) {
         configured = true;
     }
     // one persistent workgroup per compute unit (the tile needs the CU's whole LDS and register file)
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        if (n_cu <= 0) n_cu = 256;
-        n_cu &= ~7;
-        if (n_cu == 0) n_cu = 8;
-    }
-    const int tiles = p.tiles_m * p.tiles_n * (OUT_F32 ? p.splits : 1);
-    kern<<<tiles < n_cu ? tiles : n_cu, 256, SMEM_BYTES, st>>>(p);
+    int n_cu = 0;
+    hipError_t e = compute_units(n_cu);
+    if (e != hipSuccess) return e;
+    const int items = p.tile_count * (OUT_F32 ? p.splits : 1);
+    if (items <= 0) return hipSuccess;
+    kern<<<items < n_cu ? items : n_cu, 256, SMEM_BYTES, st>>>(p);
     return hipGetLastError();
-}
-
-}  // namespace
-
-bool gemm_mfma_supported(const GemmArgs &g) {
-    if (g.M <= 0 || g.N <= 0 || g.K <= 0) return false;
-    if (g.c_f32 && (g.layout != GEMM_TN || g.bias || g.residual)) return false;   // fp32 output: weight gradients only
-    if ((g.lda | g.ldb | g.ldc | g.N) & 7) return false;
-    const bool a_kc = g.layout != GEMM_TN, b_kc = g.layout == GEMM_NT;
-    if ((a_kc || b_kc) && (g.K & 7)) return false;
-    if (!a_kc && (g.M & 7)) return false;
-    // operands are addressed with 32-bit byte offsets, tile overhang included
-    const size_t rows_a = a_kc ? g.M : g.K, rows_b = b_kc ? g.N : g.K;
-    if ((rows_a + 256) * (size_t)g.lda * 2 >= 0xfff00000ull || (rows_b + 256) * (size_t)g.ldb * 2 >= 0xfff00000ull)
-        return false;
-    const uintptr_t bits = (uintptr_t)g.A | (uintptr_t)g.B | (uintptr_t)g.C | (uintptr_t)g.bias | (uintptr_t)g.residual;
-    return (bits & 15) == 0;
 }
 
 // C (+)= sum over the K chunks of the fp32 partial products; C is bf16 or fp32.  4 elements per thread.
@@ -575,6 +576,68 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
+// The same for the dense 256 x 256 partial blocks of the tiles [tile_begin, tile_begin + tile_count) of the tile
+// order: block (s * tile_count + j) belongs to chunk s of tile tile_begin + j.  64 workgroups per tile.
+template <typename TC>
+__global__ __launch_bounds__(256) void tail_reduce_kernel(const float *__restrict__ part, int splits, int tile_begin, int tile_count,
+                                                          int tiles_m, int tiles_n, int M, int N, TC *__restrict__ C, int ldc,
+                                                          int accumulate) {
+    const int j = blockIdx.x >> 6;
+    const int e0 = ((blockIdx.x & 63) * 256 + threadIdx.x) * 4;         // element of the block: row e0 / 256, column e0 % 256
+    int tm, tn;
+    tile_coords(tile_begin + j, tiles_m, tiles_n, tm, tn);
+    const int m = tm * BM + (e0 >> 8), n = tn * BN + (e0 & 255);
+    if (m >= M || n >= N) return;                                       // N is a multiple of 8: the 4 columns are in or out together
+    f32x4 v = *reinterpret_cast<const f32x4 *>(part + ((size_t)j << 16) + e0);
+    for (int sp = 1; sp < splits; ++sp) v += *reinterpret_cast<const f32x4 *>(part + ((size_t)(sp * tile_count + j) << 16) + e0);
+    TC *c = C + (size_t)m * ldc + n;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float r = v[e];
+        if (accumulate) r += Elem<TC>::load(c + e);
+        Elem<TC>::store(c + e, r);
+    }
+}
+
+GemmP params(const GemmArgs &g) {
+    GemmP p;
+    p.M = g.M; p.N = g.N; p.K = g.K;
+    p.A = (const bf16_t *)g.A; p.lda = g.lda;
+    p.B = (const bf16_t *)g.B; p.ldb = g.ldb;
+    p.C = (bf16_t *)g.C; p.ldc = g.ldc;
+    p.bias = (const bf16_t *)g.bias;
+    p.residual = (const bf16_t *)g.residual;
+    p.accumulate = g.accumulate ? 1 : 0;
+    p.c_f32 = g.c_f32 ? 1 : 0;
+    p.tiles_m = ceil_div(g.M, BM);
+    p.tiles_n = ceil_div(g.N, BN);
+    p.splits = 1; p.k_chunk = g.K; p.split_stride = 0;
+    p.tile_begin = 0; p.tile_count = p.tiles_m * p.tiles_n; p.compact = 0;
+    return p;
+}
+
+// all K chunks of the tiles p covers as fp32 partial products (p.C: scratch)
+hipError_t launch_partials(int layout, const GemmP &p, hipStream_t st) {
+    return layout == GEMM_TN ? launch<false, false, false, true>(p, st) : launch<true, false, false, true>(p, st);
+}
+
+}  // namespace
+
+bool gemm_mfma_supported(const GemmArgs &g) {
+    if (g.M <= 0 || g.N <= 0 || g.K <= 0) return false;
+    if (g.c_f32 && (g.layout != GEMM_TN || g.bias || g.residual)) return false;   // fp32 output: weight gradients only
+    if ((g.lda | g.ldb | g.ldc | g.N) & 7) return false;
+    const bool a_kc = g.layout != GEMM_TN, b_kc = g.layout == GEMM_NT;
+    if ((a_kc || b_kc) && (g.K & 7)) return false;
+    if (!a_kc && (g.M & 7)) return false;
+    // operands are addressed with 32-bit byte offsets, tile overhang included
+    const size_t rows_a = a_kc ? g.M : g.K, rows_b = b_kc ? g.N : g.K;
+    if ((rows_a + 256) * (size_t)g.lda * 2 >= 0xfff00000ull || (rows_b + 256) * (size_t)g.ldb * 2 >= 0xfff00000ull)
+        return false;
+    const uintptr_t bits = (uintptr_t)g.A | (uintptr_t)g.B | (uintptr_t)g.C | (uintptr_t)g.bias | (uintptr_t)g.residual;
+    return (bits & 15) == 0;
+}
+
 // How many K chunks for a weight-gradient GEMM: enough to give every compute unit a work item when the
 // output has few tiles (a ViT-sized layer: 16 to 64 tiles against 256 compute units, K = all tokens of the
 // pack), chunks of at least 512, and the partial products must fit the scratch buffer.
@@ -590,21 +653,40 @@ int gemm_mfma_splits(const GemmArgs &g) {
     return s >= 2 ? (int)s : 1;
 }
 
+// The last, partly filled round of a large GEMM.  With one workgroup per compute unit the tiles are worked off in
+// rounds of n_cu; when the last round holds at most half that many tiles, each of them is cut along K into
+// n_cu / tiles chunks so that the round takes a fraction of a full one.  Returns the number of chunks (1: do not
+// split) and the number of tiles in that round.  Only for input- and weight-gradient GEMMs without bias or
+// residual, with scratch for the partial products, and only for long K: a partly filled round is faster than a full
+// one to begin with (fewer active compute units run at a higher clock), and the cut costs two extra launches.
+// Measured on the 22016 x 4096 x 8192 weight gradient (96 tiles in the last round, 2 chunks): 1.137 -> 1.100 ms; the
+// 8192 x 11008 x 4096 input gradient gains nothing, hence the bound on K.
+int gemm_mfma_tail_splits(const GemmArgs &g, int n_cu, int &tail_tiles) {
+    tail_tiles = 0;
+    if (g.layout == GEMM_NT || !g.split_ws || g.bias || g.residual) return 1;
+    const long tiles = (long)ceil_div(g.M, BM) * ceil_div(g.N, BN);
+    const long rem = tiles % n_cu;
+    if (tiles < n_cu || rem == 0 || rem > n_cu / 2) return 1;
+    long s = n_cu / rem;
+    s = s < g.K / 512 ? s : g.K / 512;
+    s = s < 16 ? s : 16;
+    const long fit = (long)(g.split_ws_bytes / ((size_t)rem * BM * BN * 4));
+    s = s < fit ? s : fit;
+    if (s < 2 || (long)g.K * (s - 1) / s < 4096) return 1;
+    tail_tiles = (int)rem;
+    return (int)s;
+}
+
 hipError_t gemm_mfma(const GemmArgs &g, hipStream_t st) {
     const int splits = gemm_mfma_splits(g);
     if (splits > 1) {
-        GemmP p;
-        p.M = g.M; p.N = g.N; p.K = g.K;
-        p.A = (const bf16_t *)g.A; p.lda = g.lda;
-        p.B = (const bf16_t *)g.B; p.ldb = g.ldb;
+        GemmP p = params(g);
         p.C = (bf16_t *)g.split_ws; p.ldc = g.N;
-        p.bias = nullptr; p.residual = nullptr; p.accumulate = 0; p.c_f32 = 1;
-        p.tiles_m = ceil_div(g.M, BM); p.tiles_n = ceil_div(g.N, BN);
-        p.splits = splits;
+        p.accumulate = 0; p.c_f32 = 1;
         p.k_chunk = ceil_div(ceil_div(g.K, splits), BK) * BK;
         p.splits = ceil_div(g.K, p.k_chunk);                          // no empty chunk
         p.split_stride = (long)g.M * g.N;
-        hipError_t e = launch<false, false, false, true>(p, st);
+        hipError_t e = launch_partials(g.layout, p, st);
         if (e != hipSuccess) return e;
         const long quads = ((long)g.M * g.N + 3) / 4;
         if (g.c_f32)
@@ -615,25 +697,36 @@ hipError_t gemm_mfma(const GemmArgs &g, hipStream_t st) {
                                                                              g.M, g.N, (bf16_t *)g.C, g.ldc, g.accumulate ? 1 : 0);
         return hipGetLastError();
     }
-    GemmP p;
-    p.splits = 1; p.k_chunk = g.K; p.split_stride = 0;
-    p.M = g.M; p.N = g.N; p.K = g.K;
-    p.A = (const bf16_t *)g.A; p.lda = g.lda;
-    p.B = (const bf16_t *)g.B; p.ldb = g.ldb;
-    p.C = (bf16_t *)g.C; p.ldc = g.ldc;
-    p.bias = (const bf16_t *)g.bias;
-    p.residual = (const bf16_t *)g.residual;
-    p.accumulate = g.accumulate ? 1 : 0;
-    p.tiles_m = ceil_div(g.M, BM);
-    p.tiles_n = ceil_div(g.N, BN);
-    p.c_f32 = g.c_f32 ? 1 : 0;
-    if (g.c_f32) return launch<false, false, false, true>(p, st);
-    const bool add = p.residual || p.accumulate;
-    switch (g.layout) {
-        case GEMM_NT: return add ? launch<true, true, true>(p, st) : launch<true, true, false>(p, st);
-        case GEMM_NN: return add ? launch<true, false, true>(p, st) : launch<true, false, false>(p, st);
-        default: return add ? launch<false, false, true>(p, st) : launch<false, false, false>(p, st);
+    GemmP p = params(g);
+    int n_cu = 0, tail_tiles = 0;
+    hipError_t e = compute_units(n_cu);
+    if (e != hipSuccess) return e;
+    const int tail_s = gemm_mfma_tail_splits(g, n_cu, tail_tiles);
+    p.tile_count -= tail_tiles;                                       // the full rounds
+    if (g.c_f32) e = launch<false, false, false, true>(p, st);
+    else {
+        const bool add = p.residual || p.accumulate;
+        switch (g.layout) {
+            case GEMM_NT: e = add ? launch<true, true, true>(p, st) : launch<true, true, false>(p, st); break;
+            case GEMM_NN: e = add ? launch<true, false, true>(p, st) : launch<true, false, false>(p, st); break;
+            default: e = add ? launch<false, false, true>(p, st) : launch<false, false, false>(p, st); break;
+        }
     }
+    if (e != hipSuccess || tail_tiles == 0) return e;
+    GemmP t = params(g);
+    t.C = (bf16_t *)g.split_ws; t.accumulate = 0; t.c_f32 = 1;
+    t.tile_begin = p.tile_count; t.tile_count = tail_tiles; t.compact = 1;
+    t.k_chunk = ceil_div(ceil_div(g.K, tail_s), BK) * BK;
+    t.splits = ceil_div(g.K, t.k_chunk);
+    e = launch_partials(g.layout, t, st);
+    if (e != hipSuccess) return e;
+    if (g.c_f32)
+        tail_reduce_kernel<float><<<tail_tiles * 64, 256, 0, st>>>((const float *)g.split_ws, t.splits, t.tile_begin, tail_tiles, t.tiles_m,
+                                                                  t.tiles_n, g.M, g.N, (float *)g.C, g.ldc, g.accumulate ? 1 : 0);
+    else
+        tail_reduce_kernel<bf16_t><<<tail_tiles * 64, 256, 0, st>>>((const float *)g.split_ws, t.splits, t.tile_begin, tail_tiles, t.tiles_m,
+                                                                   t.tiles_n, g.M, g.N, (bf16_t *)g.C, g.ldc, g.accumulate ? 1 : 0);
+    return hipGetLastError();
 }
 
 }  // namespace mmt

@@ -43,11 +43,14 @@ def bench_gemm(a):
     Cm = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
     R = torch.randn((M, N), device="cuda", generator=g).to(torch.bfloat16) if a.residual else None
 
+    wsb = 0 if a.no_workspace or a.residual else mm.mmtrain_gemm_workspace_bytes(layout, M, N)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda") if wsb else None
+
     def run():
-        check(mm.mmtrain_gemm(mm.BF16, layout, M, N, K, A, shp_a[1], B, shp_b[1], Cm, N, None, R, 0), "mmtrain_gemm")
+        check(mm.mmtrain_gemm(mm.BF16, layout, M, N, K, A, shp_a[1], B, shp_b[1], Cm, N, None, R, 0, ws, wsb), "mmtrain_gemm")
 
     ms = _time(run, a.iters)
-    print(json.dumps({"op": "gemm", "layout": a.layout, "M": M, "N": N, "K": K, "ms": ms,
+    print(json.dumps({"op": "gemm", "layout": a.layout, "M": M, "N": N, "K": K, "workspace_bytes": wsb, "ms": ms,
                       "tflops": 2.0 * M * N * K / ms / 1e9}))
 
 
@@ -106,6 +109,7 @@ def main(argv=None):
     g.add_argument("--n", type=int, default=22016)
     g.add_argument("--k", type=int, default=4096)
     g.add_argument("--residual", action="store_true")
+    g.add_argument("--no-workspace", action="store_true", help="no scratch: the product is never cut along K")
     g.add_argument("--iters", type=int, default=20)
     t = sub.add_parser("attn")
     t.add_argument("--config", type=int, default=3)

@@ -21,7 +21,7 @@ def header_symbols():
 def test_library_exports_every_declared_symbol():
     lib = mm.load_library()
     names = header_symbols()
-    assert len(names) == 13 and set(names) == set(mm.EXPORTS)
+    assert len(names) == 14 and set(names) == set(mm.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -140,3 +140,17 @@ def test_gemm_validation():
     assert g(ldc=8) == mm.ERR_INVALID_ARG
     assert g(K=60, lda=60, ldb=60) == mm.ERR_UNSUPPORTED                       # bf16 rows must be 16-byte multiples
     assert g(M=0) == mm.OK
+    assert g(workspace=None, workspace_bytes=1024) == mm.ERR_INVALID_ARG       # bytes without a buffer
+    assert g(workspace=FAKE + 16, workspace_bytes=1024) == mm.ERR_INVALID_ARG  # not 256-byte aligned
+
+
+def test_gemm_workspace_size():
+    # nothing to cut: forward layout, outputs that fill whole rounds of 256 tiles, or more than half of the last one
+    assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_NT, 512, 512) == 0
+    assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_NN, 8192, 4096) == 0        # 512 tiles
+    assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_TN, 4096, 11008) == 0       # 688 tiles: 176 in the last round
+    assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_TN, 0, 64) == 0
+    # few tiles: 256 / tiles products of M x N in fp32; a partly filled last round: 256 blocks of 256 x 256
+    assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_TN, 1024, 1024) == 16 * 1024 * 1024 * 4
+    assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_TN, 22016, 4096) == 256 * 256 * 256 * 4
+    assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_NN, 8192, 11008) == 256 * 256 * 256 * 4

@@ -12,7 +12,7 @@ from util import assert_parity
 pytestmark = pytest.mark.gpu
 
 
-def gemm_case(dtype, layout, M, N, K, bias=False, residual=False, accumulate=False, seed=0):
+def gemm_case(dtype, layout, M, N, K, bias=False, residual=False, accumulate=False, seed=0, workspace=False):
     rng = np.random.default_rng(seed)
     shp_a = (K, M) if layout == mm.GEMM_TN else (M, K)
     shp_b = (N, K) if layout == mm.GEMM_NT else (K, N)
@@ -30,8 +30,10 @@ def gemm_case(dtype, layout, M, N, K, bias=False, residual=False, accumulate=Fal
     dA, dB, dC = to_device(A, dtype), to_device(B, dtype), to_device(C0, dtype)
     dbias = to_device(bv, dtype) if bias else None
     dR = to_device(R, dtype) if residual else None
+    wsb = mm.mmtrain_gemm_workspace_bytes(layout, M, N) if workspace else 0
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda") if wsb else None
     check(mm.mmtrain_gemm(dtype, layout, M, N, K, dA, shp_a[1], dB, shp_b[1], dC, N, dbias, dR,
-                          mm.GEMM_ACCUMULATE if accumulate else 0), "mmtrain_gemm")
+                          mm.GEMM_ACCUMULATE if accumulate else 0, ws, wsb), "mmtrain_gemm")
     torch.cuda.synchronize()
     got = to_host(dC)
     # one bf16 rounding of the fp32-accumulated result: at most 2^-9 relative per element
@@ -60,6 +62,22 @@ def test_gemm_bf16_epilogues(layout):
 def test_gemm_bf16_many_tiles(layout):
     # more tiles than compute units' worth of one XCD, ragged in every dimension
     gemm_case(mm.BF16, layout, 2056, 2312, 328, seed=4)
+
+
+def test_gemm_bf16_few_tiles_cut_along_k():
+    # 4 output tiles, K = 4104: with scratch the weight-gradient layout is cut into K chunks (the last one ragged)
+    assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_TN, 512, 392) > 0
+    gemm_case(mm.BF16, mm.GEMM_TN, 512, 392, 4104, seed=5, workspace=True)
+    gemm_case(mm.BF16, mm.GEMM_TN, 512, 392, 4104, accumulate=True, seed=6, workspace=True)
+
+
+@pytest.mark.parametrize("layout,accumulate", [(mm.GEMM_NN, False), (mm.GEMM_TN, True), (mm.GEMM_TN, False)])
+def test_gemm_bf16_last_round_cut_along_k(layout, accumulate):
+    # 18 x 16 = 288 tiles on 256 compute units: the 32 tiles of the second round are cut into 8 K chunks (the last
+    # one ragged) whose partial products go through scratch; ragged last tile row and column
+    M, N, K = 4360, 4040, 4872
+    assert mm.mmtrain_gemm_workspace_bytes(layout, M, N) > 0
+    gemm_case(mm.BF16, layout, M, N, K, accumulate=accumulate, seed=7, workspace=True)
 
 
 @pytest.mark.parametrize("layout", [mm.GEMM_NT, mm.GEMM_NN, mm.GEMM_TN])
