@@ -91,6 +91,10 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph that holds one forward + backward (no per-kernel figures)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--layers", type=int, default=1,
+                    help="more than 1: time a stack of that many layers through mmtrain_stack_fwd / mmtrain_stack_bwd")
+    ap.add_argument("--recompute", action="store_true",
+                    help="with --layers: keep only layer inputs in forward and recompute each layer in backward")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (one GPU's share of the training step); run with --gpus 1")
@@ -98,7 +102,7 @@ def main():
     import torch
     from paper_2408_04275_amd import binding as mm
     from paper_2408_04275_amd import workloads as wl
-    from paper_2408_04275_amd.harness import LayerRunner, check
+    from paper_2408_04275_amd.harness import LayerRunner, StackRunner, check
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -110,9 +114,31 @@ def main():
     T = int(cu[-1])
     W = wl.make_weights(shape, seed)
     x, dy = wl.make_activations(shape, T, seed)
+    flops = wl.model_flops(shape, cu, modes)
+    if args.layers > 1:
+        # a stack: model FLOP = layers x one layer's; recomputation runs every layer's forward but the last twice,
+        # which the model FLOP count (and so the reported rate) does not credit
+        stack = StackRunner(shape, [W] + [wl.make_weights(shape, seed + 100 * l) for l in range(1, args.layers)], cu, modes,
+                            recompute=args.recompute)
+        stack.set_inputs(x, dy)
+        for _ in range(args.warmup):
+            stack.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            stack.step()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        print(json.dumps({"metric": "layer-stack fwd+bwd TFLOP/s (model FLOP)",
+                          "value": args.layers * flops["fwd_bwd"] / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+                          "dtype": "bf16" if shape.dtype == wl.BF16 else "f32", "data": "synthetic",
+                          "config": {"workload": f"config {args.config}: {shape.name}", "layers": args.layers,
+                                     "recompute": bool(args.recompute), "ctx_bytes": stack.ctx_bytes,
+                                     "workspace_bytes": stack.ws_bytes}}))
+        return
     runner = LayerRunner(shape, W, cu, modes)
     runner.set_inputs(x, dy)
-    flops = wl.model_flops(shape, cu, modes)
 
     for _ in range(args.warmup):
         runner.step()

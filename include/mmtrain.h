@@ -149,6 +149,37 @@ MMTRAIN_API int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_
                       const void *ctx, void *dx, const mmtrain_layer_grads *grads, uint32_t flags,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------
+ * A stack of n_layers layers of one description applied in sequence (the
+ * homogeneous transformer layers of Section 4.2; Table 2 lists the depths):
+ * y = layer[n-1](... layer[0](x)).  `weights` (and `grads`, which may be NULL,
+ * as may any of its members' members) are HOST arrays of n_layers structures
+ * holding device pointers.  `ctx` is opaque as for one layer.
+ *
+ * Without flags the stack keeps every layer's context for the backward pass.
+ * With MMTRAIN_STACK_RECOMPUTE (pass the same flag to all four calls) forward
+ * keeps only the input of every layer ([T, hidden] each) plus one layer
+ * context; backward runs each layer's forward again right before its
+ * backward (the last layer's context is still there from the forward pass).
+ * The kernels are deterministic, so both modes give bit-identical results;
+ * recomputation trades one extra forward pass for n_layers - 1 contexts of
+ * memory.  mmtrain_stack_bwd takes the MMTRAIN_BWD_* flags as well.
+ * ------------------------------------------------------------------------ */
+#define MMTRAIN_STACK_RECOMPUTE 256u
+
+MMTRAIN_API size_t mmtrain_stack_ctx_bytes(const mmtrain_layer_desc *desc, int32_t n_layers, int32_t total_tokens,
+                                           uint32_t flags);
+MMTRAIN_API size_t mmtrain_stack_workspace_bytes(const mmtrain_layer_desc *desc, int32_t n_layers,
+                                                 int32_t total_tokens, int32_t n_segments, int is_bwd,
+                                                 uint32_t flags);
+MMTRAIN_API int mmtrain_stack_fwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mmtrain_batch *batch,
+                                  const mmtrain_layer_weights *weights, const void *x, void *y, void *ctx,
+                                  uint32_t flags, void *workspace, size_t workspace_bytes, void *hip_stream);
+MMTRAIN_API int mmtrain_stack_bwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mmtrain_batch *batch,
+                                  const mmtrain_layer_weights *weights, const void *x, const void *dy,
+                                  void *ctx, void *dx, const mmtrain_layer_grads *grads, uint32_t flags,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
 MMTRAIN_API const char *mmtrain_status_string(int status);
 
 /* ------------------------------------------------------------------------

@@ -307,3 +307,25 @@ def layer_fwd_bwd(kind, n_heads, n_kv_heads, head_dim, cu, modes, weights, x, dy
     y, cache = layer_fwd(kind, n_heads, n_kv_heads, head_dim, cu, modes, weights, x, **kw)
     dx, grads = layer_bwd(weights, cache, dy)
     return y, dx, grads, cache
+
+
+# ----------------------------------------------------------------------------
+# a stack of layers (Section 4.2: the backbone is a sequence of identical transformer layers)
+# ----------------------------------------------------------------------------
+def stack_fwd(kind, n_heads, n_kv_heads, head_dim, cu, modes, weights_per_layer, x, **kw):
+    """y = layer[n-1](... layer[0](x)).  Returns (y, caches), one cache per layer."""
+    caches = []
+    h = np.asarray(x, dtype=f64)
+    for W in weights_per_layer:
+        h, cache = layer_fwd(kind, n_heads, n_kv_heads, head_dim, cu, modes, W, h, **kw)
+        caches.append(cache)
+    return h, caches
+
+
+def stack_bwd(weights_per_layer, caches, dy):
+    """Chain rule down the stack.  Returns (dx, grads), grads being one dictionary per layer."""
+    g = np.asarray(dy, dtype=f64)
+    grads = [None] * len(caches)
+    for l in range(len(caches) - 1, -1, -1):
+        g, grads[l] = layer_bwd(weights_per_layer[l], caches[l], g)
+    return g, grads

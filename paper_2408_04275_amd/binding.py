@@ -22,11 +22,13 @@ MASK_CAUSAL, MASK_BIDIR = 0, 1
 GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
 BWD_ACCUMULATE_WGRAD = 1
 BWD_WGRAD_F32 = 2
+STACK_RECOMPUTE = 256
 GEMM_ACCUMULATE = 1
 
 EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_layer_fwd", "mmtrain_layer_bwd",
            "mmtrain_status_string", "mmtrain_gemm", "mmtrain_gemm_workspace_bytes", "mmtrain_attn_workspace_bytes", "mmtrain_attn_fwd",
-           "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read", "mmtrain_intra_reorder", "mmtrain_adam_step")
+           "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read", "mmtrain_intra_reorder", "mmtrain_adam_step",
+           "mmtrain_stack_ctx_bytes", "mmtrain_stack_workspace_bytes", "mmtrain_stack_fwd", "mmtrain_stack_bwd")
 PROF_GEMM_NT, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD = range(5)
 
 WEIGHT_FIELDS = ("norm1_w", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
@@ -85,6 +87,14 @@ def load_library() -> C.CDLL:
     lib.mmtrain_layer_fwd.argtypes = [P, P, P, P, P, P, P, S, P]
     lib.mmtrain_layer_bwd.restype = C.c_int
     lib.mmtrain_layer_bwd.argtypes = [P, P, P, P, P, P, P, P, U, P, S, P]
+    lib.mmtrain_stack_ctx_bytes.restype = S
+    lib.mmtrain_stack_ctx_bytes.argtypes = [P, I, I, U]
+    lib.mmtrain_stack_workspace_bytes.restype = S
+    lib.mmtrain_stack_workspace_bytes.argtypes = [P, I, I, I, C.c_int, U]
+    lib.mmtrain_stack_fwd.restype = C.c_int
+    lib.mmtrain_stack_fwd.argtypes = [P, I, P, P, P, P, P, U, P, S, P]
+    lib.mmtrain_stack_bwd.restype = C.c_int
+    lib.mmtrain_stack_bwd.argtypes = [P, I, P, P, P, P, P, P, P, U, P, S, P]
     lib.mmtrain_status_string.restype = C.c_char_p
     lib.mmtrain_status_string.argtypes = [C.c_int]
     lib.mmtrain_gemm.restype = C.c_int
@@ -219,6 +229,36 @@ def mmtrain_layer_bwd(desc, batch, weights, x, dy, ctx, dx, grads, flags, worksp
     return load_library().mmtrain_layer_bwd(_ref(desc), _ref(b), _ref(weights), _ptr(x), _ptr(dy), _ptr(ctx),
                                             _ptr(dx), _ref(grads), flags, _ptr(workspace), workspace_bytes,
                                             _stream(stream))
+
+
+def _array(structs, ctype):
+    """A host array of C structures from a list (None stays None)."""
+    if structs is None:
+        return None
+    return structs if isinstance(structs, C.Array) else (ctype * len(structs))(*structs)
+
+
+def mmtrain_stack_ctx_bytes(desc, n_layers: int, total_tokens: int, flags: int = 0) -> int:
+    return load_library().mmtrain_stack_ctx_bytes(_ref(desc), n_layers, total_tokens, flags)
+
+
+def mmtrain_stack_workspace_bytes(desc, n_layers: int, total_tokens: int, n_segments: int, is_bwd: int,
+                                  flags: int = 0) -> int:
+    return load_library().mmtrain_stack_workspace_bytes(_ref(desc), n_layers, total_tokens, n_segments, is_bwd, flags)
+
+
+def mmtrain_stack_fwd(desc, n_layers, batch, weights, x, y, ctx, flags, workspace, workspace_bytes, stream=None) -> int:
+    b = batch.struct if isinstance(batch, PackedBatch) else batch
+    return load_library().mmtrain_stack_fwd(_ref(desc), n_layers, _ref(b), _array(weights, Weights), _ptr(x), _ptr(y),
+                                            _ptr(ctx), flags, _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def mmtrain_stack_bwd(desc, n_layers, batch, weights, x, dy, ctx, dx, grads, flags, workspace, workspace_bytes,
+                      stream=None) -> int:
+    b = batch.struct if isinstance(batch, PackedBatch) else batch
+    return load_library().mmtrain_stack_bwd(_ref(desc), n_layers, _ref(b), _array(weights, Weights), _ptr(x), _ptr(dy),
+                                            _ptr(ctx), _ptr(dx), _array(grads, Grads), flags, _ptr(workspace),
+                                            workspace_bytes, _stream(stream))
 
 
 def mmtrain_gemm_workspace_bytes(layout: int, M: int, N: int) -> int:

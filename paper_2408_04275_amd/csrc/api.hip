@@ -395,6 +395,111 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     return MMTRAIN_OK;
 }
 
+// ---- a stack of layers -------------------------------------------------------------
+// ctx: the inputs of layers 1 .. n-1 ([T, H] each), then the layer contexts: one per layer, or a single one with
+// MMTRAIN_STACK_RECOMPUTE.  Backward workspace: the layer's own, then two [T, H] buffers through which the
+// gradient travels down the stack, then (recomputation) one [T, H] buffer for the recomputed layer output.
+namespace {
+struct StackPlan {
+    size_t act, layer_ctx, layer_ws_fwd, layer_ws_bwd;
+    bool recompute;
+    size_t ctx_bytes(int n) const { return (size_t)(n - 1) * act + (recompute ? 1 : (size_t)n) * layer_ctx; }
+    size_t ws_bytes(bool bwd) const { return bwd ? layer_ws_bwd + 2 * act + (recompute ? act : 0) : layer_ws_fwd; }
+};
+int plan_stack(const mmtrain_layer_desc *desc, int n_layers, int T, int S, uint32_t flags, uint32_t allowed, StackPlan &p) {
+    Dims D;
+    int rc = check_desc(desc, D);
+    if (rc) return rc;
+    if (n_layers < 1 || T < 0 || S < 0 || (flags & ~allowed)) return MMTRAIN_ERR_INVALID_ARG;
+    p.act = ((size_t)T * D.H * (D.dtype == DT_BF16 ? 2 : 4) + 255) & ~size_t(255);
+    p.layer_ctx = mmtrain_layer_ctx_bytes(desc, T);
+    p.layer_ws_fwd = mmtrain_layer_workspace_bytes(desc, T, S, 0);
+    p.layer_ws_bwd = mmtrain_layer_workspace_bytes(desc, T, S, 1);
+    p.recompute = flags & MMTRAIN_STACK_RECOMPUTE;
+    return MMTRAIN_OK;
+}
+}  // namespace
+
+size_t mmtrain_stack_ctx_bytes(const mmtrain_layer_desc *desc, int32_t n_layers, int32_t total_tokens, uint32_t flags) {
+    StackPlan p;
+    if (plan_stack(desc, n_layers, total_tokens, 0, flags, MMTRAIN_STACK_RECOMPUTE, p)) return 0;
+    return p.ctx_bytes(n_layers);
+}
+
+size_t mmtrain_stack_workspace_bytes(const mmtrain_layer_desc *desc, int32_t n_layers, int32_t total_tokens,
+                                     int32_t n_segments, int is_bwd, uint32_t flags) {
+    StackPlan p;
+    if (plan_stack(desc, n_layers, total_tokens, n_segments, flags, MMTRAIN_STACK_RECOMPUTE, p)) return 0;
+    return p.ws_bytes(is_bwd != 0);
+}
+
+int mmtrain_stack_fwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mmtrain_batch *batch,
+                      const mmtrain_layer_weights *weights, const void *x, void *y, void *ctx, uint32_t flags,
+                      void *workspace, size_t workspace_bytes, void *hip_stream) {
+    Dims D;
+    int rc = check_desc(desc, D);
+    if (rc) return rc;
+    if ((rc = check_batch(batch))) return rc;
+    StackPlan p;
+    if ((rc = plan_stack(desc, n_layers, batch->total_tokens, batch->n_segments, flags, MMTRAIN_STACK_RECOMPUTE, p))) return rc;
+    if (!weights) return MMTRAIN_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l)
+        if ((rc = check_weights(D, &weights[l]))) return rc;
+    if (batch->total_tokens == 0) return MMTRAIN_OK;
+    if (!x || !y || !ctx || x == y || (((uintptr_t)ctx | (uintptr_t)workspace) & 255)) return MMTRAIN_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < p.ws_bytes(false)) return MMTRAIN_ERR_WORKSPACE;
+    uint8_t *acts = (uint8_t *)ctx, *ctxs = acts + (size_t)(n_layers - 1) * p.act;
+    for (int l = 0; l < n_layers; ++l) {
+        const void *in = l == 0 ? x : acts + (size_t)(l - 1) * p.act;
+        void *out = l == n_layers - 1 ? y : acts + (size_t)l * p.act;
+        void *lctx = ctxs + (p.recompute ? 0 : (size_t)l * p.layer_ctx);
+        if ((rc = mmtrain_layer_fwd(desc, batch, &weights[l], in, out, lctx, workspace, workspace_bytes, hip_stream))) return rc;
+    }
+    return MMTRAIN_OK;
+}
+
+int mmtrain_stack_bwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mmtrain_batch *batch,
+                      const mmtrain_layer_weights *weights, const void *x, const void *dy, void *ctx, void *dx,
+                      const mmtrain_layer_grads *grads, uint32_t flags, void *workspace, size_t workspace_bytes,
+                      void *hip_stream) {
+    Dims D;
+    int rc = check_desc(desc, D);
+    if (rc) return rc;
+    if ((rc = check_batch(batch))) return rc;
+    StackPlan p;
+    const uint32_t bwd_flags = MMTRAIN_BWD_ACCUMULATE_WGRAD | MMTRAIN_BWD_WGRAD_F32;
+    if ((rc = plan_stack(desc, n_layers, batch->total_tokens, batch->n_segments, flags, MMTRAIN_STACK_RECOMPUTE | bwd_flags, p)))
+        return rc;
+    if (!weights) return MMTRAIN_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l)
+        if ((rc = check_weights(D, &weights[l]))) return rc;
+    const uint32_t lflags = flags & bwd_flags;
+    if (batch->total_tokens == 0) {                 // an empty pack: every layer's gradients are zero (or left as they are)
+        for (int l = 0; l < n_layers; ++l)
+            if ((rc = mmtrain_layer_bwd(desc, batch, &weights[l], x, dy, ctx, dx, grads ? &grads[l] : nullptr, lflags, workspace,
+                                        workspace_bytes, hip_stream))) return rc;
+        return MMTRAIN_OK;
+    }
+    if (!x || !dy || !ctx || !dx || (((uintptr_t)ctx | (uintptr_t)workspace) & 255)) return MMTRAIN_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < p.ws_bytes(true)) return MMTRAIN_ERR_WORKSPACE;
+    uint8_t *acts = (uint8_t *)ctx, *ctxs = acts + (size_t)(n_layers - 1) * p.act;
+    uint8_t *ws = (uint8_t *)workspace;
+    uint8_t *grad_buf[2] = {ws + p.layer_ws_bwd, ws + p.layer_ws_bwd + p.act};
+    uint8_t *y_again = ws + p.layer_ws_bwd + 2 * p.act;
+    const void *g_in = dy;
+    for (int l = n_layers - 1; l >= 0; --l) {
+        const void *in = l == 0 ? x : acts + (size_t)(l - 1) * p.act;
+        void *lctx = ctxs + (p.recompute ? 0 : (size_t)l * p.layer_ctx);
+        if (p.recompute && l != n_layers - 1)
+            if ((rc = mmtrain_layer_fwd(desc, batch, &weights[l], in, y_again, lctx, workspace, p.layer_ws_bwd, hip_stream))) return rc;
+        void *g_out = l == 0 ? dx : (void *)grad_buf[l & 1];
+        if ((rc = mmtrain_layer_bwd(desc, batch, &weights[l], in, g_in, lctx, g_out, grads ? &grads[l] : nullptr, lflags,
+                                    workspace, p.layer_ws_bwd, hip_stream))) return rc;
+        g_in = g_out;
+    }
+    return MMTRAIN_OK;
+}
+
 // ---- profiling ---------------------------------------------------------------------
 
 void mmtrain_profile_enable(int on) { g_prof.on = on != 0; }

@@ -83,3 +83,54 @@ class LayerRunner:
     def results(self):
         torch.cuda.synchronize()
         return to_host(self.y), to_host(self.dx), {k: to_host(v) for k, v in self.g.items()}
+
+
+class StackRunner:
+    """Device memory and calls for a stack of layers of one shape (one weight dictionary per layer)."""
+
+    def __init__(self, shape: LayerShape, weights_per_layer, cu: np.ndarray, modes: Optional[np.ndarray] = None,
+                 mask_mode: int = mm.MASK_CAUSAL, recompute: bool = False, device="cuda", with_grads: bool = True):
+        self.shape, self.device, self.n = shape, device, len(weights_per_layer)
+        self.flags = mm.STACK_RECOMPUTE if recompute else 0
+        self.desc = mm.make_desc(shape.kind, shape.dtype, shape.hidden, shape.n_heads, shape.n_kv_heads,
+                                 shape.head_dim, shape.ffn_hidden, shape.norm_eps, shape.rope_base)
+        self.batch = mm.PackedBatch.on_device(cu, modes, mask_mode, device)
+        self.T = int(cu[-1])
+        S = len(cu) - 1
+        dt = torch_dtype(shape.dtype)
+        self.w = [{k: to_device(v, shape.dtype, device) for k, v in W.items()} for W in weights_per_layer]
+        self.g = [{k: torch.zeros(s, dtype=dt, device=device) for k, s in weight_shapes(shape).items()}
+                  for _ in range(self.n)] if with_grads else None
+        self.weights = [mm.make_weights(w) for w in self.w]
+        self.grads = [mm.make_grads(g) for g in self.g] if with_grads else None
+        self.ctx_bytes = mm.mmtrain_stack_ctx_bytes(self.desc, self.n, self.T, self.flags)
+        self.ws_bytes = max(mm.mmtrain_stack_workspace_bytes(self.desc, self.n, self.T, S, 0, self.flags),
+                            mm.mmtrain_stack_workspace_bytes(self.desc, self.n, self.T, S, 1, self.flags))
+        if self.ctx_bytes == 0 or self.ws_bytes == 0:
+            raise RuntimeError("stack description rejected by the library")
+        self.ctx = torch.empty(self.ctx_bytes, dtype=torch.uint8, device=device)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        self.x = torch.empty((self.T, shape.hidden), dtype=dt, device=device)
+        self.y = torch.empty_like(self.x)
+        self.dy = torch.empty_like(self.x)
+        self.dx = torch.empty_like(self.x)
+
+    def set_inputs(self, x: np.ndarray, dy: np.ndarray):
+        self.x.copy_(to_device(x, self.shape.dtype, self.device))
+        self.dy.copy_(to_device(dy, self.shape.dtype, self.device))
+
+    def forward(self, stream=None) -> int:
+        return mm.mmtrain_stack_fwd(self.desc, self.n, self.batch, self.weights, self.x, self.y, self.ctx, self.flags,
+                                    self.ws, self.ws_bytes, stream)
+
+    def backward(self, flags: int = 0, stream=None) -> int:
+        return mm.mmtrain_stack_bwd(self.desc, self.n, self.batch, self.weights, self.x, self.dy, self.ctx, self.dx,
+                                    self.grads, self.flags | flags, self.ws, self.ws_bytes, stream)
+
+    def step(self, flags: int = 0):
+        check(self.forward(), "mmtrain_stack_fwd")
+        check(self.backward(flags), "mmtrain_stack_bwd")
+
+    def results(self):
+        torch.cuda.synchronize()
+        return to_host(self.y), to_host(self.dx), [{k: to_host(v) for k, v in g.items()} for g in self.g]

@@ -21,7 +21,7 @@ def header_symbols():
 def test_library_exports_every_declared_symbol():
     lib = mm.load_library()
     names = header_symbols()
-    assert len(names) == 14 and set(names) == set(mm.EXPORTS)
+    assert len(names) == 18 and set(names) == set(mm.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -154,3 +154,34 @@ def test_gemm_workspace_size():
     assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_TN, 1024, 1024) == 16 * 1024 * 1024 * 4
     assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_TN, 22016, 4096) == 256 * 256 * 256 * 4
     assert mm.mmtrain_gemm_workspace_bytes(mm.GEMM_NN, 8192, 11008) == 256 * 256 * 256 * 4
+
+
+def test_stack_sizes_and_validation():
+    d = good_desc()
+    T, S, n = 512, 3, 5
+    act = T * d.hidden * 2
+    lc = mm.mmtrain_layer_ctx_bytes(d, T)
+    assert mm.mmtrain_stack_ctx_bytes(d, n, T, 0) == (n - 1) * act + n * lc
+    assert mm.mmtrain_stack_ctx_bytes(d, n, T, mm.STACK_RECOMPUTE) == (n - 1) * act + lc
+    lw = mm.mmtrain_layer_workspace_bytes(d, T, S, 1)
+    assert mm.mmtrain_stack_workspace_bytes(d, n, T, S, 1, 0) == lw + 2 * act
+    assert mm.mmtrain_stack_workspace_bytes(d, n, T, S, 1, mm.STACK_RECOMPUTE) == lw + 3 * act
+    assert mm.mmtrain_stack_workspace_bytes(d, n, T, S, 0, 0) == mm.mmtrain_layer_workspace_bytes(d, T, S, 0)
+    assert mm.mmtrain_stack_ctx_bytes(d, 0, T, 0) == 0 and mm.mmtrain_stack_ctx_bytes(d, n, T, 7) == 0
+    b = batch([0, 200, 512])
+    W = [mm.Weights(*[FAKE] * 12)] * n
+    big = 1 << 40
+    f = lambda **k: mm.mmtrain_stack_fwd(**dict(dict(desc=d, n_layers=n, batch=b, weights=W, x=FAKE, y=FAKE + 256, ctx=FAKE,
+                                                      flags=0, workspace=FAKE, workspace_bytes=big, stream=0), **k))
+    assert f(n_layers=0) == mm.ERR_INVALID_ARG
+    assert f(weights=None) == mm.ERR_INVALID_ARG
+    assert f(flags=mm.BWD_ACCUMULATE_WGRAD) == mm.ERR_INVALID_ARG           # a backward flag on the forward call
+    assert f(y=FAKE) == mm.ERR_INVALID_ARG                                   # x and y alias
+    assert f(workspace_bytes=16) == mm.ERR_WORKSPACE
+    g = lambda **k: mm.mmtrain_stack_bwd(**dict(dict(desc=d, n_layers=n, batch=b, weights=W, x=FAKE, dy=FAKE, ctx=FAKE,
+                                                      dx=FAKE, grads=None, flags=0, workspace=FAKE, workspace_bytes=big,
+                                                      stream=0), **k))
+    assert g(flags=1024) == mm.ERR_INVALID_ARG
+    assert g(dx=None) == mm.ERR_INVALID_ARG
+    assert g(workspace_bytes=mm.mmtrain_layer_workspace_bytes(d, 512, 2, 1)) == mm.ERR_WORKSPACE   # no room for the gradient buffers
+    assert f(batch=batch([0], dev=False)) == mm.OK                           # an empty pack is a no-op

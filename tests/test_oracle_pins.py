@@ -196,6 +196,34 @@ def test_finite_differences(kind):
             assert abs(num - ana) <= 2e-6 * max(1.0, abs(ana)), (name, i, num, ana)
 
 
+@pytest.mark.parametrize("kind", [DEC, ENC])
+def test_stack_matches_torch_autograd(kind):
+    # three layers with different weights: the stack's output and every layer's gradients against autograd
+    # through the independently written torch layer
+    shape = small_shape(kind)
+    cu = np.array([0, 7, 8, 20, 33], dtype=np.int32)
+    modes = np.array([0, 1, 1, 0], dtype=np.uint8) if kind == DEC else np.ones(4, dtype=np.uint8)
+    Ws = []
+    for l in range(3):
+        W, x, dy = draw(shape, cu, seed=10 + l)
+        Ws.append(W)
+    y, caches = orc.stack_fwd(shape.kind, shape.n_heads, shape.n_kv_heads, shape.head_dim, cu, modes, Ws, x,
+                              eps=shape.norm_eps, rope_base=shape.rope_base)
+    dx, Gs = orc.stack_bwd(Ws, caches, dy)
+    tWs = [{k: torch.tensor(v, requires_grad=True) for k, v in W.items()} for W in Ws]
+    tx = torch.tensor(x, requires_grad=True)
+    th = tx
+    for tW in tWs:
+        th = torch_layer(shape, cu, modes, tW, th)
+    th.backward(torch.tensor(dy))
+    assert np.max(np.abs(y - th.detach().numpy())) < 1e-9
+    assert np.max(np.abs(dx - tx.grad.numpy())) < 1e-9
+    for G, tW in zip(Gs, tWs):
+        for name in tW:
+            ref = tW[name].grad.numpy()
+            assert np.max(np.abs(G[name] - ref)) < 1e-9 * max(1.0, np.max(np.abs(ref))), name
+
+
 # ----------------------------------------------------------------------------
 # P2 / P8: packed == unpacked, segment-order invariance
 # ----------------------------------------------------------------------------
