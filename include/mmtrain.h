@@ -259,6 +259,38 @@ MMTRAIN_API int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_b
 MMTRAIN_API int mmtrain_intra_reorder(const double *sizes, int32_t n, int32_t m, int32_t *order,
                                       int32_t *group_begin, double *group_load);
 
+/* Timeline of a one-forward-one-backward (1F1B) pipeline over l microbatches and p stages (Section
+ * "Inter-microbatch Reordering": an operation starts when the previous operation of its stage and the operation that
+ * produces its input have both ended).  Stage s runs min(p-1-s, l) warm-up forward passes, then forward / backward
+ * pairs, then the remaining backward passes.
+ *   fwd, bwd   host, [p][l] row-major: duration of microbatch j's forward / backward pass on stage s at [s*l + j],
+ *              finite and >= 0 (for this library: measured layer times x layers per stage, as a function of the pack)
+ *   order      host, [l], may be NULL (identity): order[q] = index of the microbatch run at position q; a permutation
+ *   makespan   host, out, may be NULL: end of the last operation
+ *   intervals  host, [l], out, may be NULL: the first stage's pipeline intervals as the section defines them:
+ *              intervals[0] = wait between the end of the first forward pass and the arrival of the first gradient
+ *              (filled by forward passes 2..p); intervals[i-1], i >= 2 = wait between the end of backward pass i-1
+ *              and the arrival of gradient i (filled by forward pass i+p-1; the last p-1 have nothing to fill them)
+ * Host memory only, no GPU call.  Returns MMTRAIN_OK or MMTRAIN_ERR_INVALID_ARG (p < 1, l < 0, NULL fwd / bwd with
+ * l > 0, a negative, infinite or NaN duration, an order that is not a permutation); nothing is written then. */
+MMTRAIN_API int mmtrain_pipeline_1f1b(const double *fwd, const double *bwd, int32_t p, int32_t l, const int32_t *order,
+                                      double *makespan, double *intervals);
+
+/* Inter-microbatch reordering (Algorithm 2, Section "Inter-microbatch Reordering") for the 1F1B schedule above: the
+ * smallest microbatch first, the p-1 smallest of the rest last (ascending), and in between, interval by interval, the
+ * microbatches whose first-stage forward time comes closest to the interval's size (p-1 of them for the first
+ * interval, each aiming at its share of what is still open; one for every later interval).  The interval sizes come
+ * from the timeline of the microbatches placed so far, advanced by O(p) operations per placement.  Size of a
+ * microbatch = its total time over all stages; ties go to the lowest index; the loop runs until no microbatch is
+ * left (the listing's l-p iterations would hand out l+p-2 microbatches).
+ *   fwd, bwd        as above
+ *   order           host, [l], out: order[q] = index of the microbatch to run at position q
+ *   intervals_seen  host, [l], out, may be NULL: the interval size each loop iteration worked with
+ *   n_intervals     host, out, may be NULL: number of loop iterations (entries written to intervals_seen)
+ * Host memory only, no GPU call.  Returns MMTRAIN_OK or MMTRAIN_ERR_INVALID_ARG (as above; NULL order with l > 0). */
+MMTRAIN_API int mmtrain_inter_reorder(const double *fwd, const double *bwd, int32_t p, int32_t l, int32_t *order,
+                                      double *intervals_seen, int32_t *n_intervals);
+
 /* Optimizer step of mixed-precision training with sharded optimizer state (Section 3: ZeRO-1 and mixed
  * precision for the LLM backbone; Section 4.2's memory constraint counts the optimizer state of one shard
  * per GPU).  One AdamW step, all in one pass over the shard:

@@ -28,7 +28,8 @@ GEMM_ACCUMULATE = 1
 EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_layer_fwd", "mmtrain_layer_bwd",
            "mmtrain_status_string", "mmtrain_gemm", "mmtrain_gemm_workspace_bytes", "mmtrain_attn_workspace_bytes", "mmtrain_attn_fwd",
            "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read", "mmtrain_intra_reorder", "mmtrain_adam_step",
-           "mmtrain_stack_ctx_bytes", "mmtrain_stack_workspace_bytes", "mmtrain_stack_fwd", "mmtrain_stack_bwd")
+           "mmtrain_stack_ctx_bytes", "mmtrain_stack_workspace_bytes", "mmtrain_stack_fwd", "mmtrain_stack_bwd",
+           "mmtrain_pipeline_1f1b", "mmtrain_inter_reorder")
 PROF_GEMM_NT, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD = range(5)
 
 WEIGHT_FIELDS = ("norm1_w", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
@@ -115,6 +116,10 @@ def load_library() -> C.CDLL:
     lib.mmtrain_adam_step.argtypes = [P, C.c_int64, P, P, P, P, P, I, P]
     lib.mmtrain_intra_reorder.restype = C.c_int
     lib.mmtrain_intra_reorder.argtypes = [P, I, I, P, P, P]
+    lib.mmtrain_pipeline_1f1b.restype = C.c_int
+    lib.mmtrain_pipeline_1f1b.argtypes = [P, P, I, I, P, C.POINTER(C.c_double), P]
+    lib.mmtrain_inter_reorder.restype = C.c_int
+    lib.mmtrain_inter_reorder.argtypes = [P, P, I, I, P, P, C.POINTER(C.c_int32)]
     _lib = lib
     return lib
 
@@ -202,6 +207,42 @@ def mmtrain_intra_reorder(sizes, m: int):
     rc = load_library().mmtrain_intra_reorder(sizes.ctypes.data if n else None, n, m, order.ctypes.data if n else None,
                                               begin.ctypes.data, load.ctypes.data if m > 0 else None)
     return rc, order, begin, load
+
+
+def _stage_times(t):
+    import numpy as np
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    if t.ndim != 2:
+        raise ValueError("stage times must be [p, l]")
+    return t
+
+
+def mmtrain_pipeline_1f1b(fwd, bwd, order=None):
+    """1F1B timeline through the C ABI.  fwd, bwd: [p, l].  Returns (status, makespan, intervals[l])."""
+    import numpy as np
+    fwd, bwd = _stage_times(fwd), _stage_times(bwd)
+    p, l = fwd.shape
+    if order is not None:
+        order = np.ascontiguousarray(order, dtype=np.int32)
+    makespan = C.c_double(-1.0)
+    intervals = np.full(l, -1.0, dtype=np.float64)
+    rc = load_library().mmtrain_pipeline_1f1b(fwd.ctypes.data if l else None, bwd.ctypes.data if l else None, p, l,
+                                              order.ctypes.data if order is not None and l else None, C.byref(makespan),
+                                              intervals.ctypes.data if l else None)
+    return rc, makespan.value, intervals
+
+
+def mmtrain_inter_reorder(fwd, bwd):
+    """Algorithm 2 through the C ABI.  fwd, bwd: [p, l].  Returns (status, order[l], intervals_seen)."""
+    import numpy as np
+    fwd, bwd = _stage_times(fwd), _stage_times(bwd)
+    p, l = fwd.shape
+    order = np.full(l, -1, dtype=np.int32)
+    seen = np.full(l, -1.0, dtype=np.float64)
+    n = C.c_int32(0)
+    rc = load_library().mmtrain_inter_reorder(fwd.ctypes.data if l else None, bwd.ctypes.data if l else None, p, l,
+                                              order.ctypes.data if l else None, seen.ctypes.data if l else None, C.byref(n))
+    return rc, order, seen[:n.value]
 
 
 def mmtrain_layer_ctx_bytes(desc: Optional[LayerDesc], total_tokens: int) -> int:

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmmtrain.so")
-SOURCES = ["api.hip", "elementwise.hip", "gemm_simple.hip", "gemm_mfma.hip", "attn_simple.hip", "attn_mfma.hip", "reorder.hip", "optimizer.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "gemm_simple.hip", "gemm_mfma.hip", "attn_simple.hip", "attn_mfma.hip", "reorder.hip", "pipeline.hip", "optimizer.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -623,6 +623,37 @@ int mmtrain_intra_reorder(const double *sizes, int32_t n, int32_t m, int32_t *or
     return MMTRAIN_OK;
 }
 
+static bool durations_ok(const double *v, size_t n) {
+    for (size_t i = 0; i < n; ++i)
+        if (!(v[i] >= 0.0) || v[i] > 1e300) return false;              // also rejects NaN
+    return true;
+}
+
+int mmtrain_pipeline_1f1b(const double *fwd, const double *bwd, int32_t p, int32_t l, const int32_t *order,
+                          double *makespan, double *intervals) {
+    if (p < 1 || l < 0 || (l > 0 && (!fwd || !bwd))) return MMTRAIN_ERR_INVALID_ARG;
+    if ((size_t)p * (size_t)l > (size_t)1 << 28) return MMTRAIN_ERR_INVALID_ARG;
+    if (!durations_ok(fwd, (size_t)p * l) || !durations_ok(bwd, (size_t)p * l)) return MMTRAIN_ERR_INVALID_ARG;
+    if (order) {
+        std::vector<char> seen((size_t)l, 0);
+        for (int32_t q = 0; q < l; ++q) {
+            if (order[q] < 0 || order[q] >= l || seen[order[q]]) return MMTRAIN_ERR_INVALID_ARG;
+            seen[order[q]] = 1;
+        }
+    }
+    if (l == 0) { if (makespan) *makespan = 0.0; return MMTRAIN_OK; }
+    return pipeline_1f1b(fwd, bwd, p, l, order, makespan, intervals) ? MMTRAIN_ERR_INVALID_ARG : MMTRAIN_OK;
+}
+
+int mmtrain_inter_reorder(const double *fwd, const double *bwd, int32_t p, int32_t l, int32_t *order,
+                          double *intervals_seen, int32_t *n_intervals) {
+    if (p < 1 || l < 0 || (l > 0 && (!fwd || !bwd || !order))) return MMTRAIN_ERR_INVALID_ARG;
+    if ((size_t)p * (size_t)l > (size_t)1 << 28) return MMTRAIN_ERR_INVALID_ARG;
+    if (!durations_ok(fwd, (size_t)p * l) || !durations_ok(bwd, (size_t)p * l)) return MMTRAIN_ERR_INVALID_ARG;
+    inter_reorder(fwd, bwd, p, l, order, intervals_seen, n_intervals);
+    return MMTRAIN_OK;
+}
+
 int mmtrain_adam_step(const mmtrain_adam_desc *d, int64_t n, float *master, float *grad, float *exp_avg,
                       float *exp_avg_sq, void *param_out, int32_t param_dtype, void *hip_stream) {
     if (!d || d->struct_size != sizeof(mmtrain_adam_desc) || n < 0) return MMTRAIN_ERR_INVALID_ARG;

@@ -60,6 +60,12 @@ struct AttnArgs {
 // reorder.hip (host): Algorithm 1 and the tile orders above
 int intra_reorder(const double *sizes, int n, int m, int32_t *order, int32_t *group_begin, double *group_load);
 void attn_tile_order(const int32_t *cu_host, const uint8_t *modes_host, int default_mode, int S, int T, AttnArgs &a);
+// pipeline.hip (host): timeline of the one-forward-one-backward pipeline schedule and Algorithm 2.
+// fwd / bwd: [p][l] durations by original microbatch index; order: [l] (null: identity); return 0 on success
+int pipeline_1f1b(const double *fwd, const double *bwd, int p, int l, const int32_t *order, double *makespan,
+                  double *intervals /* [l] or null */);
+int inter_reorder(const double *fwd, const double *bwd, int p, int l, int32_t *order, double *intervals_seen /* [l] or null */,
+                  int32_t *n_seen /* or null */);
 // attn_simple.hip: fp32 arithmetic on the vector ALUs, any storage dtype
 hipError_t attn_simple_fwd(int dtype, const AttnArgs &a, hipStream_t st);
 hipError_t attn_simple_bwd(int dtype, const AttnArgs &a, hipStream_t st);
