@@ -131,8 +131,8 @@ void carve_bwd(Bump &b, const Dims &D, size_t T, BwdWs &w) {
     w.d_o = b.take_elems(T * D.nq, D.dtype);
     w.d_qkv = b.take_elems(T * D.nqkv, D.dtype);
     w.Dsum = b.take<float>(T * D.nh);
-    w.part_g = b.take<float>((size_t)norm_bwd_blocks((int)T) * D.H);
-    w.part_b = b.take<float>((size_t)norm_bwd_blocks((int)T) * D.H);
+    w.part_g = b.take<float>((size_t)norm_bwd_blocks((int)T, D.H) * D.H);
+    w.part_b = b.take<float>((size_t)norm_bwd_blocks((int)T, D.H) * D.H);
     const int maxn = D.nqkv > D.F1 ? (D.nqkv > D.H ? D.nqkv : D.H) : (D.F1 > D.H ? D.F1 : D.H);
     w.part_c = b.take<float>((size_t)colsum_slabs((int)T) * maxn);
     // scratch for the fp32 partial products of GEMMs that are cut along K (see gemm_scratch_bytes)
@@ -342,7 +342,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     Bump bw = {(uint8_t *)workspace, 0};
     BwdWs w;
     carve_bwd(bw, D, (size_t)T, w);
-    const int nb = norm_bwd_blocks(T), ns = colsum_slabs(T);
+    const int nb = norm_bwd_blocks(T, D.H), ns = colsum_slabs(T);
 
     // ---- MLP block:  y = y1 + m . Wfc2^T (+ b_fc2)
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), w.split_ws, w.split_bytes), st));

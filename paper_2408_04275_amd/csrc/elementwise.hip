@@ -134,12 +134,17 @@ hipError_t norm_fwd(int dtype, bool layernorm, const void *x, const void *g, con
 // A workgroup walks rows blockIdx.x, blockIdx.x + gridDim.x, ...; each thread owns the same
 // columns in every row, so the gain/bias partial sums stay in registers and are written once
 // per workgroup to part_g / part_b [gridDim.x, H].
-constexpr int NORM_BWD_MAXC = 4;          // column chunks of 8 per thread: H <= 256 * 8 * 4 = 8192
+constexpr int NORM_BWD_MAXC = 4;          // column chunks of 8 per thread: H <= 256 * 8 * 4 = 8192 (the kernel is also
+                                          // built for 1 and 2 chunks: fewer registers per thread, more rows in flight)
 constexpr int NORM_BWD_GRID = 512;
 
-int norm_bwd_blocks(int T) { return T < NORM_BWD_GRID ? (T > 0 ? T : 1) : NORM_BWD_GRID; }
+// narrow rows leave registers for more resident workgroups: twice the grid
+int norm_bwd_blocks(int T, int H) {
+    const int grid = H <= 4096 ? 2 * NORM_BWD_GRID : NORM_BWD_GRID;
+    return T < grid ? (T > 0 ? T : 1) : grid;
+}
 
-template <typename T, bool LN>
+template <typename T, bool LN, int NORM_BWD_MAXC>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ d_out, const T *__restrict__ x,
                                                        const T *__restrict__ g, const float *__restrict__ mean,
                                                        const float *__restrict__ rstd, const T *__restrict__ d_res,
@@ -212,10 +217,12 @@ hipError_t norm_bwd(int dtype, bool layernorm, const void *d_out, const void *x,
                     float *part_b, int T, int H, hipStream_t st) {
     if (T == 0) return hipSuccess;
     if (H > 256 * 8 * NORM_BWD_MAXC) return hipErrorInvalidValue;
-    const int grid = norm_bwd_blocks(T);
-#define L(TT, LNV) norm_bwd_kernel<TT, LNV><<<grid, 256, 0, st>>>((const TT *)d_out, (const TT *)x, (const TT *)g, mean, rstd, (const TT *)d_res, (TT *)d_in, part_g, part_b, T, H)
+    const int grid = norm_bwd_blocks(T, H);
+#define L1(TT, LNV, MC) norm_bwd_kernel<TT, LNV, MC><<<grid, 256, 0, st>>>((const TT *)d_out, (const TT *)x, (const TT *)g, mean, rstd, (const TT *)d_res, (TT *)d_in, part_g, part_b, T, H)
+#define L(TT, LNV) do { if (H <= 2048) L1(TT, LNV, 1); else if (H <= 4096) L1(TT, LNV, 2); else L1(TT, LNV, 4); } while (0)
     if (dtype == DT_F32) { if (layernorm) L(float, true); else L(float, false); }
     else { if (layernorm) L(bf16_t, true); else L(bf16_t, false); }
+#undef L1
 #undef L
     return hipGetLastError();
 }

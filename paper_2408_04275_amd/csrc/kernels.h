@@ -80,8 +80,8 @@ hipError_t prep_tokens(const int *cu, const uint8_t *modes, int default_mode, in
 hipError_t norm_fwd(int dtype, bool layernorm, const void *x, const void *g, const void *b, void *out,
                     float *mean, float *rstd, int T, int H, float eps, hipStream_t st);
 // d_in = norm_bwd(d_out) + d_res;  gain/bias gradient partial sums go to part_g/part_b
-// ([norm_bwd_blocks(T), H] fp32 each; null = skip).
-int norm_bwd_blocks(int T);
+// ([norm_bwd_blocks(T, H), H] fp32 each; null = skip).
+int norm_bwd_blocks(int T, int H);
 hipError_t norm_bwd(int dtype, bool layernorm, const void *d_out, const void *x, const void *g,
                     const float *mean, const float *rstd, const void *d_res, void *d_in,
                     float *part_g, float *part_b, int T, int H, hipStream_t st);
