@@ -7,8 +7,9 @@ One step = mmtrain_layer_fwd + mmtrain_layer_bwd (all weight gradients) on one s
 already resident in HBM.  Prints ONE JSON line: throughput in model TFLOP/s (GEMMs 2*T*K*N forward and
 twice that backward; attention 4*d per unmasked (query, key) pair per head forward, 8*d backward), the
 fraction of the MI355X dense bf16 MFMA peak, a roofline object for the dominant kernel (durations from
-HIP events recorded inside the timed region on the launch stream), and the fp64 oracle timed on the host
-cores on a bounded sample of the same workload.
+HIP events recorded inside the timed region on the launch stream, around that kernel class only; the other
+classes' durations in "kernels" come from a short untimed pass in front of it, with events around every
+class), and the fp64 oracle timed on the host cores on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -163,25 +164,36 @@ def main():
                           "higher_is_better": True, "dtype": "bf16" if shape.dtype == wl.BF16 else "f32", "data": "synthetic",
                           "config": {"workload": f"config {args.config}: {shape.name}", "graph": True}}))
         return
-    mm.mmtrain_profile_enable(True)
-    for k in range(5):
-        mm.mmtrain_profile_read(k, reset=True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        check(runner.forward(), "mmtrain_layer_fwd")
-        check(runner.backward(), "mmtrain_layer_bwd")
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    mm.mmtrain_profile_enable(False)
-    ms_per_step = dt * 1e3 / args.steps
+    names = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd"]
+
+    def timed_pass(steps, class_mask):
+        """`steps` steps with HIP events around the launches of the classes in class_mask; wall time per step and the
+        event-timed duration per step of each class."""
+        for k in range(5):
+            mm.mmtrain_profile_read(k, reset=True)
+        mm.mmtrain_profile_enable(class_mask)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            check(runner.forward(), "mmtrain_layer_fwd")
+            check(runner.backward(), "mmtrain_layer_bwd")
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        mm.mmtrain_profile_enable(0)
+        res = {}
+        for k, name in enumerate(names):
+            ms, n = mm.mmtrain_profile_read(k, reset=True)
+            res[name] = {"ms_per_step": ms / steps, "launches_per_step": n / steps}
+        return dt * 1e3 / steps, res
+
+    # Breakdown pass (untimed for the headline): every class bracketed by events.  It names the dominant GEMM class;
+    # the timed region then carries events around that class only (36 event pairs per step cost about 1 % of the step).
+    _, prof = timed_pass(max(3, min(args.steps, 10)), mm.PROF_ALL)
+    dom = max(("gemm_nt", "gemm_nn", "gemm_tn"), key=lambda n: prof[n]["ms_per_step"])
+    ms_per_step, timed = timed_pass(args.steps, 1 << names.index(dom))
+    prof[dom] = timed[dom]                       # the dominant class's figures come from the timed region itself
     tflops = flops["fwd_bwd"] / (ms_per_step * 1e-3) / 1e12
 
-    # per-kernel-class durations from the events recorded inside the timed region
-    names = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd"]
-    prof = {}
-    for k, name in enumerate(names):
-        ms, n = mm.mmtrain_profile_read(k, reset=True)
-        prof[name] = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps}
     gf = gemm_flops_by_layout(shape, T)
     peak = PEAK_BF16_TFLOPS if shape.dtype == wl.BF16 else PEAK_F32_TFLOPS
     kernels = {}
@@ -192,7 +204,6 @@ def main():
     af, ab = prof["attn_fwd"]["ms_per_step"], prof["attn_bwd"]["ms_per_step"]
     kernels["attn_fwd"] = {"tflops": flops["attn_fwd"] / (af * 1e-3) / 1e12 if af > 0 else None, "ms_per_step": af}
     kernels["attn_bwd"] = {"tflops": 2 * flops["attn_fwd"] / (ab * 1e-3) / 1e12 if ab > 0 else None, "ms_per_step": ab}
-    dom = max(("gemm_nt", "gemm_nn", "gemm_tn"), key=lambda n: kernels[n]["ms_per_step"])
     dom_launches = max(prof[dom]["launches_per_step"], 1)
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"], "peak": peak, "unit": "TFLOP/s",
                 "frac": (kernels[dom]["tflops"] or 0.0) / peak,
@@ -213,7 +224,9 @@ def main():
                    "hidden": shape.hidden, "heads": f"{shape.n_heads}/{shape.n_kv_heads}x{shape.head_dim}",
                    "ffn_hidden": shape.ffn_hidden, "model_tflop_per_step": flops["fwd_bwd"] / 1e12,
                    "attention_share": 3 * flops["attn_fwd"] / flops["fwd_bwd"]},
-        "roofline": roofline, "kernels": kernels, "context": PAPER_CONTEXT,
+        "roofline": roofline, "kernels": kernels,
+        "kernels_note": f"{dom}: events inside the timed region; the others: untimed breakdown pass before it",
+        "context": PAPER_CONTEXT,
     }
     if not args.no_cpu_baseline:
         del runner

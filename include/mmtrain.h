@@ -184,18 +184,22 @@ MMTRAIN_API const char *mmtrain_status_string(int status);
 
 /* ------------------------------------------------------------------------
  * Measurement aid (not part of the layer's arithmetic).  While enabled, the
- * layer calls bracket each launch of the classes below with HIP events on the
- * caller's stream; mmtrain_profile_read waits for the recorded events of one
- * class, returns their summed duration and count, and (reset != 0) forgets
- * them.  Process-wide, not thread-safe; event objects are created on demand
- * and reused.  Used by the benchmark to obtain per-kernel launch durations
- * inside the timed region.
+ * layer calls bracket each launch of the enabled classes below with HIP events
+ * on the caller's stream; mmtrain_profile_read waits for the recorded events of
+ * one class, returns their summed duration and count, and (reset != 0) forgets
+ * them.  mmtrain_profile_enable takes a mask: bit k enables class k, 0 switches
+ * everything off, MMTRAIN_PROF_ALL enables all (an event pair costs a few
+ * microseconds on the stream, so a timed region enables only what it reports).
+ * Process-wide, not thread-safe; event objects are created on demand and
+ * reused.  Used by the benchmark to obtain per-kernel launch durations inside
+ * the timed region.
  * ------------------------------------------------------------------------ */
 typedef enum {
     MMTRAIN_PROF_GEMM_NT = 0, MMTRAIN_PROF_GEMM_NN = 1, MMTRAIN_PROF_GEMM_TN = 2,
     MMTRAIN_PROF_ATTN_FWD = 3, MMTRAIN_PROF_ATTN_BWD = 4
 } mmtrain_prof_kind;
-MMTRAIN_API void mmtrain_profile_enable(int on);
+#define MMTRAIN_PROF_ALL 0x1f
+MMTRAIN_API void mmtrain_profile_enable(int class_mask);
 MMTRAIN_API int mmtrain_profile_read(int32_t kind, double *total_ms, int64_t *launches, int reset);
 
 /* ------------------------------------------------------------------------

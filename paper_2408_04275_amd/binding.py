@@ -329,8 +329,14 @@ def mmtrain_attn_bwd(desc, batch, qkv, o, lse, d_o, d_qkv, workspace, workspace_
                                            _ptr(d_qkv), _ptr(workspace), workspace_bytes, _stream(stream))
 
 
-def mmtrain_profile_enable(on: bool) -> None:
-    load_library().mmtrain_profile_enable(1 if on else 0)
+PROF_ALL = 0x1f
+
+
+def mmtrain_profile_enable(class_mask) -> None:
+    """Bit k of class_mask enables the event timing of class PROF_* = k; True = all classes, False / 0 = off."""
+    if class_mask is True:
+        class_mask = PROF_ALL
+    load_library().mmtrain_profile_enable(int(class_mask))
 
 
 def mmtrain_profile_read(kind: int, reset: bool = True):

@@ -194,7 +194,7 @@ hipError_t fill_zero(void *p, size_t elems, int dtype, hipStream_t st) {
 
 // ---- optional per-kernel-class timing with HIP events on the caller's stream -------------
 struct Profiler {
-    bool on = false;
+    int mask = 0;                                  // bit k: class k is being timed
     struct Span { int kind; hipEvent_t a, b; };
     std::vector<Span> spans;
     std::vector<hipEvent_t> pool;
@@ -210,7 +210,7 @@ Profiler g_prof;
 struct ProfScope {
     int kind; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
     ProfScope(int k, hipStream_t s) : kind(k), st(s) {
-        if (!g_prof.on) return;
+        if (!((g_prof.mask >> k) & 1)) return;
         a = g_prof.get(); b = g_prof.get();
         if (a && b) (void)hipEventRecord(a, st);
     }
@@ -502,7 +502,7 @@ int mmtrain_stack_bwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mm
 
 // ---- profiling ---------------------------------------------------------------------
 
-void mmtrain_profile_enable(int on) { g_prof.on = on != 0; }
+void mmtrain_profile_enable(int class_mask) { g_prof.mask = class_mask & MMTRAIN_PROF_ALL; }
 
 int mmtrain_profile_read(int32_t kind, double *total_ms, int64_t *launches, int reset) {
     if (!total_ms || !launches) return MMTRAIN_ERR_INVALID_ARG;
