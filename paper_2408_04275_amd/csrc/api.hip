@@ -40,7 +40,7 @@ struct Ctx {
 
 struct BwdWs {
     void *d_m, *d_pre, *d_h, *d_y1, *d_o, *d_qkv;
-    float *Dsum, *part_g, *part_b, *part_c;
+    float *Dsum, *part_g, *part_b, *part_c, *part_din, *part_dres;
     void *split_ws; size_t split_bytes;     // fp32 partial products of split weight-gradient GEMMs
 };
 
@@ -133,6 +133,9 @@ void carve_bwd(Bump &b, const Dims &D, size_t T, BwdWs &w) {
     w.Dsum = b.take<float>(T * D.nh);
     w.part_g = b.take<float>((size_t)norm_bwd_blocks((int)T, D.H) * D.H);
     w.part_b = b.take<float>((size_t)norm_bwd_blocks((int)T, D.H) * D.H);
+    const bool enc = D.kind == MMTRAIN_ENCODER;            // bias gradients that the normalisation's backward kernel sums
+    w.part_din = enc ? b.take<float>((size_t)norm_bwd_blocks((int)T, D.H) * D.H) : nullptr;
+    w.part_dres = enc ? b.take<float>((size_t)norm_bwd_blocks((int)T, D.H) * D.H) : nullptr;
     const int maxn = D.nqkv > D.F1 ? (D.nqkv > D.H ? D.nqkv : D.H) : (D.F1 > D.H ? D.F1 : D.H);
     w.part_c = b.take<float>((size_t)colsum_slabs((int)T) * maxn);
     // scratch for the fp32 partial products of GEMMs that are cut along K (see gemm_scratch_bytes)
@@ -347,31 +350,25 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     // ---- MLP block:  y = y1 + m . Wfc2^T (+ b_fc2)
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), w.split_ws, w.split_bytes), st));
     if (G.w_fc2) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
-    if (enc && G.b_fc2) {
-        HIP_TRY(colsum_partials(D.dtype, dy, T, D.H, D.H, w.part_c, st));
-        HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.H, G.b_fc2, accum, st));
-    }
-    if (enc) HIP_TRY(gelu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, (long)T * D.F, st));
-    else HIP_TRY(swiglu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F, st));
-    if (enc && G.b_fc1) {
-        HIP_TRY(colsum_partials(D.dtype, w.d_pre, T, D.F1, D.F1, w.part_c, st));
+    if (enc && G.b_fc1) {                         // the bias gradient is the column sum of what this kernel writes
+        HIP_TRY(gelu_bwd_colsum(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F1, w.part_c, st));
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.F1, G.b_fc1, accum, st));
-    }
+    } else if (enc) HIP_TRY(gelu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, (long)T * D.F, st));
+    else HIP_TRY(swiglu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F, st));
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.H, D.F1, w.d_pre, D.F1, W->w_fc1, D.H, w.d_h, D.H), w.split_ws, w.split_bytes), st));
     if (G.w_fc1) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
-    // d_y1 = dy + norm2_bwd(d_h2)
+    // d_y1 = dy + norm2_bwd(d_h2); the same kernel sums the columns of dy (b_fc2's gradient) and of d_y1 (b_o's)
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
-                     G.norm2_w ? w.part_g : nullptr, (enc && G.norm2_b) ? w.part_b : nullptr, T, D.H, st));
+                     G.norm2_w ? w.part_g : nullptr, (enc && G.norm2_b) ? w.part_b : nullptr,
+                     (enc && G.b_o) ? w.part_din : nullptr, (enc && G.b_fc2) ? w.part_dres : nullptr, T, D.H, st));
     if (G.norm2_w) HIP_TRY(reduce_partials(gdt, w.part_g, nb, D.H, G.norm2_w, accum, st));
     if (enc && G.norm2_b) HIP_TRY(reduce_partials(gdt, w.part_b, nb, D.H, G.norm2_b, accum, st));
+    if (enc && G.b_o) HIP_TRY(reduce_partials(gdt, w.part_din, nb, D.H, G.b_o, accum, st));
+    if (enc && G.b_fc2) HIP_TRY(reduce_partials(gdt, w.part_dres, nb, D.H, G.b_fc2, accum, st));
 
     // ---- attention block:  y1 = x + o . Wo^T (+ b_o)
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.nq, D.H, w.d_y1, D.H, W->w_o, D.nq, w.d_o, D.nq), w.split_ws, w.split_bytes), st));
     if (G.w_o) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.nq, T, w.d_y1, D.H, c.o, D.nq, G.w_o, D.nq, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
-    if (enc && G.b_o) {
-        HIP_TRY(colsum_partials(D.dtype, w.d_y1, T, D.H, D.H, w.part_c, st));
-        HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.H, G.b_o, accum, st));
-    }
     AttnArgs a = mk_attn(D, batch, c);
     a.d_o = w.d_o; a.d_qkv = w.d_qkv; a.Dsum = w.Dsum;
     const bool fused_unrotate = !enc && D.dtype == DT_BF16 && (D.d == 64 || D.d == 128);       // the matrix-core kernels rotate dQ, dK back themselves
@@ -389,7 +386,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     if (G.w_qkv) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     // dx = d_y1 + norm1_bwd(d_h1)
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
-                     G.norm1_w ? w.part_g : nullptr, (enc && G.norm1_b) ? w.part_b : nullptr, T, D.H, st));
+                     G.norm1_w ? w.part_g : nullptr, (enc && G.norm1_b) ? w.part_b : nullptr, nullptr, nullptr, T, D.H, st));
     if (G.norm1_w) HIP_TRY(reduce_partials(gdt, w.part_g, nb, D.H, G.norm1_w, accum, st));
     if (enc && G.norm1_b) HIP_TRY(reduce_partials(gdt, w.part_b, nb, D.H, G.norm1_b, accum, st));
     return MMTRAIN_OK;

@@ -144,20 +144,27 @@ int norm_bwd_blocks(int T, int H) {
     return T < grid ? (T > 0 ? T : 1) : grid;
 }
 
-template <typename T, bool LN, int NORM_BWD_MAXC>
+template <typename T, bool LN, int NORM_BWD_MAXC, bool COLS>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ d_out, const T *__restrict__ x,
                                                        const T *__restrict__ g, const float *__restrict__ mean,
                                                        const float *__restrict__ rstd, const T *__restrict__ d_res,
                                                        T *__restrict__ d_in, float *__restrict__ part_g,
-                                                       float *__restrict__ part_b, int nrows, int H) {
+                                                       float *__restrict__ part_b, float *__restrict__ part_din,
+                                                       float *__restrict__ part_dres, int nrows, int H) {
     __shared__ float red[4];
     float gv[NORM_BWD_MAXC][8], ag[NORM_BWD_MAXC][8], ab[NORM_BWD_MAXC][8];
+    // COLS: column sums of the result and of the added gradient as well (the bias gradients of the two linears
+    // that sit on either side of the normalisation's residual branch)
+    float ad[COLS ? NORM_BWD_MAXC : 1][8], ae[COLS ? NORM_BWD_MAXC : 1][8];
 #pragma unroll
     for (int i = 0; i < NORM_BWD_MAXC; ++i) {
         const int c = (threadIdx.x + i * 256) * 8;
         if (c < H) load8(g + c, gv[i]);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { ag[i][j] = 0.f; ab[i][j] = 0.f; }
+        for (int j = 0; j < 8; ++j) {
+            ag[i][j] = 0.f; ab[i][j] = 0.f;
+            if (COLS) { ad[i][j] = 0.f; ae[i][j] = 0.f; }
+        }
     }
     for (size_t row = blockIdx.x; row < (size_t)nrows; row += gridDim.x) {
         const float r = rstd[row];
@@ -197,7 +204,11 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ d_o
             const int c = (threadIdx.x + i * 256) * 8;
             if (c < H) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) rv[i][j] += r * (dv[i][j] - s0 - xh[i][j] * s1);
+                for (int j = 0; j < 8; ++j) {
+                    if (COLS) ae[i][j] += rv[i][j];
+                    rv[i][j] += r * (dv[i][j] - s0 - xh[i][j] * s1);
+                    if (COLS) ad[i][j] += rv[i][j];
+                }
                 store8(d_in + row * H + c, rv[i]);
             }
         }
@@ -208,20 +219,25 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ d_o
         if (c < H) {
             if (part_g) store8(part_g + (size_t)blockIdx.x * H + c, ag[i]);
             if (LN && part_b) store8(part_b + (size_t)blockIdx.x * H + c, ab[i]);
+            if (COLS && part_din) store8(part_din + (size_t)blockIdx.x * H + c, ad[i]);
+            if (COLS && part_dres) store8(part_dres + (size_t)blockIdx.x * H + c, ae[i]);
         }
     }
 }
 
 hipError_t norm_bwd(int dtype, bool layernorm, const void *d_out, const void *x, const void *g,
                     const float *mean, const float *rstd, const void *d_res, void *d_in, float *part_g,
-                    float *part_b, int T, int H, hipStream_t st) {
+                    float *part_b, float *part_din, float *part_dres, int T, int H, hipStream_t st) {
     if (T == 0) return hipSuccess;
     if (H > 256 * 8 * NORM_BWD_MAXC) return hipErrorInvalidValue;
     const int grid = norm_bwd_blocks(T, H);
-#define L1(TT, LNV, MC) norm_bwd_kernel<TT, LNV, MC><<<grid, 256, 0, st>>>((const TT *)d_out, (const TT *)x, (const TT *)g, mean, rstd, (const TT *)d_res, (TT *)d_in, part_g, part_b, T, H)
+    const bool cols = part_din || part_dres;
+#define L2(TT, LNV, MC, CV) norm_bwd_kernel<TT, LNV, MC, CV><<<grid, 256, 0, st>>>((const TT *)d_out, (const TT *)x, (const TT *)g, mean, rstd, (const TT *)d_res, (TT *)d_in, part_g, part_b, part_din, part_dres, T, H)
+#define L1(TT, LNV, MC) do { if (cols) L2(TT, LNV, MC, true); else L2(TT, LNV, MC, false); } while (0)
 #define L(TT, LNV) do { if (H <= 2048) L1(TT, LNV, 1); else if (H <= 4096) L1(TT, LNV, 2); else L1(TT, LNV, 4); } while (0)
     if (dtype == DT_F32) { if (layernorm) L(float, true); else L(float, false); }
     else { if (layernorm) L(bf16_t, true); else L(bf16_t, false); }
+#undef L2
 #undef L1
 #undef L
     return hipGetLastError();
@@ -296,11 +312,18 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ in, i
     if (c >= N) return;
     const int r0 = blockIdx.y * COLSUM_ROWS;
     const int r1 = min(nrows, r0 + COLSUM_ROWS);
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, v[8];
-    for (int r = r0; r < r1; ++r) {
-        load8(in + (size_t)r * ld + c, v);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int r = r0; r < r1; r += 8) {              // 8 rows requested before the first is added
+        float v[8][8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] += v[j];
+        for (int k = 0; k < 8; ++k)
+            if (r + k < r1) load8(in + (size_t)(r + k) * ld + c, v[k]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (r + k < r1) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] += v[k][j];
+            }
     }
     store8(part + (size_t)blockIdx.y * N + c, acc);
 }
@@ -437,11 +460,50 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T *__restrict__ d_a
     store8(d_z + idx * 8, v);
 }
 
+// The same over [nrows, N] with the column sums of d_z (the bias gradient of the linear in front of the activation):
+// a thread owns 8 columns of a slab of COLSUM_ROWS rows; part[slab, N] receives the slab's sums.
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_colsum_kernel(const T *__restrict__ d_a, const T *__restrict__ z,
+                                                              T *__restrict__ d_z, int nrows, int N,
+                                                              float *__restrict__ part) {
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 8;
+    if (c >= N) return;
+    const int r0 = blockIdx.y * COLSUM_ROWS, r1 = min(nrows, r0 + COLSUM_ROWS);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int r = r0; r < r1; r += 4) {
+        float v[4][8], g[4][8];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (r + k < r1) { load8(z + (size_t)(r + k) * N + c, v[k]); load8(d_a + (size_t)(r + k) * N + c, g[k]); }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (r + k < r1) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float cdf = 0.5f * (1.f + erff(v[k][j] * 0.70710678118654752f));
+                    const float pdf = 0.3989422804014327f * expf(-0.5f * v[k][j] * v[k][j]);
+                    v[k][j] = g[k][j] * (cdf + v[k][j] * pdf);
+                }
+                store8(d_z + (size_t)(r + k) * N + c, v[k]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] += v[k][j];
+            }
+    }
+    store8(part + (size_t)blockIdx.y * N + c, acc);
+}
+
 hipError_t gelu_fwd(int dtype, const void *z, void *a, long n, hipStream_t st) {
     const long nc = n / 8;
     if (nc == 0) return hipSuccess;
     if (dtype == DT_F32) gelu_fwd_kernel<float><<<ceil_div(nc, 256), 256, 0, st>>>((const float *)z, (float *)a, nc);
     else gelu_fwd_kernel<bf16_t><<<ceil_div(nc, 256), 256, 0, st>>>((const bf16_t *)z, (bf16_t *)a, nc);
+    return hipGetLastError();
+}
+hipError_t gelu_bwd_colsum(int dtype, const void *d_a, const void *z, void *d_z, int T, int N, float *part, hipStream_t st) {
+    if (T == 0 || N == 0) return hipSuccess;
+    dim3 grid(ceil_div(N, 2048), colsum_slabs(T));
+    if (dtype == DT_F32) gelu_bwd_colsum_kernel<float><<<grid, 256, 0, st>>>((const float *)d_a, (const float *)z, (float *)d_z, T, N, part);
+    else gelu_bwd_colsum_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t *)d_a, (const bf16_t *)z, (bf16_t *)d_z, T, N, part);
     return hipGetLastError();
 }
 hipError_t gelu_bwd(int dtype, const void *d_a, const void *z, void *d_z, long n, hipStream_t st) {

@@ -79,12 +79,12 @@ hipError_t prep_tokens(const int *cu, const uint8_t *modes, int default_mode, in
                        hipStream_t st);
 hipError_t norm_fwd(int dtype, bool layernorm, const void *x, const void *g, const void *b, void *out,
                     float *mean, float *rstd, int T, int H, float eps, hipStream_t st);
-// d_in = norm_bwd(d_out) + d_res;  gain/bias gradient partial sums go to part_g/part_b
-// ([norm_bwd_blocks(T, H), H] fp32 each; null = skip).
+// d_in = norm_bwd(d_out) + d_res;  gain/bias gradient partial sums go to part_g/part_b, the column sums of d_in
+// and of d_res to part_din / part_dres ([norm_bwd_blocks(T, H), H] fp32 each; null = skip).
 int norm_bwd_blocks(int T, int H);
 hipError_t norm_bwd(int dtype, bool layernorm, const void *d_out, const void *x, const void *g,
                     const float *mean, const float *rstd, const void *d_res, void *d_in,
-                    float *part_g, float *part_b, int T, int H, hipStream_t st);
+                    float *part_g, float *part_b, float *part_din, float *part_dres, int T, int H, hipStream_t st);
 // out[c] (+)= sum_r part[r, c]
 hipError_t reduce_partials(int dtype, const float *part, int rows, int N, void *out, bool accumulate,
                            hipStream_t st);
@@ -96,6 +96,8 @@ hipError_t swiglu_fwd(int dtype, const void *gu, void *m, int T, int F, hipStrea
 hipError_t swiglu_bwd(int dtype, const void *d_m, const void *gu, void *d_gu, int T, int F, hipStream_t st);
 hipError_t gelu_fwd(int dtype, const void *z, void *a, long n, hipStream_t st);
 hipError_t gelu_bwd(int dtype, const void *d_a, const void *z, void *d_z, long n, hipStream_t st);
+// the same over [T, N] rows, with the column sums of d_z as partial sums part[colsum_slabs(T), N]
+hipError_t gelu_bwd_colsum(int dtype, const void *d_a, const void *z, void *d_z, int T, int N, float *part, hipStream_t st);
 
 
 // optimizer.hip: one AdamW step on fp32 master weights; omb = 1 - beta, inv_bias1 = 1 / (1 - beta1^t),
