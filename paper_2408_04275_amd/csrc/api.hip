@@ -361,10 +361,11 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
                      G.norm2_w ? w.part_g : nullptr, (enc && G.norm2_b) ? w.part_b : nullptr,
                      (enc && G.b_o) ? w.part_din : nullptr, (enc && G.b_fc2) ? w.part_dres : nullptr, T, D.H, st));
-    if (G.norm2_w) HIP_TRY(reduce_partials(gdt, w.part_g, nb, D.H, G.norm2_w, accum, st));
-    if (enc && G.norm2_b) HIP_TRY(reduce_partials(gdt, w.part_b, nb, D.H, G.norm2_b, accum, st));
-    if (enc && G.b_o) HIP_TRY(reduce_partials(gdt, w.part_din, nb, D.H, G.b_o, accum, st));
-    if (enc && G.b_fc2) HIP_TRY(reduce_partials(gdt, w.part_dres, nb, D.H, G.b_fc2, accum, st));
+    {
+        const float *parts[4] = {w.part_g, w.part_b, w.part_din, w.part_dres};
+        void *outs[4] = {G.norm2_w, enc ? G.norm2_b : nullptr, enc ? G.b_o : nullptr, enc ? G.b_fc2 : nullptr};
+        HIP_TRY(reduce_partials_set(gdt, parts, outs, 4, nb, D.H, accum, st));
+    }
 
     // ---- attention block:  y1 = x + o . Wo^T (+ b_o)
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.nq, D.H, w.d_y1, D.H, W->w_o, D.nq, w.d_o, D.nq), w.split_ws, w.split_bytes), st));
@@ -387,8 +388,11 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     // dx = d_y1 + norm1_bwd(d_h1)
     HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
                      G.norm1_w ? w.part_g : nullptr, (enc && G.norm1_b) ? w.part_b : nullptr, nullptr, nullptr, T, D.H, st));
-    if (G.norm1_w) HIP_TRY(reduce_partials(gdt, w.part_g, nb, D.H, G.norm1_w, accum, st));
-    if (enc && G.norm1_b) HIP_TRY(reduce_partials(gdt, w.part_b, nb, D.H, G.norm1_b, accum, st));
+    {
+        const float *parts[2] = {w.part_g, w.part_b};
+        void *outs[2] = {G.norm1_w, enc ? G.norm1_b : nullptr};
+        HIP_TRY(reduce_partials_set(gdt, parts, outs, 2, nb, D.H, accum, st));
+    }
     return MMTRAIN_OK;
 }
 

@@ -301,8 +301,53 @@ hipError_t reduce_partials(int dtype, const float *part, int rows, int N, void *
     return hipGetLastError();
 }
 
+// Up to four reductions of the same shape in one launch (blockIdx.y picks the array): the gain, bias and column-sum
+// partial sums that one normalisation-backward launch leaves behind.
+struct ReduceSet { const float *part[4]; void *out[4]; };
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_partials_set_kernel(ReduceSet set, int rows, int N, bool accumulate) {
+    __shared__ float red[32][36];
+    const float *part = set.part[blockIdx.y];
+    T *out = (T *)set.out[blockIdx.y];
+    const int cl = threadIdx.x & 7, rl = threadIdx.x >> 3;
+    const int c = blockIdx.x * 32 + cl * 4;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (c < N)
+        for (int r = rl; r < rows; r += 32) s += *reinterpret_cast<const f32x4 *>(part + (size_t)r * N + c);
+    *reinterpret_cast<f32x4 *>(&red[rl][cl * 4]) = s;
+    __syncthreads();
+    const int oc = blockIdx.x * 32 + threadIdx.x;
+    if (threadIdx.x < 32 && oc < N) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) t += red[i][threadIdx.x];
+        if (accumulate) t += Elem<T>::load(out + oc);
+        Elem<T>::store(out + oc, t);
+    }
+}
+
+hipError_t reduce_partials_set(int dtype, const float *const *parts, void *const *outs, int n, int rows, int N,
+                               bool accumulate, hipStream_t st) {
+    ReduceSet set = {};
+    int m = 0;
+    for (int i = 0; i < n && m < 4; ++i)
+        if (parts[i] && outs[i]) { set.part[m] = parts[i]; set.out[m] = outs[i]; ++m; }
+    if (m == 0 || N == 0) return hipSuccess;
+    if (N % 4) {                                   // the vector form needs whole quads: fall back to one launch each
+        for (int i = 0; i < m; ++i) {
+            hipError_t e = reduce_partials(dtype, set.part[i], rows, N, set.out[i], accumulate, st);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    dim3 grid(ceil_div(N, 32), m);
+    if (dtype == DT_F32) reduce_partials_set_kernel<float><<<grid, 256, 0, st>>>(set, rows, N, accumulate);
+    else reduce_partials_set_kernel<bf16_t><<<grid, 256, 0, st>>>(set, rows, N, accumulate);
+    return hipGetLastError();
+}
+
 // ---- column sums (bias gradients) ----------------------------------------------------
-constexpr int COLSUM_ROWS = 64;
+constexpr int COLSUM_ROWS = 16;            // rows per workgroup: short slabs, so that a [T, N] pass has T N / 32768 workgroups
 int colsum_slabs(int T) { return T > 0 ? ceil_div(T, COLSUM_ROWS) : 1; }
 
 template <typename T>
