@@ -201,6 +201,13 @@ typedef enum {
 #define MMTRAIN_PROF_ALL 0x1f
 MMTRAIN_API void mmtrain_profile_enable(int class_mask);
 MMTRAIN_API int mmtrain_profile_read(int32_t kind, double *total_ms, int64_t *launches, int reset);
+/* Load balance of the attention kernels over the compute units (measurement aid; bf16 storage only).  While
+ * device_counters is not NULL, every workgroup of the attention kernels adds its run time, in ticks of the GPU's
+ * constant 100 MHz counter, to the entry of the compute unit it ran on: device memory, uint64[3][1024], rows =
+ * forward, dQ, dK/dV; the entry index is the hardware's compute-unit identifier (XCD, shader engine, unit), so most
+ * of the 1024 entries stay untouched.  The caller zeroes the buffer, owns it and keeps it alive until it has
+ * passed NULL again and the stream has drained.  Process-wide, not thread-safe. */
+MMTRAIN_API void mmtrain_profile_attn_busy(void *device_counters);
 
 /* ------------------------------------------------------------------------
  * Operator-level entry points: the kernels the layer calls are built from,

@@ -172,8 +172,11 @@ GemmArgs mk(int layout, int M, int N, int K, const void *A, int lda, const void 
     return g;
 }
 
+unsigned long long *g_attn_busy = nullptr;      // device [3][1024] or null: see mmtrain_profile_attn_busy
+
 AttnArgs mk_attn(const Dims &D, const mmtrain_batch *b, const Ctx &c) {
     AttnArgs a = {};
+    a.cu_busy = g_attn_busy;
     a.T = b->total_tokens; a.S = b->n_segments; a.nh = D.nh; a.nkv = D.nkv; a.d = D.d; a.scale = D.scale;
     a.cu = b->cu_seqlens_dev; a.modes = b->seg_mask_dev; a.default_mode = b->mask_mode;
     a.tok_seg = c.tok_seg; a.tok_info = c.tok_info; a.qkv = c.qkv; a.ld_qkv = D.nqkv; a.o = c.o; a.lse = c.lse;
@@ -503,6 +506,8 @@ int mmtrain_stack_bwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mm
 
 // ---- profiling ---------------------------------------------------------------------
 
+void mmtrain_profile_attn_busy(void *device_counters) { g_attn_busy = (unsigned long long *)device_counters; }
+
 void mmtrain_profile_enable(int class_mask) { g_prof.mask = class_mask & MMTRAIN_PROF_ALL; }
 
 int mmtrain_profile_read(int32_t kind, double *total_ms, int64_t *launches, int reset) {
@@ -582,6 +587,7 @@ static int attn_common(const mmtrain_layer_desc *desc, const mmtrain_batch *batc
     a.T = T; a.S = batch->n_segments; a.nh = D.nh; a.nkv = D.nkv; a.d = D.d; a.scale = D.scale;
     a.cu = batch->cu_seqlens_dev; a.modes = batch->seg_mask_dev; a.default_mode = batch->mask_mode;
     a.tok_seg = tok_seg; a.tok_info = tok_info; a.ld_qkv = D.nqkv; a.Dsum = Dsum;
+    a.cu_busy = g_attn_busy;
     attn_tile_order(batch->cu_seqlens_host, batch->seg_mask_host, batch->mask_mode, batch->n_segments, T, a);
     HIP_TRY(prep_tokens(batch->cu_seqlens_dev, batch->seg_mask_dev, batch->mask_mode, batch->n_segments, T, tok_seg, tok_info,
                         D.d, 0.f, nullptr, st));

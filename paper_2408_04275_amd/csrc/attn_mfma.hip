@@ -71,6 +71,16 @@ __device__ __forceinline__ f32x16 zero16() {
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
+// Per-compute-unit busy time (measurement aid): a workgroup adds its run time, in ticks of the constant 100 MHz
+// counter, to the entry of the compute unit it ran on: minus the time at its start, plus the time at its end
+// (unsigned wrap-around), so that nothing has to be kept in a register in between.
+__device__ __forceinline__ void add_busy(unsigned long long *row, bool end) {
+    if (row && threadIdx.x == 0) {
+        const unsigned long long t = wall_clock64();
+        atomicAdd(row + (__smid() & 1023u), end ? t : 0ull - t);
+    }
+}
+
 struct RowInfo { int lo, hi; };   // allowed partner range of one token
 
 __device__ __forceinline__ RowInfo query_range(const int2 *info, int q, int T) {
@@ -131,6 +141,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     constexpr int COPIES = FT / ROWS_PER_COPY / 4;                  // per copying wavefront (4 of them)
     constexpr int V_TASKS = 8 * UPR * 2;                            // (unit, 8-feature block, half of the unit's keys)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    add_busy(a.cu_busy, false);
 
     // grid: x = head, y = position in the dispatch order of the query tiles (heaviest first)
     const int head = blockIdx.x, g = head / (a.nh / a.nkv);
@@ -299,6 +310,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
             }
         if (half == 0) a.lse[(long)head * T + q] = (m_run * sl2 + __builtin_amdgcn_logf(l_tot)) * LN2;
     }
+    add_busy(a.cu_busy, true);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -395,6 +407,7 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     constexpr int TILE = BT2 * D * 2, SLOT = 2 * TILE;             // K tile, then V tile
     constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                 // per wavefront (4 wavefronts per tile)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    add_busy(a.cu_busy ? a.cu_busy + 1024 : nullptr, false);
 
     // grid: x = head, y = position in the dispatch order of the query tiles (heaviest first)
     const int head = blockIdx.x, g = head / (a.nh / a.nkv);
@@ -520,6 +533,7 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
                 if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(out + 32 * c + 8 * gq + 4 * half) = w;
             }
     }
+    add_busy(a.cu_busy ? a.cu_busy + 1024 : nullptr, true);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -532,6 +546,7 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     constexpr int TILE = BT2 * D * 2, SLOT = 2 * TILE + 2 * BT2 * 4;   // Q tile, dO tile, lse[64], D[64]
     constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                     // per wavefront and tile
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    add_busy(a.cu_busy ? a.cu_busy + 2048 : nullptr, false);
 
     // grid: x = key/value head, y = position in the dispatch order of the key tiles (heaviest first)
     const int g = blockIdx.x, group = a.nh / a.nkv;
@@ -698,6 +713,7 @@ done:
                 if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(ovp + 32 * c + 8 * gq + 4 * half) = w;
             }
     }
+    add_busy(a.cu_busy ? a.cu_busy + 2048 : nullptr, true);
 }
 
 template <typename K>

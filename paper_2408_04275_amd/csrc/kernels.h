@@ -56,6 +56,9 @@ struct AttnArgs {
     int use_order;
     uint8_t order_q[64];
     uint8_t order_k[128];
+    // MFMA path, measurement aid: when not null, device [3][1024] counters; every workgroup adds its run time
+    // (100 MHz ticks) to the entry of the compute unit it ran on (forward: row 0, dQ: row 1, dK/dV: row 2)
+    unsigned long long *cu_busy;
 };
 // reorder.hip (host): Algorithm 1 and the tile orders above
 int intra_reorder(const double *sizes, int n, int m, int32_t *order, int32_t *group_begin, double *group_load);

@@ -72,8 +72,22 @@ def bench_attn(a):
     fl = wl.model_flops(shape, cu, modes)["attn_fwd"]
     ms_f = _time(lambda: check(mm.mmtrain_attn_fwd(desc, batch, qkv, o, lse, ws, wsb), "attn_fwd"), a.iters)
     ms_b = _time(lambda: check(mm.mmtrain_attn_bwd(desc, batch, qkv, o, lse, d_o, d_qkv, ws, wsb), "attn_bwd"), a.iters)
-    print(json.dumps({"op": "attn", "config": a.config, "T": T, "segments": len(cu) - 1, "fwd_ms": ms_f, "bwd_ms": ms_b,
-                      "fwd_tflops": fl / ms_f / 1e9, "bwd_tflops": 2 * fl / ms_b / 1e9}))
+    out = {"op": "attn", "config": a.config, "T": T, "segments": len(cu) - 1, "fwd_ms": ms_f, "bwd_ms": ms_b,
+           "fwd_tflops": fl / ms_f / 1e9, "bwd_tflops": 2 * fl / ms_b / 1e9}
+    if a.cu_busy:
+        # one forward + backward with the per-compute-unit busy counters on: max / mean over the units that ran work
+        busy = torch.zeros((3, 1024), dtype=torch.int64, device="cuda")
+        mm.mmtrain_profile_attn_busy(busy)
+        check(mm.mmtrain_attn_fwd(desc, batch, qkv, o, lse, ws, wsb), "attn_fwd")
+        check(mm.mmtrain_attn_bwd(desc, batch, qkv, o, lse, d_o, d_qkv, ws, wsb), "attn_bwd")
+        torch.cuda.synchronize()
+        mm.mmtrain_profile_attn_busy(None)
+        rows = busy.cpu().numpy()
+        for name, r in zip(("fwd", "dq", "dkv"), rows):
+            used = r[r > 0].astype(np.float64) / 100.0            # 100 MHz ticks -> microseconds
+            out["cu_busy_" + name] = {"units": int(used.size), "mean_us": float(used.mean()), "max_us": float(used.max()),
+                                      "max_over_mean": float(used.max() / used.mean())}
+    print(json.dumps(out))
 
 
 def bench_adam(a):
@@ -114,6 +128,7 @@ def main(argv=None):
     t = sub.add_parser("attn")
     t.add_argument("--config", type=int, default=3)
     t.add_argument("--iters", type=int, default=20)
+    t.add_argument("--cu-busy", action="store_true", help="also report the attention kernels' load balance over the compute units")
     ad = sub.add_parser("adam")
     ad.add_argument("--mparams", type=int, default=202, help="millions of parameters (202 = one 7B layer)")
     ad.add_argument("--iters", type=int, default=20)

@@ -143,3 +143,43 @@ def test_attention_one_long_segment(mode):
 def test_attention_padded_head_dim(nh, nkv, d):
     # head dimensions that are not a native tile width run zero-padded in LDS and registers (80 = ViT-Huge)
     attn_case(mm.BF16, nh, nkv, d, RAGGED_CU, RAGGED_MODES, std=1.0, seed=7)
+
+
+def test_attention_busy_counters_leave_results_unchanged():
+    """The per-compute-unit busy counters (a measurement aid) change nothing in the outputs, and every workgroup's time
+    lands in some compute unit's entry."""
+    rng = np.random.default_rng(11)
+    cu = np.array([0, 300, 301, 1500, 2048], dtype=np.int32)
+    modes = np.array([0, 1, 0, 1], dtype=np.uint8)
+    T, nh, nkv, d = 2048, 4, 2, 128
+    nq, nk = nh * d, nkv * d
+    dqkv = to_device(wl.round_to(rng.standard_normal((T, nq + 2 * nk)), mm.BF16), mm.BF16)
+    dd_o = to_device(wl.round_to(rng.standard_normal((T, nq)), mm.BF16), mm.BF16)
+    desc = mm.make_desc(mm.DECODER, mm.BF16, 64, nh, nkv, d, 64)
+    batch = mm.PackedBatch.on_device(cu, modes)
+    wsb = mm.mmtrain_attn_workspace_bytes(T, len(cu) - 1, nh)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+
+    def run():
+        o = torch.zeros((T, nq), dtype=torch.bfloat16, device="cuda")
+        lse = torch.zeros((nh, T), dtype=torch.float32, device="cuda")
+        d_qkv = torch.zeros_like(dqkv)
+        check(mm.mmtrain_attn_fwd(desc, batch, dqkv, o, lse, ws, wsb), "mmtrain_attn_fwd")
+        check(mm.mmtrain_attn_bwd(desc, batch, dqkv, o, lse, dd_o, d_qkv, ws, wsb), "mmtrain_attn_bwd")
+        torch.cuda.synchronize()
+        return o, lse, d_qkv
+
+    plain = run()
+    busy = torch.zeros((3, 1024), dtype=torch.int64, device="cuda")
+    mm.mmtrain_profile_attn_busy(busy)
+    try:
+        counted = run()
+    finally:
+        mm.mmtrain_profile_attn_busy(None)
+    for a, b in zip(plain, counted):
+        assert torch.equal(a, b)
+    rows = busy.cpu().numpy()
+    for r in rows:
+        used = r[r != 0]
+        assert 1 <= used.size <= 256
+        assert (used > 0).all() and (used < 100_000_000).all()      # between one tick and a second, at 100 MHz
