@@ -166,6 +166,8 @@ def main():
                           "config": {"workload": f"config {args.config}: {shape.name}", "graph": True}}))
         return
     names = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd"]
+    # shader-clock and 100 MHz counters at the start and end of the first workgroup of the last bf16 GEMM launch
+    clock_probe = torch.zeros(4, dtype=torch.int64, device="cuda")
 
     def timed_pass(steps, class_mask):
         """`steps` steps with HIP events around the launches of the classes in class_mask; wall time per step and the
@@ -173,6 +175,7 @@ def main():
         for k in range(5):
             mm.mmtrain_profile_read(k, reset=True)
         mm.mmtrain_profile_enable(class_mask)
+        mm.mmtrain_profile_gemm_clock(clock_probe)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
@@ -181,6 +184,7 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         mm.mmtrain_profile_enable(0)
+        mm.mmtrain_profile_gemm_clock(None)
         res = {}
         for k, name in enumerate(names):
             ms, n = mm.mmtrain_profile_read(k, reset=True)
@@ -227,6 +231,8 @@ def main():
                    "attention_share": 3 * flops["attn_fwd"] / flops["fwd_bwd"]},
         "roofline": roofline, "kernels": kernels,
         "kernels_note": f"{dom}: events inside the timed region; the others: untimed breakdown pass before it",
+        # the clock a compute unit sustained during the last GEMM launch of the timed region (the published peak is quoted at 2400 MHz)
+        "gemm_shader_clock_mhz": mm.gemm_clock_mhz(clock_probe),
         "context": PAPER_CONTEXT,
     }
     if not args.no_cpu_baseline:

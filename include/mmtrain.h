@@ -208,6 +208,11 @@ MMTRAIN_API int mmtrain_profile_read(int32_t kind, double *total_ms, int64_t *la
  * of the 1024 entries stay untouched.  The caller zeroes the buffer, owns it and keeps it alive until it has
  * passed NULL again and the stream has drained.  Process-wide, not thread-safe. */
 MMTRAIN_API void mmtrain_profile_attn_busy(void *device_counters);
+/* Shader clock under the bf16 GEMM kernel (measurement aid).  While device_counters (device memory, uint64[4]) is not
+ * NULL, the first workgroup of every matrix-core GEMM launch stores the shader-clock counter and the GPU's constant
+ * 100 MHz counter at its start ([0], [1]) and at its end ([2], [3]); ([2] - [0]) / ([3] - [1]) x 100 MHz is the clock the
+ * compute unit sustained during that launch (the last launch's values remain).  Same ownership rules as above. */
+MMTRAIN_API void mmtrain_profile_gemm_clock(void *device_counters);
 
 /* ------------------------------------------------------------------------
  * Operator-level entry points: the kernels the layer calls are built from,

@@ -29,7 +29,8 @@ EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_
            "mmtrain_status_string", "mmtrain_gemm", "mmtrain_gemm_workspace_bytes", "mmtrain_attn_workspace_bytes", "mmtrain_attn_fwd",
            "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read", "mmtrain_intra_reorder", "mmtrain_adam_step",
            "mmtrain_stack_ctx_bytes", "mmtrain_stack_workspace_bytes", "mmtrain_stack_fwd", "mmtrain_stack_bwd",
-           "mmtrain_pipeline_1f1b", "mmtrain_inter_reorder", "mmtrain_profile_attn_busy")
+           "mmtrain_pipeline_1f1b", "mmtrain_inter_reorder", "mmtrain_profile_attn_busy",
+           "mmtrain_profile_gemm_clock")
 PROF_GEMM_NT, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD = range(5)
 
 WEIGHT_FIELDS = ("norm1_w", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
@@ -112,6 +113,8 @@ def load_library() -> C.CDLL:
     lib.mmtrain_profile_enable.argtypes = [C.c_int]
     lib.mmtrain_profile_attn_busy.restype = None
     lib.mmtrain_profile_attn_busy.argtypes = [P]
+    lib.mmtrain_profile_gemm_clock.restype = None
+    lib.mmtrain_profile_gemm_clock.argtypes = [P]
     lib.mmtrain_profile_read.restype = C.c_int
     lib.mmtrain_profile_read.argtypes = [I, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
     lib.mmtrain_adam_step.restype = C.c_int
@@ -344,6 +347,18 @@ def mmtrain_profile_enable(class_mask) -> None:
 def mmtrain_profile_attn_busy(counters) -> None:
     """counters: a zeroed device tensor of 3 x 1024 int64 (rows: forward, dQ, dK/dV), or None to switch off."""
     load_library().mmtrain_profile_attn_busy(None if counters is None else counters.data_ptr())
+
+
+def mmtrain_profile_gemm_clock(counters) -> None:
+    """counters: a device tensor of 4 int64 (shader-clock and 100 MHz counters at the start and end of the first workgroup of
+    the last bf16 GEMM launch), or None to switch off."""
+    load_library().mmtrain_profile_gemm_clock(None if counters is None else counters.data_ptr())
+
+
+def gemm_clock_mhz(counters):
+    """Shader clock in MHz from the four counters mmtrain_profile_gemm_clock fills (None if no launch wrote them)."""
+    c = [int(v) for v in counters.cpu().tolist()]
+    return 100.0 * (c[2] - c[0]) / (c[3] - c[1]) if c[3] > c[1] else None
 
 
 def mmtrain_profile_read(kind: int, reset: bool = True):

@@ -227,9 +227,16 @@ struct ProfScope {
     }
 };
 
+unsigned long long *g_gemm_clock = nullptr;     // device uint64[4] or null: see mmtrain_profile_gemm_clock
+
 hipError_t gemm(int dtype, const GemmArgs &g, hipStream_t st) {
     ProfScope ps(g.layout, st);                    // MMTRAIN_PROF_GEMM_NT / _NN / _TN
-    if (dtype == DT_BF16 && gemm_mfma_supported(g)) return gemm_mfma(g, st);
+    if (dtype == DT_BF16 && gemm_mfma_supported(g)) {
+        if (!g_gemm_clock) return gemm_mfma(g, st);
+        GemmArgs probed = g;
+        probed.clock_probe = g_gemm_clock;
+        return gemm_mfma(probed, st);
+    }
     return gemm_simple(dtype, g, st);
 }
 
@@ -505,6 +512,8 @@ int mmtrain_stack_bwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mm
 }
 
 // ---- profiling ---------------------------------------------------------------------
+
+void mmtrain_profile_gemm_clock(void *device_counters) { g_gemm_clock = (unsigned long long *)device_counters; }
 
 void mmtrain_profile_attn_busy(void *device_counters) { g_attn_busy = (unsigned long long *)device_counters; }
 

@@ -61,6 +61,7 @@ struct GemmP {
     // the partial product of chunk s of the launch's tile j is a dense 256 x 256 block at
     // C + (s * tile_count + j) * 65536 instead of a window of an M x N matrix.
     int tile_begin, tile_count, compact;
+    unsigned long long *clock_probe;       // see GemmArgs
 };
 
 // position t of the tile order -> tile coordinates: column-major inside groups of GROUP_M tile-rows
@@ -217,8 +218,8 @@ __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
 // A0 B0 .. B7 A1 .. A7, one per MFMA group, one slice ahead.  MFMA group g of a slice (row block g >> 1
 // of A against four of the B fragments) needs the fragments up to position need(g); LDS reads return in
 // order, so the group may proceed once at most this many LDS instructions are outstanding: the previous
-// slice's reads behind that position plus this slice's reads issued so far (groups 0..g).  The counter
-// holds 15 at most.
+// slice's reads behind that position plus this slice's reads issued so far (groups 0..g-1: a group's own
+// read follows its first MFMA).  The counter holds 15 at most.
 constexpr int frag_is_a(int f) { return f == 0 || f >= 9; }
 constexpr int frag_index(int f) { return f == 0 ? 0 : f <= 8 ? f - 1 : f - 8; }
 template <bool A_KC, bool B_KC>
@@ -227,7 +228,7 @@ constexpr int lgkm_allowed(int g) {
     const int need = g == 0 ? 4 : g == 1 ? 8 : 8 + (g >> 1);
     int n = 0;
     for (int f = need + 1; f < 16; ++f) n += frag_is_a(f) ? ca : cb;
-    for (int f = 0; f <= g; ++f) n += frag_is_a(f) ? ca : cb;
+    for (int f = 0; f < g; ++f) n += frag_is_a(f) ? ca : cb;
     return n < 15 ? n : 15;
 }
 template <int N>
@@ -257,6 +258,10 @@ void gemm_mfma_kernel(const GemmP p) {
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
+    if (p.clock_probe && blockIdx.x == 0 && threadIdx.x == 0) {
+        p.clock_probe[0] = (unsigned long long)clock64();
+        p.clock_probe[1] = (unsigned long long)wall_clock64();
+    }
 
     // ---- persistent workgroup -> tiles.  Workgroup b runs on XCD b % 8 (round-robin dispatch); XCD x
     // owns a contiguous run of the tile order, and its workgroups stride through that run together.
@@ -350,11 +355,9 @@ void gemm_mfma_kernel(const GemmP p) {
     // the 64 four-register accumulators are shuffled between registers in every iteration.  An
     // accumulator is touched again only 64 MFMAs later, and the code after the K loop starts with waits
     // and a barrier, so none of the software-managed MFMA hazards can occur.
-    auto mfma_group = [&](int buf, int g) {
+    auto mfma = [&](int buf, int g, int t) {
         const int i = g >> 1, j = 4 * (g & 1);
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j + t]) : "v"(fb[buf][j + t]), "v"(fa[buf][i]));
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j + t]) : "v"(fb[buf][j + t]), "v"(fa[buf][i]));
     };
 
     // Software pipeline, one barrier per 64-deep K step.  The operand tiles A0 B0 A1 B1 A2 B2 ... go round
@@ -390,10 +393,17 @@ void gemm_mfma_kernel(const GemmP p) {
         // first slice: fragments of the second slice; A(kt+2) into the slot B(kt-1) had
         static_for(Groups16{}, [&](auto G) {
             constexpr int g = decltype(G)::value;
-            read_frag(S1{}, G, o0, o1, 1);
-            if (!(g & 1)) la.template copy_one<FAST>(smem + o4, k2, g >> 1);
             wait_group(G, 0);
-            mfma_group(0, g);
+            mfma(0, g, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frag(S1{}, G, o0, o1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(0, g, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (!(g & 1)) la.template copy_one<FAST>(smem + o4, k2, g >> 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(0, g, 2);
+            mfma(0, g, 3);
             __builtin_amdgcn_sched_barrier(0);
         });
         asm volatile("s_waitcnt vmcnt(8)" ::: "memory");       // A(kt+1) and B(kt+1) have landed
@@ -402,14 +412,21 @@ void gemm_mfma_kernel(const GemmP p) {
         // The barrier has waited for every LDS read, so this slice's MFMAs need no wait of their own.
         static_for(Groups16{}, [&](auto G) {
             constexpr int g = decltype(G)::value;
-            read_frag(S0{}, G, o2, o3, 0);
-            if (!(g & 1)) lb.template copy_one<FAST>(smem + o0, k2, g >> 1);
             if (ASM_READS && g == 0)       // ties the MFMAs below to this side of the barrier
                 asm volatile("" : "+v"(fa[1][0]), "+v"(fa[1][1]), "+v"(fa[1][2]), "+v"(fa[1][3]),
                                   "+v"(fa[1][4]), "+v"(fa[1][5]), "+v"(fa[1][6]), "+v"(fa[1][7]),
                                   "+v"(fb[1][0]), "+v"(fb[1][1]), "+v"(fb[1][2]), "+v"(fb[1][3]),
                                   "+v"(fb[1][4]), "+v"(fb[1][5]), "+v"(fb[1][6]), "+v"(fb[1][7]));
-            mfma_group(1, g);
+            mfma(1, g, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frag(S0{}, G, o2, o3, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(1, g, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (!(g & 1)) lb.template copy_one<FAST>(smem + o0, k2, g >> 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(1, g, 2);
+            mfma(1, g, 3);
             __builtin_amdgcn_sched_barrier(0);
         });
         { const int t0 = o0, t1 = o1; o0 = o2; o1 = o3; o2 = o4; o3 = t0; o4 = t1; }
@@ -520,6 +537,10 @@ void gemm_mfma_kernel(const GemmP p) {
     }
     lds_barrier();      // staging area is free again: the next tile's first stage may overwrite it
     }   // tiles of this workgroup
+    if (p.clock_probe && blockIdx.x == 0 && threadIdx.x == 0) {
+        p.clock_probe[2] = (unsigned long long)clock64();
+        p.clock_probe[3] = (unsigned long long)wall_clock64();
+    }
 }
 
 // compute units of the current device, rounded down to whole XCD octets (one persistent workgroup each)
@@ -613,6 +634,7 @@ GemmP params(const GemmArgs &g) {
     p.tiles_n = ceil_div(g.N, BN);
     p.splits = 1; p.k_chunk = g.K; p.split_stride = 0;
     p.tile_begin = 0; p.tile_count = p.tiles_m * p.tiles_n; p.compact = 0;
+    p.clock_probe = g.clock_probe;
     return p;
 }
 

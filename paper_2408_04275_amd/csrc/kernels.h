@@ -22,6 +22,9 @@ struct GemmArgs {
     // optional scratch for split-K (TN on the matrix cores only): fp32 partial products, 256-byte aligned
     void *split_ws = nullptr;
     size_t split_ws_bytes = 0;
+    // measurement aid (matrix-core kernel only): when not null, device uint64[4]; the first workgroup stores the
+    // shader-clock counter and the constant 100 MHz counter at its start ([0], [1]) and at its end ([2], [3])
+    unsigned long long *clock_probe = nullptr;
 };
 
 // gemm_simple.hip: any dtype, any shape, LDS-tiled FMA kernel (the fp32 path).

@@ -21,7 +21,7 @@ def header_symbols():
 def test_library_exports_every_declared_symbol():
     lib = mm.load_library()
     names = header_symbols()
-    assert len(names) == 21 and set(names) == set(mm.EXPORTS)
+    assert len(names) == 22 and set(names) == set(mm.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
 
