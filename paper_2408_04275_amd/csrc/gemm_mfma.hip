@@ -84,6 +84,16 @@ typedef __attribute__((ext_vector_type(4))) uint32_t rawx4;
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, size_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)(uint32_t)bytes, 0x00020000);
 }
+// the descriptor make_rsrc builds, as four scalar words
+__device__ __forceinline__ rawx4 raw_rsrc(const void *p, size_t bytes) {
+    const uint64_t a = (uint64_t)p;
+    rawx4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    r[1] = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
+    r[2] = __builtin_amdgcn_readfirstlane((uint32_t)bytes);
+    r[3] = 0x00020000u;
+    return r;
+}
 __device__ __forceinline__ uint4 buf_load(__amdgpu_buffer_rsrc_t r, uint32_t off) {
     const rawx4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
     return make_uint4(v[0], v[1], v[2], v[3]);
@@ -96,7 +106,11 @@ __device__ __forceinline__ uint4 buf_load(__amdgpu_buffer_rsrc_t r, uint32_t off
 // (l & 7) ^ swz(r0 + (l >> 3)).  Wavefront w copies rows 32 i + 8 w .. + 7 for i = 0..7.
 typedef __attribute__((address_space(3))) void lds_void;
 struct LoaderKC {
+    static constexpr int ITEM_LDS = 32 * 128;      // LDS bytes between consecutive items
     __amdgpu_buffer_rsrc_t rs;
+    rawx4 rsv;                    // the same descriptor as four words, for the copies written as assembly
+    uint32_t vo8[8];              // fast path: this lane's byte offset for item i, without k0
+    __device__ __forceinline__ uint32_t step_soff(int k0) const { return (uint32_t)k0 * 2u; }
     uint32_t off0, row_step;      // byte offset of this lane's row at i = 0 (without the unit); bytes per 32 rows
     uint32_t vo_e, vo_o;          // fast path: this lane's byte offset for even / odd i, without k0 and i * row_step
     int kc0, K, slab0;            // unit column (elements) for even i (odd i: kc0 ^ 32); first slab's LDS offset
@@ -112,6 +126,10 @@ struct LoaderKC {
         vo_o = off0 + (uint32_t)(kc0 ^ 32) * 2u;
         full = row0 + BM <= nrows;
         slab0 = __builtin_amdgcn_readfirstlane(w * 8 * 128);
+        // one register per item, kept there (recomputed inside the K loop they would cost a vector add per copy)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { vo8[i] = ((i & 1) ? vo_o : vo_e) + (uint32_t)i * row_step; asm volatile("" : "+v"(vo8[i])); }
+        rsv = raw_rsrc(X, ((size_t)(nrows - 1) * ld + K_) * 2);
     }
     // item i of 8 of the tile at k0: rows 32 i + 8 w .. + 7 -> LDS.  FAST: the caller guarantees that the
     // tile lies inside the matrix (all rows, k0 + 64 <= K); then the per-lane offset is a constant and the
@@ -147,7 +165,11 @@ typedef __attribute__((ext_vector_type(4))) short shortx4;
 typedef __attribute__((ext_vector_type(8))) short shortx8;
 typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
 struct LoaderKS {
+    static constexpr int ITEM_LDS = 1024;
     __amdgpu_buffer_rsrc_t rs;
+    rawx4 rsv;
+    uint32_t vo8[8];
+    __device__ __forceinline__ uint32_t step_soff(int k0) const { return (uint32_t)k0 * k_step; }
     uint32_t off_e, off_o, k_step;   // byte offset of this lane's 16 bytes for even / odd i (k0 = 0, i = 0 or 1); bytes per k
     int slab0;
     bool full;                       // all 256 rows of the tile exist
@@ -162,6 +184,9 @@ struct LoaderKS {
         off_o = row0 + n_o < nrows ? (uint32_t)(((size_t)(w * 16 + 2 + kh) * ld + row0 + n_o) * 2) : OOB;
         full = row0 + BM <= nrows;
         slab0 = __builtin_amdgcn_readfirstlane(w * 8 * 1024);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { vo8[i] = ((i & 1) ? off_o : off_e) + (uint32_t)(2 * (i & ~1)) * k_step; asm volatile("" : "+v"(vo8[i])); }
+        rsv = raw_rsrc(X, ((size_t)(K_ - 1) * ld + nrows) * 2);
     }
     // FAST: as for the K-contiguous loader (all rows exist, k0 + 64 <= K).
     template <bool FAST>
@@ -246,6 +271,18 @@ __device__ __forceinline__ void wait_frags(bf16x8 &a) {
 template <int... I, class F>
 __device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F &&f) {
     (f(std::integral_constant<int, I>{}), ...);
+}
+
+// One MFMA with the copy of one item of an operand tile behind it, as one statement: M0 (the LDS destination) is written in
+// front of the MFMA, which also is the wait state the copy needs after that write, and the copy's scalar offset is the same for
+// all items of a step (the builtin form costs a scalar add for the offset, one for M0 and a no-op per copy).
+template <int MOFF>
+__device__ __forceinline__ void mfma_copy(f32x4 &acc, const bf16x8 &b, const bf16x8 &a, uint32_t mbase, uint32_t vo, const rawx4 &rsv,
+                                          uint32_t so) {
+    asm volatile("s_add_u32 m0, %[mb], %[moff]\n\tv_mfma_f32_16x16x32_bf16 %[acc], %[b], %[a], %[acc]\n\t"
+                 "buffer_load_dwordx4 %[vo], %[rs], %[so] offen lds"
+                 : [acc] "+a"(acc) : [b] "v"(b), [a] "v"(a), [mb] "s"(mbase), [moff] "n"(MOFF), [vo] "v"(vo), [rs] "s"(rsv), [so] "s"(so)
+                 : "memory", "m0", "scc");
 }
 
 template <bool KC> struct LoaderSel { typedef LoaderKC type; };
@@ -390,6 +427,11 @@ void gemm_mfma_kernel(const GemmP p) {
     auto step = [&](auto FAST_, int kt) {
         constexpr bool FAST = decltype(FAST_)::value;
         const int k2 = (kt + 2) * BK;
+        typedef std::remove_reference_t<decltype(la)> LA;
+        typedef std::remove_reference_t<decltype(lb)> LB;
+        // fast path: scalar offsets and LDS destinations of this step's copies
+        const uint32_t so_a = __builtin_amdgcn_readfirstlane(la.step_soff(k2)), so_b = __builtin_amdgcn_readfirstlane(lb.step_soff(k2));
+        const uint32_t mb_a = __builtin_amdgcn_readfirstlane(lds0 + o4 + la.slab0), mb_b = __builtin_amdgcn_readfirstlane(lds0 + o0 + lb.slab0);
         // first slice: fragments of the second slice; A(kt+2) into the slot B(kt-1) had
         static_for(Groups16{}, [&](auto G) {
             constexpr int g = decltype(G)::value;
@@ -398,9 +440,11 @@ void gemm_mfma_kernel(const GemmP p) {
             __builtin_amdgcn_sched_barrier(0);
             read_frag(S1{}, G, o0, o1, 1);
             __builtin_amdgcn_sched_barrier(0);
-            mfma(0, g, 1);
+            if (FAST && !(g & 1))
+                mfma_copy<(g >> 1) * LA::ITEM_LDS>(acc[g >> 1][4 * (g & 1) + 1], fb[0][4 * (g & 1) + 1], fa[0][g >> 1], mb_a, la.vo8[g >> 1], la.rsv, so_a);
+            else mfma(0, g, 1);
             __builtin_amdgcn_sched_barrier(0);
-            if (!(g & 1)) la.template copy_one<FAST>(smem + o4, k2, g >> 1);
+            if (!FAST && !(g & 1)) la.template copy_one<false>(smem + o4, k2, g >> 1);
             __builtin_amdgcn_sched_barrier(0);
             mfma(0, g, 2);
             mfma(0, g, 3);
@@ -421,9 +465,11 @@ void gemm_mfma_kernel(const GemmP p) {
             __builtin_amdgcn_sched_barrier(0);
             read_frag(S0{}, G, o2, o3, 0);
             __builtin_amdgcn_sched_barrier(0);
-            mfma(1, g, 1);
+            if (FAST && !(g & 1))
+                mfma_copy<(g >> 1) * LB::ITEM_LDS>(acc[g >> 1][4 * (g & 1) + 1], fb[1][4 * (g & 1) + 1], fa[1][g >> 1], mb_b, lb.vo8[g >> 1], lb.rsv, so_b);
+            else mfma(1, g, 1);
             __builtin_amdgcn_sched_barrier(0);
-            if (!(g & 1)) lb.template copy_one<FAST>(smem + o0, k2, g >> 1);
+            if (!FAST && !(g & 1)) lb.template copy_one<false>(smem + o0, k2, g >> 1);
             __builtin_amdgcn_sched_barrier(0);
             mfma(1, g, 2);
             mfma(1, g, 3);
