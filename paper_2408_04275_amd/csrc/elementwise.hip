@@ -31,6 +31,25 @@ __device__ __forceinline__ void store8(bf16_t *p, const float (&v)[8]) {
     *reinterpret_cast<uint4 *>(p) = a;
 }
 
+// Streaming forms for tensors that a kernel passes over once and that are far larger than the caches.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+__device__ __forceinline__ void load8_stream(const bf16_t *p, float (&v)[8]) {
+    const u32x4_t a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(a[i] << 16);
+        v[2 * i + 1] = __uint_as_float(a[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void load8_stream(const float *p, float (&v)[8]) { load8(p, v); }
+__device__ __forceinline__ void store8_stream(bf16_t *p, const float (&v)[8]) {
+    u32x4_t a;
+    a[0] = pack_bf16x2(v[0], v[1]); a[1] = pack_bf16x2(v[2], v[3]);
+    a[2] = pack_bf16x2(v[4], v[5]); a[3] = pack_bf16x2(v[6], v[7]);
+    __builtin_nontemporal_store(a, reinterpret_cast<u32x4_t *>(p));
+}
+__device__ __forceinline__ void store8_stream(float *p, const float (&v)[8]) { store8(p, v); }
+
 // ---- token bookkeeping ---------------------------------------------------------------
 // tok_seg[t] = s with cu[s] <= t < cu[s+1].
 __device__ __forceinline__ int find_segment(const int *__restrict__ cu, int S, int t) {
@@ -430,11 +449,11 @@ __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T *__restrict__ g
     const long t = idx / cpr;
     const int c = (int)(idx % cpr) * 8;
     float g[8], u[8];
-    load8(gu + t * 2 * F + c, g);
-    load8(gu + t * 2 * F + F + c, u);
+    load8_stream(gu + t * 2 * F + c, g);
+    load8_stream(gu + t * 2 * F + F + c, u);
 #pragma unroll
     for (int j = 0; j < 8; ++j) g[j] = g[j] / (1.f + expf(-g[j])) * u[j];
-    store8(m + t * F + c, g);
+    store8_stream(m + t * F + c, g);
 }
 
 // d_gate = d_m * up * s * (1 + gate * (1 - s)),  d_up = d_m * gate * s,  s = sigmoid(gate).
@@ -447,9 +466,9 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T *__restrict__ d
     const long t = idx / cpr;
     const int c = (int)(idx % cpr) * 8;
     float g[8], u[8], dm[8];
-    load8(gu + t * 2 * F + c, g);
-    load8(gu + t * 2 * F + F + c, u);
-    load8(d_m + t * F + c, dm);
+    load8_stream(gu + t * 2 * F + c, g);
+    load8_stream(gu + t * 2 * F + F + c, u);
+    load8_stream(d_m + t * F + c, dm);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const float s = 1.f / (1.f + expf(-g[j]));
@@ -457,8 +476,8 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T *__restrict__ d
         u[j] = dm[j] * g[j] * s;
         g[j] = dg;
     }
-    store8(d_gu + t * 2 * F + c, g);
-    store8(d_gu + t * 2 * F + F + c, u);
+    store8_stream(d_gu + t * 2 * F + c, g);
+    store8_stream(d_gu + t * 2 * F + F + c, u);
 }
 
 hipError_t swiglu_fwd(int dtype, const void *gu, void *m, int T, int F, hipStream_t st) {
