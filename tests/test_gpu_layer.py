@@ -98,6 +98,22 @@ def test_accumulate_and_frozen():
     compare_layer(shape, (gy3, gdx3, gG3), (y, dx, {k: G[k] for k in ("w_fc1", "w_fc2")}), "partial ")
 
 
+@pytest.mark.parametrize("names", [["b_o"], ["b_fc2", "norm2_w"], ["b_fc1"], ["b_qkv", "norm1_b"], ["norm2_b", "b_o", "b_fc2"]])
+def test_encoder_partially_frozen(names):
+    # the encoder's bias gradients are summed inside kernels that also serve other gradients: every subset must still
+    # give the requested ones, bit-identical to the run that requests them all, and the same input gradient
+    shape = wl.LayerShape("enc-frozen", wl.ENCODER, wl.BF16, 272, 4, 4, 64, 528, 648)
+    W = wl.make_weights(shape, 9, std=0.05)
+    x, dy = wl.make_activations(shape, 648, 9)
+    modes = np.ones(7, dtype=np.uint8)
+    y, dx, G = gpu_run(shape, RAGGED_CU, modes, W, x, dy)
+    y2, dx2, G2 = gpu_run(shape, RAGGED_CU, modes, W, x, dy, grad_names=names)
+    assert sorted(G2) == sorted(names)
+    assert np.array_equal(y, y2) and np.array_equal(dx, dx2)
+    for k in names:
+        assert np.array_equal(G[k], G2[k]), k
+
+
 def test_segment_order_invariance_on_gpu():
     # Section 5.2: reordering subsequences permutes outputs block-wise; summed weight gradients agree to rounding
     shape = wl.LayerShape("perm", wl.DECODER, wl.BF16, 256, 4, 2, 64, 512, 648)
