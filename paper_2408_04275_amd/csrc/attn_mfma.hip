@@ -19,8 +19,8 @@
 // running max / sum / log-sum-exp / D are per-lane scalars, and P^T (or dS^T) is already laid
 // out as the column operand of the next MFMA: O^T = V^T . P^T, dQ^T = K^T . dS^T.  The row
 // operand of those products is the K or V tile transposed ([feature][key]), its keys in the order in
-// which the accumulator registers hold them: the forward kernel transposes V in registers on its way to
-// LDS, the backward kernels form the transposed fragments with the transposing LDS read.
+// which the accumulator registers hold them: all kernels keep the tiles row-major in LDS, as they are copied, and form
+// the transposed fragments with the transposing LDS read.
 //
 // The backward pass is two kernels: dQ (same roles as forward; also writes D = rowsum(dO * O)),
 // then dK/dV with one KEY per lane, looping over the query tiles that can see the workgroup's
@@ -103,15 +103,9 @@ __device__ __forceinline__ RowInfo key_range(const int2 *info, int k, int T) {
 }
 
 // ------------------------------------------------------------------------------------------
-// forward
+// shared pieces
 // ------------------------------------------------------------------------------------------
-// 512 threads: 8 wavefronts x 32 queries = 256 queries per workgroup (two wavefronts per SIMD, so that
-// one can run its softmax on the vector ALUs while the other occupies the matrix core), walking the
-// keys 64 at a time through two LDS slots of {K tile [64][D], V^T tile [D][64]}.  K goes global -> LDS
-// directly (buffer_load ... lds, issued by wavefronts 4..7); V is fetched into registers by wavefronts
-// 0..3, transposed there and written one step later.  One barrier per step: after it every wavefront has
-// finished the previous step, so the slot that step used may be refilled.
-constexpr int FQ = 256, FT = 64;
+constexpr int FQ = 256;         // queries per workgroup of the forward and dQ kernels (8 wavefronts x 32)
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((ext_vector_type(4))) uint32_t rawx4;
@@ -127,190 +121,6 @@ template <int D>
 __device__ __forceinline__ bf16x8 frag_k(const uint8_t *tile, int row, int ks, int half) {
     constexpr int UPR = D / 8;
     return *reinterpret_cast<const bf16x8 *>(tile + (row * UPR + ((ks * 2 + half) ^ swz(row))) * 16);
-}
-// fragment of a transposed [D][64] tile: feature row c, unit u (0..7)
-__device__ __forceinline__ bf16x8 frag_vt(const uint8_t *tile, int c, int u) {
-    return *reinterpret_cast<const bf16x8 *>(tile + (c * 8 + (u ^ swz(c))) * 16);
-}
-
-template <int D>
-__global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
-    constexpr int KS = D / 16, CB = D / 32, UPR = D / 8;
-    constexpr int K_BYTES = FT * D * 2, SLOT = 2 * K_BYTES;          // K tile, then V^T tile
-    constexpr int ROWS_PER_COPY = 1024 / (2 * D);                   // tile rows filled by one 1 KiB copy
-    constexpr int COPIES = FT / ROWS_PER_COPY / 4;                  // per copying wavefront (4 of them)
-    constexpr int V_TASKS = 8 * UPR * 2;                            // (unit, 8-feature block, half of the unit's keys)
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    add_busy(a.cu_busy, false);
-
-    // grid: x = head, y = position in the dispatch order of the query tiles (heaviest first)
-    const int head = blockIdx.x, g = head / (a.nh / a.nkv);
-    const int q0 = (a.use_order ? a.order_q[blockIdx.y] : blockIdx.y) * FQ;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
-    const int T = a.T;
-    const bf16_t *qkv = (const bf16_t *)a.qkv;
-    const long ld = a.ld_qkv;
-    const int dh = a.d;                                 // head dimension in memory (<= D: LDS tiles and fragments are zero-padded to D)
-    const int nq = a.nh * dh, nk = a.nkv * dh;
-
-    const int q = q0 + wave * 32 + l32;
-    const RowInfo me = query_range(a.tok_info, q, T);
-    const bool valid = q < T;
-    const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
-    const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
-    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
-    const int kbeg = first.lo, kend = last.hi;
-
-    bf16x8 qf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (valid && ks * 16 + half * 8 < dh) v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * dh + ks * 16 + half * 8);
-        qf[ks] = *reinterpret_cast<bf16x8 *>(&v);
-    }
-    f32x16 oacc[CB];
-#pragma unroll
-    for (int c = 0; c < CB; ++c) oacc[c] = zero16();
-    float m_run = -INFINITY, l_run = 0.f;
-    const float sl2 = a.scale * LOG2E;
-
-    // ---- feeding roles
-    const __amdgpu_buffer_rsrc_t rs =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
-    // K copies (wavefronts 4..7): copy i of this wavefront fills tile rows r0 .. r0 + ROWS_PER_COPY - 1
-    const int cw = wave - 4;
-    const int k_lrow = lane / UPR, k_pos = lane % UPR;              // row within the copy, unit position in the row
-    auto copy_k = [&](uint8_t *slot, int kt) {
-#pragma unroll
-        for (int i = 0; i < COPIES; ++i) {
-            const int r0 = (cw * COPIES + i) * ROWS_PER_COPY, row = r0 + k_lrow;
-            const int unit = (k_pos & ~7) | ((k_pos & 7) ^ swz(row));
-            const uint32_t off = unit * 8 < dh ? (uint32_t)(((size_t)(kt + row) * ld + nq + g * dh + unit * 8) * 2) : 0xfffffff0u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(slot + r0 * 2 * D), 16, (int)off, 0, 0, 0);
-        }
-    };
-    // V tasks (threads < V_TASKS): unit u of 8 keys, 8-feature block cb, keys kk = 4 part .. 4 part + 3 of the unit.
-    // Unit u = (block b, mfma m, lane half hh) of the 64-key tile holds keys 32 b + 16 m + 8 (kk >> 2) + 4 hh + (kk & 3).
-    const bool v_thread = threadIdx.x < V_TASKS;
-    const int v_cb = threadIdx.x % UPR, v_u = (threadIdx.x / UPR) & 7, v_part = threadIdx.x / (UPR * 8);
-    uint4 vr[4];
-    auto load_v = [&](int kt) {
-        if (!v_thread) return;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (v_cb * 8 >= dh) { vr[j] = make_uint4(0, 0, 0, 0); continue; }
-            const int key = kt + 32 * (v_u >> 2) + 16 * ((v_u >> 1) & 1) + 8 * v_part + 4 * (v_u & 1) + j;
-            const uint32_t off = (uint32_t)(((size_t)key * ld + nq + nk + g * dh + v_cb * 8) * 2);
-            const rawx4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
-            vr[j] = make_uint4(v[0], v[1], v[2], v[3]);
-        }
-    };
-    auto store_v = [&](uint8_t *vt) {
-        if (!v_thread) return;
-        const uint32_t *w = reinterpret_cast<const uint32_t *>(vr);   // w[j * 4 + e]: features 2e, 2e+1 of key j
-#pragma unroll
-        for (int rr = 0; rr < 8; ++rr) {
-            const uint32_t sel = (rr & 1) ? 0x07060302u : 0x05040100u;
-            uint2 o;
-            o.x = __builtin_amdgcn_perm(w[1 * 4 + (rr >> 1)], w[0 * 4 + (rr >> 1)], sel);
-            o.y = __builtin_amdgcn_perm(w[3 * 4 + (rr >> 1)], w[2 * 4 + (rr >> 1)], sel);
-            const int c = v_cb * 8 + rr;
-            *reinterpret_cast<uint2 *>(vt + (c * 8 + (v_u ^ swz(c))) * 16 + v_part * 8) = o;
-        }
-    };
-
-    // ---- prologue: tile 0
-    if (wave >= 4) copy_k(smem, kbeg);
-    load_v(kbeg);
-
-    int slot = 0;
-    for (int kt = kbeg; kt < kend; kt += FT, slot ^= 1) {
-        uint8_t *sK = smem + slot * SLOT, *sVT = sK + K_BYTES;
-        store_v(sVT);                                                // V^T of this step (slot last read two steps ago)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // this step's K copy has landed
-        lds_barrier();                                               // ... and everyone is done with the other slot
-        if (kt + FT < kend) {
-            if (wave >= 4) copy_k(smem + (slot ^ 1) * SLOT, kt + FT);
-            load_v(kt + FT);
-        }
-        // which 32-key blocks can any query of this wavefront see?
-        bool act[2];
-#pragma unroll
-        for (int b = 0; b < 2; ++b) act[b] = (kt + 32 * b < w_hi_max) && (kt + 32 * b + 32 > w_lo_min);
-        if (!(act[0] || act[1])) continue;
-        f32x16 s[2];
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            s[b] = zero16();
-            if (act[b]) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) s[b] = MFMA(frag_k<D>(sK, 32 * b + l32, ks, half), qf[ks], s[b]);
-            }
-        }
-        // online softmax on the raw scores (the scale is folded into the exponent);
-        // register i of block b  <->  key kt + 32 b + 8 (i >> 2) + 4 half + (i & 3)
-        float mx = m_run;
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            if (!act[b]) continue;
-            const int kb = kt + 32 * b;
-            if (!(kb >= w_lo_max && kb + 32 <= w_hi_min)) {            // some lane needs masking
-                const unsigned span = (unsigned)(me.hi - me.lo);
-                const int rel = kb + 4 * half - me.lo;
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    s[b][i] = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? s[b][i] : -INFINITY;
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[b][i]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_use = mx == -INFINITY ? 0.f : mx;
-        if (__builtin_amdgcn_ballot_w64(mx != m_run) != 0) {           // some lane's maximum moved
-            const float corr = __builtin_amdgcn_exp2f((m_run - m_use) * sl2);
-            l_run *= corr;
-#pragma unroll
-            for (int c = 0; c < CB; ++c)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[c][i] *= corr;
-        }
-        m_run = mx;
-        const float msc = m_use * sl2;
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            if (!act[b]) continue;
-            float p[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                p[i] = __builtin_amdgcn_exp2f(fmaf(s[b][i], sl2, -msc));
-                l_run += p[i];
-            }
-#pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                const bf16x8 pf = pack8(p + 8 * m);
-                const int u = b * 4 + m * 2 + half;
-#pragma unroll
-                for (int c = 0; c < CB; ++c) oacc[c] = MFMA(frag_vt(sVT, 32 * c + l32, u), pf, oacc[c]);
-            }
-        }
-    }
-
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    if (valid) {
-        const float inv = 1.f / l_tot;
-        bf16_t *o = (bf16_t *)a.o + (long)q * nq + head * dh;
-#pragma unroll
-        for (int c = 0; c < CB; ++c)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                uint2 w;
-                w.x = pack_bf16x2(oacc[c][4 * gq] * inv, oacc[c][4 * gq + 1] * inv);
-                w.y = pack_bf16x2(oacc[c][4 * gq + 2] * inv, oacc[c][4 * gq + 3] * inv);
-                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(o + 32 * c + 8 * gq + 4 * half) = w;
-            }
-        if (half == 0) a.lse[(long)head * T + q] = (m_run * sl2 + __builtin_amdgcn_logf(l_tot)) * LN2;
-    }
-    add_busy(a.cu_busy, true);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -537,6 +347,165 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// forward.  512 threads: 8 wavefronts x 32 queries = 256 queries per workgroup (two wavefronts per SIMD, so that one can
+// run its softmax on the vector ALUs while the other occupies the matrix core), walking the keys 64 at a time through
+// two LDS slots of {K tile, V tile}, both copied global -> LDS directly in their memory order (wavefronts 4..7 copy K,
+// 0..3 copy V).  O^T = V^T . P^T takes V^T from the row-major tile by the transposing LDS read, the same scheme as
+// dQ^T = K^T . dS^T above.  One barrier per step: after it every wavefront has finished the previous step, so the slot
+// that step used may be refilled.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
+    constexpr int KS = D / 16, CB = D / 32;
+    constexpr int TILE = BT2 * D * 2, SLOT = 2 * TILE;             // K tile, then V tile
+    constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                 // per wavefront (4 wavefronts per tile)
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    add_busy(a.cu_busy, false);
+
+    const int head = blockIdx.x, g = head / (a.nh / a.nkv);
+    const int q0 = (a.use_order ? a.order_q[blockIdx.y] : blockIdx.y) * FQ;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
+    const int T = a.T;
+    const bf16_t *qkv = (const bf16_t *)a.qkv;
+    const long ld = a.ld_qkv;
+    const int dh = a.d;
+    const int nq = a.nh * dh, nk = a.nkv * dh;
+
+    const int q = q0 + wave * 32 + l32;
+    const RowInfo me = query_range(a.tok_info, q, T);
+    const bool valid = q < T;
+    const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
+    const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
+    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
+    const int kbeg = first.lo, kend = last.hi;
+
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (valid && ks * 16 + half * 8 < dh) v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * dh + ks * 16 + half * 8);
+        qf[ks] = *reinterpret_cast<bf16x8 *>(&v);
+    }
+    f32x16 oacc[CB];
+#pragma unroll
+    for (int c = 0; c < CB; ++c) oacc[c] = zero16();
+    float m_run = -INFINITY, l_run = 0.f;
+    const float sl2 = a.scale * LOG2E;
+
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
+    // wavefronts 4..7 copy the K tile, wavefronts 0..3 the V tile
+    auto copy_kv = [&](uint8_t *slot, int kt) {
+        if (wave >= 4) copy_rows<D, COPIES>(rs, slot, (wave - 4) * COPIES, kt, ld, nq + g * dh, dh);
+        else copy_rows<D, COPIES>(rs, slot + TILE, wave * COPIES, kt, ld, nq + nk + g * dh, dh);
+    };
+    TrReader<D> tr;
+    tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
+
+    copy_kv(smem, kbeg);
+    int slot = 0;
+    for (int kt = kbeg; kt < kend; kt += BT2, slot ^= 1) {
+        const uint8_t *sK = smem + slot * SLOT;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // this step's tiles have landed
+        lds_barrier();                                               // ... and everyone is done with the other slot
+        if (kt + BT2 < kend) copy_kv(smem + (slot ^ 1) * SLOT, kt + BT2);
+        bool act[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) act[b] = (kt + 32 * b < w_hi_max) && (kt + 32 * b + 32 > w_lo_min);
+        if (!(act[0] || act[1])) continue;
+        f32x16 s[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            s[b] = zero16();
+            if (act[b]) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) s[b] = MFMA(frag_k<D>(sK, 32 * b + l32, ks, half), qf[ks], s[b]);
+            }
+        }
+        // online softmax on the raw scores (the scale is folded into the exponent);
+        // register i of block b  <->  key kt + 32 b + 8 (i >> 2) + 4 half + (i & 3)
+        float mx = m_run;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            if (!act[b]) continue;
+            const int kb = kt + 32 * b;
+            if (!(kb >= w_lo_max && kb + 32 <= w_hi_min)) {            // some lane needs masking
+                const unsigned span = (unsigned)(me.hi - me.lo);
+                const int rel = kb + 4 * half - me.lo;
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    s[b][i] = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? s[b][i] : -INFINITY;
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[b][i]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_use = mx == -INFINITY ? 0.f : mx;
+        if (__builtin_amdgcn_ballot_w64(mx != m_run) != 0) {           // some lane's maximum moved
+            const float corr = __builtin_amdgcn_exp2f((m_run - m_use) * sl2);
+            l_run *= corr;
+#pragma unroll
+            for (int c = 0; c < CB; ++c)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[c][i] *= corr;
+        }
+        m_run = mx;
+        const float msc = m_use * sl2;
+        const uint32_t tv = slot * SLOT + TILE;
+        auto block = [&](auto B_) {
+            constexpr int b = decltype(B_)::value;
+            if (!act[b]) return;
+            // V^T fragments of this block: [MFMA m][feature block c], two halves each; in flight during the exponentials
+            shortx4 t0[4], t1[4], t2[4], t3[4];
+            t0[0] = tr.template read<b, 0, 0, 0>(tv); t1[0] = tr.template read<b, 0, 0, 1>(tv);
+            t2[0] = tr.template read<b, 1, 0, 0>(tv); t3[0] = tr.template read<b, 1, 0, 1>(tv);
+            t0[1] = tr.template read<b, 0, 1, 0>(tv); t1[1] = tr.template read<b, 0, 1, 1>(tv);
+            t2[1] = tr.template read<b, 1, 1, 0>(tv); t3[1] = tr.template read<b, 1, 1, 1>(tv);
+            if (CB > 2) {
+                t0[2] = tr.template read<b, 0, 2, 0>(tv); t1[2] = tr.template read<b, 0, 2, 1>(tv);
+                t2[2] = tr.template read<b, 1, 2, 0>(tv); t3[2] = tr.template read<b, 1, 2, 1>(tv);
+                t0[3] = tr.template read<b, 0, 3, 0>(tv); t1[3] = tr.template read<b, 0, 3, 1>(tv);
+                t2[3] = tr.template read<b, 1, 3, 0>(tv); t3[3] = tr.template read<b, 1, 3, 1>(tv);
+            } else {
+                t0[2] = t0[3] = t1[2] = t1[3] = t2[2] = t2[3] = t3[2] = t3[3] = shortx4{0, 0, 0, 0};
+            }
+            float p[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                p[i] = __builtin_amdgcn_exp2f(fmaf(s[b][i], sl2, -msc));
+                l_run += p[i];
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT4(t0), TR_WAIT4(t1), TR_WAIT4(t2), TR_WAIT4(t3));
+            const bf16x8 p0 = pack8(p), p1 = pack8(p + 8);
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                oacc[c] = MFMA(join(t0[c], t1[c]), p0, oacc[c]);
+                oacc[c] = MFMA(join(t2[c], t3[c]), p1, oacc[c]);
+            }
+        };
+        block(std::integral_constant<int, 0>{});
+        block(std::integral_constant<int, 1>{});
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (valid) {
+        const float inv = 1.f / l_tot;
+        bf16_t *o = (bf16_t *)a.o + (long)q * nq + head * dh;
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                uint2 w;
+                w.x = pack_bf16x2(oacc[c][4 * gq] * inv, oacc[c][4 * gq + 1] * inv);
+                w.y = pack_bf16x2(oacc[c][4 * gq + 2] * inv, oacc[c][4 * gq + 3] * inv);
+                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(o + 32 * c + 8 * gq + 4 * half) = w;
+            }
+        if (half == 0) a.lse[(long)head * T + q] = (m_run * sl2 + __builtin_amdgcn_logf(l_tot)) * LN2;
+    }
+    add_busy(a.cu_busy, true);
+}
+
+// ------------------------------------------------------------------------------------------
 // backward: dK, dV.  One key per lane (4 wavefronts x 32 keys); loop over the query heads of the group and
 // over the 64-query tiles that can see the workgroup's keys.
 // ------------------------------------------------------------------------------------------
@@ -724,7 +693,7 @@ hipError_t set_smem(K kern, int bytes) {
 template <int D>
 hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
-    const int smem = 2 * 2 * FT * D * 2;
+    const int smem = 2 * 2 * BT2 * D * 2;
     if (!configured) {
         hipError_t e = set_smem(attn_fwd_kernel<D>, smem);
         if (e != hipSuccess) return e;
