@@ -222,7 +222,8 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     // grid: x = head, y = position in the dispatch order of the query tiles (heaviest first)
     const int head = blockIdx.x, g = head / (a.nh / a.nkv);
     const int q0 = (a.use_order ? a.order_q[blockIdx.y] : blockIdx.y) * FQ;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
+    // the wavefront's index as a scalar: what is derived from it (copy destinations, buffer descriptors) stays uniform
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5, l32 = lane & 31;
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
     const long ld = a.ld_qkv;
@@ -364,7 +365,8 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
 
     const int head = blockIdx.x, g = head / (a.nh / a.nkv);
     const int q0 = (a.use_order ? a.order_q[blockIdx.y] : blockIdx.y) * FQ;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
+    // the wavefront's index as a scalar: what is derived from it (copy destinations, buffer descriptors) stays uniform
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5, l32 = lane & 31;
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
     const long ld = a.ld_qkv;
@@ -520,7 +522,8 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     // grid: x = key/value head, y = position in the dispatch order of the key tiles (heaviest first)
     const int g = blockIdx.x, group = a.nh / a.nkv;
     const int k0 = (a.use_order ? a.order_k[blockIdx.y] : blockIdx.y) * BQ;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
+    // the wavefront's index as a scalar: what is derived from it (copy destinations, buffer descriptors) stays uniform
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5, l32 = lane & 31;
     const int T = a.T;
     const bf16_t *qkv = (const bf16_t *)a.qkv;
     const bf16_t *dO = (const bf16_t *)a.d_o;
@@ -622,21 +625,27 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
             const bool inside = qb >= w_lo_max && qb + 32 <= w_hi_min;
             const unsigned span = (unsigned)(me.hi - me.lo);
             float p[16], ds[16];
+            // two copies of the loop, so that a block no key of which is masked pays nothing for the mask
+            auto softmax = [&](auto MASK_) {
+                constexpr bool MASK = decltype(MASK_)::value;
 #pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const int r0 = 32 * b + 8 * gq + 4 * half;            // 4 consecutive queries
-                const float4 l4 = *reinterpret_cast<const float4 *>(sLse + r0);
-                const float4 d4 = *reinterpret_cast<const float4 *>(sD + r0);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int r0 = 32 * b + 8 * gq + 4 * half;        // 4 consecutive queries
+                    const float4 l4 = *reinterpret_cast<const float4 *>(sLse + r0);
+                    const float4 d4 = *reinterpret_cast<const float4 *>(sD + r0);
+                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = 4 * gq + e;
-                    float pv = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lv[e] * LOG2E));
-                    if (!inside) pv = (unsigned)(qt + r0 + e - me.lo) < span ? pv : 0.f;
-                    p[i] = pv;
-                    ds[i] = pv * (dp[i] - dvv[e]);
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = 4 * gq + e;
+                        float pv = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lv[e] * LOG2E));
+                        if (MASK) pv = (unsigned)(qt + r0 + e - me.lo) < span ? pv : 0.f;
+                        p[i] = pv;
+                        ds[i] = pv * (dp[i] - dvv[e]);
+                    }
                 }
-            }
+            };
+            if (inside) softmax(std::false_type{});
+            else softmax(std::true_type{});
             asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT4(o0), TR_WAIT4(o1), TR_WAIT4(q0f), TR_WAIT4(q1f));
             bf16x8 fo[4], fq[4];
 #pragma unroll
