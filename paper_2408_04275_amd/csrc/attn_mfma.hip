@@ -71,6 +71,7 @@ __device__ __forceinline__ f32x16 zero16() {
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
+
 // Per-compute-unit busy time (measurement aid): a workgroup adds its run time, in ticks of the constant 100 MHz
 // counter, to the entry of the compute unit it ran on: minus the time at its start, plus the time at its end
 // (unsigned wrap-around), so that nothing has to be kept in a register in between.
@@ -178,6 +179,16 @@ struct TrReader {
         asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(off[X] + tile), "n"(IMM));
         return v;
     }
+    // the same with the tile's offset already added to the eight addresses (base) and a constant offset on top
+    template <int B, int M, int C, int SEC, int EXTRA>
+    static __device__ __forceinline__ shortx4 read_at(const uint32_t (&base)[8]) {
+        constexpr int CST = (4 * B + 2 * M + SEC) & 7, X = (4 * (C & 1)) ^ CST;
+        constexpr int IMM = (32 * B + 16 * M + 8 * SEC) * 2 * D + (C >> 1) * 128 + EXTRA;
+        static_assert(IMM < 65536, "LDS offset field");
+        shortx4 v;
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(base[X]), "n"(IMM));
+        return v;
+    }
 };
 __device__ __forceinline__ bf16x8 join(shortx4 lo, shortx4 hi) {
     const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -186,6 +197,51 @@ __device__ __forceinline__ bf16x8 join(shortx4 lo, shortx4 hi) {
 // The transposing reads are written as assembly because the compiler makes the builtin wait for every
 // direct-to-LDS copy in flight; their results may be used only after this wait, which names them.
 #define TR_WAIT4(x) "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])
+#define TR_WAIT2(x) "+v"(x[0]), "+v"(x[1])
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+
+// LDS reads of the dK/dV kernel's pipelined section, written as assembly together with their waits: the section
+// mixes them with the transposing reads, which the compiler's counting of outstanding LDS operations does not see
+// (its waits would come out stricter than needed and undo the look-ahead).  All of them are volatile, so they
+// are issued in source order, and LdsSched counts that order.
+template <int IMM, typename V>
+__device__ __forceinline__ void lds_read16(V &dst, uint32_t addr) {
+    static_assert(sizeof(V) == 16 && IMM >= 0 && IMM < 65536, "ds_read_b128");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(IMM));
+}
+// x is complete once at most ALLOWED LDS operations issued after its read are outstanding
+template <int ALLOWED, typename V>
+__device__ __forceinline__ void lds_wait(V &x) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(ALLOWED < 15 ? ALLOWED : 15));
+}
+// Issue order of the section: the log-sum-exps and the D values of the first four queries, PF score fragments;
+// then per softmax element e (a chunk): [the fragment of score MFMA e / PER_M + PF] [one transposing read]
+// [log-sum-exps and D values of the next four queries, every fourth element].
+template <int NM, int PER_M, int PF, int PER_R>
+struct LdsSched {
+    static constexpr bool has_frag(int e) { return e % PER_M == 0 && e / PER_M + PF < NM; }
+    static constexpr bool has_tr(int e) { return e % PER_R == 0; }
+    static constexpr int in_chunk(int e) { return (has_frag(e) ? 1 : 0) + (has_tr(e) ? 1 : 0) + ((e & 3) == 0 && (e >> 2) < 3 ? 2 : 0); }
+    static constexpr int before(int e) {                 // operations issued before the waits of chunk e
+        int n = PF + 2;
+        for (int i = 0; i < e; ++i) n += in_chunk(i);
+        return n;
+    }
+    static constexpr int idx_frag(int j) { return j < PF ? 2 + j : before((j - PF) * PER_M); }
+    static constexpr int idx_d(int gq) {                 // the later of the two reads for queries 8 gq ..
+        return gq == 0 ? 1 : before(4 * (gq - 1)) + (has_frag(4 * (gq - 1)) ? 1 : 0) + (has_tr(4 * (gq - 1)) ? 1 : 0) + 1;
+    }
+    static constexpr int allowed_frag(int e) { return before(e) - 1 - idx_frag(e / PER_M); }
+    static constexpr int allowed_d(int e) { return before(e) - 1 - idx_d(e >> 2); }
+};
 
 // Inverse rotary embedding of a gradient held in accumulator layout (the backward pass of the rotation that
 // was applied to q and k before the attention): feature f < D/2 pairs with f + D/2, which sit in the same
@@ -534,6 +590,258 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     const int key = k0 + wave * 32 + l32;
     const RowInfo me = key_range(a.tok_info, key, T);       // queries [lo, hi) see this key
     const bool valid = key < T;
+    const int w_lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.lo : 0x7fffffff));
+    const int w_lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.lo));
+    const int w_hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.hi));
+    const int w_hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.hi : 0x7fffffff));
+    const RowInfo first = key_range(a.tok_info, k0, T), last = key_range(a.tok_info, min(k0 + BQ, T) - 1, T);
+    const int qbeg = first.lo, qend = last.hi;
+
+    bf16x8 kf[KS], vf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0), w = v;
+        if (valid && ks * 16 + half * 8 < dh) {
+            v = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + g * dh + ks * 16 + half * 8);
+            w = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + nk + g * dh + ks * 16 + half * 8);
+        }
+        kf[ks] = *reinterpret_cast<bf16x8 *>(&v);
+        vf[ks] = *reinterpret_cast<bf16x8 *>(&w);
+    }
+    f32x16 dk[CB], dv[CB];
+#pragma unroll
+    for (int c = 0; c < CB; ++c) { dk[c] = zero16(); dv[c] = zero16(); }
+    const float sl2 = a.scale * LOG2E;
+
+    const __amdgpu_buffer_rsrc_t rs_q =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_do =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dO), 0, (int)(uint32_t)((size_t)T * nq * 2), 0x00020000);
+    // every wavefront copies a quarter of the Q tile and of the dO tile; wavefronts 0 and 1 also fetch the
+    // 64 log-sum-exps and the 64 D values of the tile's queries (4 bytes per lane; queries >= T read as 0)
+    auto copy_tile = [&](uint8_t *slot, int head, int qt) {
+        copy_rows<D, COPIES>(rs_q, slot, wave * COPIES, qt, ld, head * dh, dh);
+        copy_rows<D, COPIES>(rs_do, slot + TILE, wave * COPIES, qt, nq, head * dh, dh);
+        if (wave < 2) {
+            const float *src = (wave == 0 ? a.lse : a.Dsum) + (long)head * T;
+            const __amdgpu_buffer_rsrc_t rs_f =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(src), 0, (int)(uint32_t)((size_t)T * 4), 0x00020000);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_f, (lds_void *)(slot + 2 * TILE + wave * BT2 * 4), 4,
+                                                     (int)((qt + lane) * 4), 0, 0, 0);
+        }
+    };
+    TrReader<D> tr;
+    tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
+
+    if (qbeg >= qend) goto done;      // no query sees these keys (cannot happen for a key of a segment: it sees itself)
+    {
+    // The (head, query tile) pairs form one sequence of steps, every step two blocks of 32 queries.  The blocks are
+    // software-pipelined: while the vector ALU turns the scores of a block into P and dS, the matrix core computes
+    // the scores of the block after it (one MFMA in front of every element of the softmax, so that neither unit
+    // waits for the other in this one-wavefront-per-SIMD kernel); the dV and dK products of the block follow.
+    // Three LDS slots: a step's second block reads the next step's tile for its look-ahead scores, so the copy of
+    // tile step + 2 is issued at the barrier in the middle of step `step`, into the slot tile step - 1 has left.
+    // A wavefront skips the steps none of whose queries sees any of its keys; the scores behind such a gap are
+    // computed on their own.
+    const int tiles_per_head = (qend - qbeg + BT2 - 1) / BT2, n_steps = group * tiles_per_head;
+    auto head_of = [&](int step) { return g * group + step / tiles_per_head; };
+    auto qt_of = [&](int step) { return qbeg + (step % tiles_per_head) * BT2; };
+    const unsigned span = (unsigned)(me.hi - me.lo);
+
+    // LDS addresses, shared by all blocks.  A fragment of the score MFMAs: row 32 bn + l32 of a tile, 16-byte unit
+    // (2 ks + half) ^ swz(row), and swz(32 + l32) = swz(l32) ^ 4, so block 1 finds slice ks where block 0 finds
+    // slice ks ^ 2, 32 rows further on; slices 4 .. 7 lie 128 bytes behind slices 0 .. 3.
+    uint32_t f0[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f0[k] = (uint32_t)(uintptr_t)(lds_void *)smem + (l32 * (D / 8) + ((2 * k + half) ^ swz(l32))) * 16;
+    const uint32_t l0 = (uint32_t)(uintptr_t)(lds_void *)smem + 2 * TILE + half * 16;
+    uint32_t fcur[4], fnxt[4], trc[8], lcur = 0;      // ... of the current step's tile, of the next step's
+    int qt_cur = 0;
+    int mbase = 0;                                      // first query of this lane's quads minus the first that sees its key
+    f32x16 sc[2], dpc[2];                               // scores and dP of a step's two blocks
+
+    auto score_frag = [&](const uint32_t (&fa)[4], auto BN_, auto J_) -> bf16x8 {
+        constexpr int bn = decltype(BN_)::value, j = decltype(J_)::value, ks = j >> 1;
+        return *(lds_bf16x8 *)(uintptr_t)(fa[(ks & 3) ^ (2 * bn)] + ((j & 1) * TILE + (ks >> 2) * 128 + bn * 64 * D));
+    };
+    auto issue_frag = [&](bf16x8 &dst, const uint32_t (&fa)[4], auto BN_, auto J_) {
+        constexpr int bn = decltype(BN_)::value, j = decltype(J_)::value, ks = j >> 1;
+        lds_read16<(j & 1) * TILE + (ks >> 2) * 128 + bn * 64 * D>(dst, fa[(ks & 3) ^ (2 * bn)]);
+    };
+    // the scores of block 0 of the current tile, on their own
+    auto scores0 = [&]() {
+        sc[0] = zero16(); dpc[0] = zero16();
+        static_for<0, 2 * KS>([&](auto J_) {
+            constexpr int j = decltype(J_)::value;
+            const bf16x8 f = score_frag(fcur, std::integral_constant<int, 0>{}, J_);
+            if constexpr ((j & 1) == 0) sc[0] = MFMA(f, kf[j >> 1], sc[0]);
+            else dpc[0] = MFMA(f, vf[j >> 1], dpc[0]);
+        });
+    };
+    // block b of the current tile: softmax from (sc[b], dpc[b]) with the look-ahead scores of the block after it into
+    // (sc[b ^ 1], dpc[b ^ 1]), then dV += dO^T P and dK += Q^T dS
+    auto block = [&](auto B_) {
+        constexpr int b = decltype(B_)::value;
+        constexpr int NM = 2 * KS, PER_M = 16 / NM, PF = NM > 8 ? 5 : 3;          // score MFMAs, softmax elements per MFMA, fragments in flight
+        constexpr int NR = 4 * CB, PER_R = 16 / NR;                  // transposing reads of the block's first 16 queries
+        const uint32_t (&fa)[4] = b == 0 ? fcur : fnxt;
+        constexpr std::integral_constant<int, b ^ 1> BN{};
+        shortx4 o0[CB], o1[CB], q0f[CB], q1f[CB], o2[CB], o3[CB], q2f[CB], q3f[CB];
+        uint32_t pp[8], dd[8];
+        auto fused = [&](auto MASK_) {
+            constexpr bool MASK = decltype(MASK_)::value;
+            using Sched = LdsSched<NM, PER_M, PF, PER_R>;
+            bf16x8 fr[NM];
+            f32x4 l4[4], d4[4];
+            lds_read16<b * 128>(l4[0], lcur);
+            lds_read16<b * 128 + BT2 * 4>(d4[0], lcur);
+            static_for<0, PF>([&](auto J_) { issue_frag(fr[decltype(J_)::value], fa, BN, J_); });
+            __builtin_amdgcn_sched_barrier(0);         // the copies of this block's scores out of the accumulation registers follow
+            float pprev = 0.f, dprev = 0.f;
+            sc[b ^ 1] = zero16(); dpc[b ^ 1] = zero16();
+            static_for<0, 16>([&](auto E_) {
+                constexpr int e = decltype(E_)::value, gq = e >> 2, el = e & 3;
+                if constexpr (el == 0) { lds_wait<Sched::allowed_d(e)>(l4[gq]); lds_wait<Sched::allowed_d(e)>(d4[gq]); }
+                if constexpr (e % PER_M == 0) {
+                    constexpr int j = e / PER_M;
+                    lds_wait<Sched::allowed_frag(e)>(fr[j]);
+                    if constexpr ((j & 1) == 0) sc[b ^ 1] = MFMA(fr[j], kf[j >> 1], sc[b ^ 1]);
+                    else dpc[b ^ 1] = MFMA(fr[j], vf[j >> 1], dpc[b ^ 1]);
+                    if constexpr (j + PF < NM) issue_frag(fr[j + PF], fa, BN, std::integral_constant<int, j + PF>{});
+                }
+                if constexpr (e % PER_R == 0) {                      // read r: feature block r / 4; dO or Q; first or second quad
+                    constexpr int r = e / PER_R, c = r >> 2;
+                    if constexpr ((r & 3) == 0) o0[c] = TrReader<D>::template read_at<b, 0, c, 0, TILE>(trc);
+                    if constexpr ((r & 3) == 1) o1[c] = TrReader<D>::template read_at<b, 0, c, 1, TILE>(trc);
+                    if constexpr ((r & 3) == 2) q0f[c] = TrReader<D>::template read_at<b, 0, c, 0, 0>(trc);
+                    if constexpr ((r & 3) == 3) q1f[c] = TrReader<D>::template read_at<b, 0, c, 1, 0>(trc);
+                }
+                if constexpr (el == 0 && gq < 3) {
+                    lds_read16<b * 128 + (gq + 1) * 32>(l4[gq + 1], lcur);
+                    lds_read16<b * 128 + (gq + 1) * 32 + BT2 * 4>(d4[gq + 1], lcur);
+                }
+                const float lv = l4[gq][el], dvv = d4[gq][el];
+                float pv = __builtin_amdgcn_exp2f(fmaf(sc[b][e], sl2, -lv * LOG2E));
+                if (MASK) pv = (unsigned)(mbase + (32 * b + 8 * gq + el)) < span ? pv : 0.f;
+                const float dsv = pv * (dpc[b][e] - dvv);
+                if constexpr (e & 1) { pp[e >> 1] = pack_bf16x2(pprev, pv); dd[e >> 1] = pack_bf16x2(dprev, dsv); }
+                else { pprev = pv; dprev = dsv; }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        };
+        if (qt_cur + 32 * b >= w_lo_max && qt_cur + 32 * b + 32 <= w_hi_min) fused(std::false_type{});
+        else fused(std::true_type{});
+        auto frag4 = [](const uint32_t *w) {
+            const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
+            return *reinterpret_cast<const bf16x8 *>(&v);
+        };
+        if constexpr (CB > 2) asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT4(o0), TR_WAIT4(o1), TR_WAIT4(q0f), TR_WAIT4(q1f));
+        else asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT2(o0), TR_WAIT2(o1), TR_WAIT2(q0f), TR_WAIT2(q1f));
+        static_for<0, CB>([&](auto C_) {                             // in flight during the next 2 CB MFMAs
+            constexpr int c = decltype(C_)::value;
+            o2[c] = TrReader<D>::template read_at<b, 1, c, 0, TILE>(trc); o3[c] = TrReader<D>::template read_at<b, 1, c, 1, TILE>(trc);
+            q2f[c] = TrReader<D>::template read_at<b, 1, c, 0, 0>(trc); q3f[c] = TrReader<D>::template read_at<b, 1, c, 1, 0>(trc);
+        });
+        {
+            const bf16x8 pf = frag4(pp), dsf = frag4(dd);
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                dv[c] = MFMA(join(o0[c], o1[c]), pf, dv[c]);
+                dk[c] = MFMA(join(q0f[c], q1f[c]), dsf, dk[c]);
+            }
+        }
+        if constexpr (CB > 2) asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT4(o2), TR_WAIT4(o3), TR_WAIT4(q2f), TR_WAIT4(q3f));
+        else asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT2(o2), TR_WAIT2(o3), TR_WAIT2(q2f), TR_WAIT2(q3f));
+        {
+            const bf16x8 pf = frag4(pp + 4), dsf = frag4(dd + 4);
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                dv[c] = MFMA(join(o2[c], o3[c]), pf, dv[c]);
+                dk[c] = MFMA(join(q2f[c], q3f[c]), dsf, dk[c]);
+            }
+        }
+    };
+
+    copy_tile(smem, head_of(0), qt_of(0));
+    if (n_steps > 1) copy_tile(smem + SLOT, head_of(1), qt_of(1));
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
+    int slot = 0;
+    bool have0 = false;                                // block 0's scores of this step were computed by the step before
+    for (int step = 0; step < n_steps; ++step) {
+        const int qt = qt_of(step), nslot = slot == 2 ? 0 : slot + 1;
+        qt_cur = qt;
+        const bool more = step + 1 < n_steps;
+        const bool act = qt < w_hi_max && qt + BT2 > w_lo_min;
+        if (act) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { fcur[k] = f0[k] + slot * SLOT; fnxt[k] = f0[k] + nslot * SLOT; }
+#pragma unroll
+            for (int x = 0; x < 8; ++x) trc[x] = tr.off[x] + slot * SLOT;
+            lcur = l0 + slot * SLOT;
+            mbase = qt + 4 * half - me.lo;
+            if (!have0) scores0();
+            block(std::integral_constant<int, 0>{});
+        }
+        if (more) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next step's tile has landed
+            lds_barrier();                                           // ... for everyone, and tile step - 1 is no longer read
+            if (step + 2 < n_steps) copy_tile(smem + (nslot == 2 ? 0 : nslot + 1) * SLOT, head_of(step + 2), qt_of(step + 2));
+        }
+        if (act) block(std::integral_constant<int, 1>{});
+        have0 = act;
+        slot = nslot;
+    }
+    }
+done:
+    if (valid) {
+        if (a.rope_cs) unrotate<CB>(dk, a.rope_cs + (long)key * (D / 2), half);
+        bf16_t *okp = (bf16_t *)a.d_qkv + (long)key * ld + nq + g * dh;
+        bf16_t *ovp = okp + nk;
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                uint2 w;
+                w.x = pack_bf16x2(dk[c][4 * gq] * a.scale, dk[c][4 * gq + 1] * a.scale);
+                w.y = pack_bf16x2(dk[c][4 * gq + 2] * a.scale, dk[c][4 * gq + 3] * a.scale);
+                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(okp + 32 * c + 8 * gq + 4 * half) = w;
+                w.x = pack_bf16x2(dv[c][4 * gq], dv[c][4 * gq + 1]);
+                w.y = pack_bf16x2(dv[c][4 * gq + 2], dv[c][4 * gq + 3]);
+                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(ovp + 32 * c + 8 * gq + 4 * half) = w;
+            }
+    }
+    add_busy(a.cu_busy ? a.cu_busy + 2048 : nullptr, true);
+}
+
+// ------------------------------------------------------------------------------------------
+// backward: dK, dV, the plain form: a block's scores, its softmax and its products one after the other, two LDS
+// slots.  Used for the 64-wide head, where it fits 256 registers, so that two workgroups share a compute unit
+// and overlap each other's phases; the pipelined kernel above needs more registers than that at any width.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_dkv_plain_kernel(AttnArgs a) {
+    constexpr int KS = D / 16, CB = D / 32;
+    constexpr int TILE = BT2 * D * 2, SLOT = 2 * TILE + 2 * BT2 * 4;   // Q tile, dO tile, lse[64], D[64]
+    constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                     // per wavefront and tile
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    add_busy(a.cu_busy ? a.cu_busy + 2048 : nullptr, false);
+
+    // grid: x = key/value head, y = position in the dispatch order of the key tiles (heaviest first)
+    const int g = blockIdx.x, group = a.nh / a.nkv;
+    const int k0 = (a.use_order ? a.order_k[blockIdx.y] : blockIdx.y) * BQ;
+    // the wavefront's index as a scalar: what is derived from it (copy destinations, buffer descriptors) stays uniform
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5, l32 = lane & 31;
+    const int T = a.T;
+    const bf16_t *qkv = (const bf16_t *)a.qkv;
+    const bf16_t *dO = (const bf16_t *)a.d_o;
+    const long ld = a.ld_qkv;
+    const int dh = a.d;                                 // head dimension in memory (<= D: LDS tiles and fragments are zero-padded to D)
+    const int nq = a.nh * dh, nk = a.nkv * dh;
+
+    const int key = k0 + wave * 32 + l32;
+    const RowInfo me = key_range(a.tok_info, key, T);       // queries [lo, hi) see this key
+    const bool valid = key < T;
     const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
     const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
     const RowInfo first = key_range(a.tok_info, k0, T), last = key_range(a.tok_info, min(k0 + BQ, T) - 1, T);
@@ -715,16 +1023,20 @@ hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
 template <int D>
 hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
-    const int smem_dq = 2 * 2 * BT2 * D * 2, smem_dkv = 2 * (2 * BT2 * D * 2 + 2 * BT2 * 4);
+    constexpr bool PIPELINED = D > 64;                  // see attn_dkv_plain_kernel
+    constexpr int DKV_SLOT = 2 * BT2 * D * 2 + 2 * BT2 * 4;
+    const int smem_dq = 2 * 2 * BT2 * D * 2, smem_dkv = (PIPELINED ? 3 : 2) * DKV_SLOT;
     if (!configured) {
         hipError_t e = set_smem(attn_dq_kernel<D>, smem_dq);
         if (e != hipSuccess) return e;
-        e = set_smem(attn_dkv_kernel<D>, smem_dkv);
+        if constexpr (PIPELINED) e = set_smem(attn_dkv_kernel<D>, smem_dkv);
+        else e = set_smem(attn_dkv_plain_kernel<D>, smem_dkv);
         if (e != hipSuccess) return e;
         configured = true;
     }
     attn_dq_kernel<D><<<dim3(a.nh, ceil_div(a.T, FQ)), 512, smem_dq, st>>>(a);
-    attn_dkv_kernel<D><<<dim3(a.nkv, ceil_div(a.T, BQ)), 256, smem_dkv, st>>>(a);
+    if constexpr (PIPELINED) attn_dkv_kernel<D><<<dim3(a.nkv, ceil_div(a.T, BQ)), 256, smem_dkv, st>>>(a);
+    else attn_dkv_plain_kernel<D><<<dim3(a.nkv, ceil_div(a.T, BQ)), 256, smem_dkv, st>>>(a);
     return hipGetLastError();
 }
 
