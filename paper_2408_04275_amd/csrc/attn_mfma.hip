@@ -289,8 +289,10 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     const int q = q0 + wave * 32 + l32;
     const RowInfo me = query_range(a.tok_info, q, T);
     const bool valid = q < T;
-    const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
-    const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
+    const int w_lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.lo : 0x7fffffff));
+    const int w_lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.lo));
+    const int w_hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.hi));
+    const int w_hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.hi : 0x7fffffff));
     const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
     const int kbeg = first.lo, kend = last.hi;
 
@@ -432,8 +434,10 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     const int q = q0 + wave * 32 + l32;
     const RowInfo me = query_range(a.tok_info, q, T);
     const bool valid = q < T;
-    const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
-    const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
+    const int w_lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.lo : 0x7fffffff));
+    const int w_lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.lo));
+    const int w_hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.hi));
+    const int w_hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.hi : 0x7fffffff));
     const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
     const int kbeg = first.lo, kend = last.hi;
 
@@ -842,8 +846,10 @@ __global__ __launch_bounds__(256) void attn_dkv_plain_kernel(AttnArgs a) {
     const int key = k0 + wave * 32 + l32;
     const RowInfo me = key_range(a.tok_info, key, T);       // queries [lo, hi) see this key
     const bool valid = key < T;
-    const int w_lo_min = wave_min_i(valid ? me.lo : 0x7fffffff), w_lo_max = wave_max_i(me.lo);
-    const int w_hi_max = wave_max_i(me.hi), w_hi_min = wave_min_i(valid ? me.hi : 0x7fffffff);
+    const int w_lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.lo : 0x7fffffff));
+    const int w_lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.lo));
+    const int w_hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.hi));
+    const int w_hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.hi : 0x7fffffff));
     const RowInfo first = key_range(a.tok_info, k0, T), last = key_range(a.tok_info, min(k0 + BQ, T) - 1, T);
     const int qbeg = first.lo, qend = last.hi;
 
