@@ -138,23 +138,37 @@ constexpr int BT2 = 64;
 typedef __attribute__((ext_vector_type(4))) short shortx4;
 typedef __attribute__((ext_vector_type(8))) short shortx8;
 
-// One wavefront's share of the copy of a [64][D] tile: copies i = 0 .. N-1 of 1 KiB each, copy (first + i)
-// of the tile covering rows (first + i) * 512 / D ...  Rows at or beyond the end of the tensor read as zero,
-// and so do the columns from row_elems on (a head narrower than the tile).
+// One wavefront's share of the copies of [64][D] tiles out of a row-major tensor: N copies of 1 KiB per tile, copy
+// (first + i) of a tile covering its rows (first + i) * 512 / D ...  What depends on the lane is computed once
+// (init); a copy then costs one addition.  Rows at or beyond the end of the tensor read as zero (the descriptor's
+// bounds check), and so do the columns from row_elems on (a head narrower than the tile): their lanes carry an
+// offset of 2 GiB, which no tensor reaches (the launchers check), and the sum with the tile's offset cannot wrap.
 template <int D, int N>
-__device__ __forceinline__ void copy_rows(__amdgpu_buffer_rsrc_t rs, uint8_t *tile, int first, long row0, long ld, long col0,
-                                          int row_elems) {
-    constexpr int UPR = D / 8, ROWS_PER_COPY = 1024 / (2 * D);
-    const int lane = threadIdx.x & 63;
-    const int lrow = lane / UPR, pos = lane % UPR;
+struct RowCopier {
+    static constexpr int UPR = D / 8, ROWS_PER_COPY = 1024 / (2 * D);
+    uint32_t off[N];
+    int first;
+    __device__ __forceinline__ void init(int first_, long ld, int row_elems) {
+        first = first_;
+        const int lane = threadIdx.x & 63;
+        const int lrow = lane / UPR, pos = lane % UPR;
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-        const int r0 = (first + i) * ROWS_PER_COPY, row = r0 + lrow;
-        const int unit = (pos & ~7) | ((pos & 7) ^ swz(row));
-        const uint32_t off = unit * 8 < row_elems ? (uint32_t)(((size_t)(row0 + row) * ld + col0 + unit * 8) * 2) : 0xfffffff0u;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + r0 * 2 * D), 16, (int)off, 0, 0, 0);
+        for (int i = 0; i < N; ++i) {
+            const int row = (first + i) * ROWS_PER_COPY + lrow;
+            const int unit = (pos & ~7) | ((pos & 7) ^ swz(row));
+            off[i] = unit * 8 < row_elems ? (uint32_t)((row * ld + unit * 8) * 2) : 0x80000000u;
+        }
     }
-}
+    // the tile whose first row is row0 and whose first column is col0 of the tensor rs describes (row length ld)
+    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, uint8_t *tile, long row0, long ld, long col0) const {
+        const uint32_t base = (uint32_t)((row0 * ld + col0) * 2);
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + (first + i) * ROWS_PER_COPY * 2 * D), 16,
+                                                     (int)(off[i] + base), 0, 0, 0);
+    }
+};
+constexpr size_t MAX_TENSOR_BYTES = 0x7fff0000ull;      // what RowCopier's offsets allow
 
 // Transposing reads.  Lane constants: 16-lane group gq = lane >> 4 forms the fragment rows (features)
 // 16 (gq & 1) .. + 15 for lane half h = gq >> 1; as a source, lane j = lane & 15 of the group supplies
@@ -329,9 +343,11 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     const __amdgpu_buffer_rsrc_t rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
     // wavefronts 4..7 copy the K tile, wavefronts 0..3 the V tile
+    RowCopier<D, COPIES> cp;
+    cp.init((wave & 3) * COPIES, ld, dh);
     auto copy_kv = [&](uint8_t *slot, int kt) {
-        if (wave >= 4) copy_rows<D, COPIES>(rs, slot, (wave - 4) * COPIES, kt, ld, nq + g * dh, dh);
-        else copy_rows<D, COPIES>(rs, slot + TILE, wave * COPIES, kt, ld, nq + nk + g * dh, dh);
+        if (wave >= 4) cp.issue(rs, slot, kt, ld, nq + g * dh);
+        else cp.issue(rs, slot + TILE, kt, ld, nq + nk + g * dh);
     };
     TrReader<D> tr;
     tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
@@ -457,9 +473,11 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     const __amdgpu_buffer_rsrc_t rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
     // wavefronts 4..7 copy the K tile, wavefronts 0..3 the V tile
+    RowCopier<D, COPIES> cp;
+    cp.init((wave & 3) * COPIES, ld, dh);
     auto copy_kv = [&](uint8_t *slot, int kt) {
-        if (wave >= 4) copy_rows<D, COPIES>(rs, slot, (wave - 4) * COPIES, kt, ld, nq + g * dh, dh);
-        else copy_rows<D, COPIES>(rs, slot + TILE, wave * COPIES, kt, ld, nq + nk + g * dh, dh);
+        if (wave >= 4) cp.issue(rs, slot, kt, ld, nq + g * dh);
+        else cp.issue(rs, slot + TILE, kt, ld, nq + nk + g * dh);
     };
     TrReader<D> tr;
     tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
@@ -623,9 +641,12 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dO), 0, (int)(uint32_t)((size_t)T * nq * 2), 0x00020000);
     // every wavefront copies a quarter of the Q tile and of the dO tile; wavefronts 0 and 1 also fetch the
     // 64 log-sum-exps and the 64 D values of the tile's queries (4 bytes per lane; queries >= T read as 0)
+    RowCopier<D, COPIES> cp_q, cp_do;
+    cp_q.init(wave * COPIES, ld, dh);
+    cp_do.init(wave * COPIES, nq, dh);
     auto copy_tile = [&](uint8_t *slot, int head, int qt) {
-        copy_rows<D, COPIES>(rs_q, slot, wave * COPIES, qt, ld, head * dh, dh);
-        copy_rows<D, COPIES>(rs_do, slot + TILE, wave * COPIES, qt, nq, head * dh, dh);
+        cp_q.issue(rs_q, slot, qt, ld, head * dh);
+        cp_do.issue(rs_do, slot + TILE, qt, nq, head * dh);
         if (wave < 2) {
             const float *src = (wave == 0 ? a.lse : a.Dsum) + (long)head * T;
             const __amdgpu_buffer_rsrc_t rs_f =
@@ -875,9 +896,12 @@ __global__ __launch_bounds__(256) void attn_dkv_plain_kernel(AttnArgs a) {
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dO), 0, (int)(uint32_t)((size_t)T * nq * 2), 0x00020000);
     // every wavefront copies a quarter of the Q tile and of the dO tile; wavefronts 0 and 1 also fetch the
     // 64 log-sum-exps and the 64 D values of the tile's queries (4 bytes per lane; queries >= T read as 0)
+    RowCopier<D, COPIES> cp_q, cp_do;
+    cp_q.init(wave * COPIES, ld, dh);
+    cp_do.init(wave * COPIES, nq, dh);
     auto copy_tile = [&](uint8_t *slot, int head, int qt) {
-        copy_rows<D, COPIES>(rs_q, slot, wave * COPIES, qt, ld, head * dh, dh);
-        copy_rows<D, COPIES>(rs_do, slot + TILE, wave * COPIES, qt, nq, head * dh, dh);
+        cp_q.issue(rs_q, slot, qt, ld, head * dh);
+        cp_do.issue(rs_do, slot + TILE, qt, nq, head * dh);
         if (wave < 2) {
             const float *src = (wave == 0 ? a.lse : a.Dsum) + (long)head * T;
             const __amdgpu_buffer_rsrc_t rs_f =
@@ -1050,11 +1074,13 @@ hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
 
 hipError_t attn_mfma_fwd(const AttnArgs &a, hipStream_t st) {
     if (a.T == 0) return hipSuccess;
+    if ((size_t)a.T * a.ld_qkv * 2 >= MAX_TENSOR_BYTES) return hipErrorInvalidValue;
     return a.d <= 64 ? launch_fwd<64>(a, st) : launch_fwd<128>(a, st);
 }
 
 hipError_t attn_mfma_bwd(const AttnArgs &a, hipStream_t st) {
     if (a.T == 0) return hipSuccess;
+    if ((size_t)a.T * a.ld_qkv * 2 >= MAX_TENSOR_BYTES) return hipErrorInvalidValue;
     return a.d <= 64 ? launch_bwd<64>(a, st) : launch_bwd<128>(a, st);
 }
 
