@@ -388,12 +388,17 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
             const unsigned span = (unsigned)(me.hi - me.lo);
             const int rel = kb + 4 * half - me.lo;
             float ds[16];
+            // two copies of the loop, so that a block no key of which is masked pays nothing for the mask
+            auto softmax = [&](auto MASK_) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float p = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lse2));
-                if (!inside) p = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? p : 0.f;
-                ds[i] = p * (dp[i] - Dq);
-            }
+                for (int i = 0; i < 16; ++i) {
+                    float p = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lse2));
+                    if (decltype(MASK_)::value) p = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? p : 0.f;
+                    ds[i] = p * (dp[i] - Dq);
+                }
+            };
+            if (inside) softmax(std::false_type{});
+            else softmax(std::true_type{});
             asm volatile("s_waitcnt lgkmcnt(0)" : TR_WAIT4(t0), TR_WAIT4(t1), TR_WAIT4(t2), TR_WAIT4(t3));
             const bf16x8 ds0 = pack8(ds), ds1 = pack8(ds + 8);
 #pragma unroll
