@@ -145,6 +145,18 @@ def test_attention_padded_head_dim(nh, nkv, d):
     attn_case(mm.BF16, nh, nkv, d, RAGGED_CU, RAGGED_MODES, std=1.0, seed=7)
 
 
+def test_attention_many_segment_boundaries_wide_head():
+    # 128-wide heads take the dK/dV kernel that looks one block ahead: segment boundaries inside key tiles make its
+    # wavefronts start and stop at different steps and restart per query head of the group (4 heads per K/V head);
+    # segments shorter than one step, a bidirectional segment spanning several key tiles, a ragged end
+    rng = np.random.default_rng(11)
+    lens = [3, 61, 130, 7, 320, 64, 1, 65, 511, 40, 200, 129]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    modes = rng.integers(0, 2, len(lens)).astype(np.uint8)
+    modes[4], modes[8] = 1, 0                                   # the 320-token one bidirectional, the 511-token one causal
+    attn_case(mm.BF16, 8, 2, 128, cu, modes, std=1.0, seed=12)
+
+
 def test_attention_busy_counters_leave_results_unchanged():
     """The per-compute-unit busy counters (a measurement aid) change nothing in the outputs, and every workgroup's time
     lands in some compute unit's entry."""
