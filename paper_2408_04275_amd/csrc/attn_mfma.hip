@@ -44,17 +44,6 @@ constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
-__device__ __forceinline__ int wave_max_i(int v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
-    return v;
-}
-__device__ __forceinline__ int wave_min_i(int v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
-    return v;
-}
-
 __device__ __forceinline__ bf16x8 pack8(const float *v) {
     bf16x8 r;
 #pragma unroll
@@ -83,6 +72,23 @@ __device__ __forceinline__ void add_busy(unsigned long long *row, bool end) {
 }
 
 struct RowInfo { int lo, hi; };   // allowed partner range of one token
+
+// Smallest and largest range bounds over the 32 consecutive tokens base .. base + 31 that a wavefront holds one per
+// lane (lanes 32 .. 63 repeat them), as scalars.  Both bounds are non-decreasing in the token index (segments follow
+// one another in the pack; a causal bound moves with the token), so the first and the last token in range have them.
+// No token in range: empty (lo_min = hi_min = INT_MAX, lo_max = hi_max = 0).
+struct WaveBounds { int lo_min, lo_max, hi_min, hi_max; };
+__device__ __forceinline__ WaveBounds wave_bounds(const RowInfo &me, int base, int T) {
+    WaveBounds w = {0x7fffffff, 0, 0x7fffffff, 0};
+    const int n = min(T - base, 32);
+    if (n > 0) {
+        w.lo_min = __builtin_amdgcn_readfirstlane(me.lo);
+        w.hi_min = __builtin_amdgcn_readfirstlane(me.hi);
+        w.lo_max = __builtin_amdgcn_readlane(me.lo, n - 1);
+        w.hi_max = __builtin_amdgcn_readlane(me.hi, n - 1);
+    }
+    return w;
+}
 
 __device__ __forceinline__ RowInfo query_range(const int2 *info, int q, int T) {
     RowInfo r = {0, 0};
@@ -303,10 +309,8 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     const int q = q0 + wave * 32 + l32;
     const RowInfo me = query_range(a.tok_info, q, T);
     const bool valid = q < T;
-    const int w_lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.lo : 0x7fffffff));
-    const int w_lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.lo));
-    const int w_hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.hi));
-    const int w_hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.hi : 0x7fffffff));
+    const WaveBounds wb = wave_bounds(me, q0 + wave * 32, T);
+    const int w_lo_min = wb.lo_min, w_lo_max = wb.lo_max, w_hi_max = wb.hi_max, w_hi_min = wb.hi_min;
     const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
     const int kbeg = first.lo, kend = last.hi;
 
@@ -455,10 +459,8 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     const int q = q0 + wave * 32 + l32;
     const RowInfo me = query_range(a.tok_info, q, T);
     const bool valid = q < T;
-    const int w_lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.lo : 0x7fffffff));
-    const int w_lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.lo));
-    const int w_hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.hi));
-    const int w_hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.hi : 0x7fffffff));
+    const WaveBounds wb = wave_bounds(me, q0 + wave * 32, T);
+    const int w_lo_min = wb.lo_min, w_lo_max = wb.lo_max, w_hi_max = wb.hi_max, w_hi_min = wb.hi_min;
     const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
     const int kbeg = first.lo, kend = last.hi;
 
@@ -617,10 +619,8 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     const int key = k0 + wave * 32 + l32;
     const RowInfo me = key_range(a.tok_info, key, T);       // queries [lo, hi) see this key
     const bool valid = key < T;
-    const int w_lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.lo : 0x7fffffff));
-    const int w_lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.lo));
-    const int w_hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.hi));
-    const int w_hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.hi : 0x7fffffff));
+    const WaveBounds wb = wave_bounds(me, k0 + wave * 32, T);
+    const int w_lo_min = wb.lo_min, w_lo_max = wb.lo_max, w_hi_max = wb.hi_max, w_hi_min = wb.hi_min;
     const RowInfo first = key_range(a.tok_info, k0, T), last = key_range(a.tok_info, min(k0 + BQ, T) - 1, T);
     const int qbeg = first.lo, qend = last.hi;
 
@@ -872,10 +872,8 @@ __global__ __launch_bounds__(256) void attn_dkv_plain_kernel(AttnArgs a) {
     const int key = k0 + wave * 32 + l32;
     const RowInfo me = key_range(a.tok_info, key, T);       // queries [lo, hi) see this key
     const bool valid = key < T;
-    const int w_lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.lo : 0x7fffffff));
-    const int w_lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.lo));
-    const int w_hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(me.hi));
-    const int w_hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? me.hi : 0x7fffffff));
+    const WaveBounds wb = wave_bounds(me, k0 + wave * 32, T);
+    const int w_lo_min = wb.lo_min, w_lo_max = wb.lo_max, w_hi_max = wb.hi_max, w_hi_min = wb.hi_min;
     const RowInfo first = key_range(a.tok_info, k0, T), last = key_range(a.tok_info, min(k0 + BQ, T) - 1, T);
     const int qbeg = first.lo, qend = last.hi;
 
