@@ -450,3 +450,33 @@ def test_model_flops_convention():
     assert abs(f["gemm_fwd"] - 3.3157e12) / 3.3157e12 < 1e-3    # 2 * T * 202 375 168 parameters
     assert f["attn_fwd"] == 4 * 128 * 32 * (8192 * 8193 // 2)
     assert f["fwd_bwd"] == 3 * f["fwd"]
+
+
+def test_allowed_ranges_are_monotonic_in_the_token_index():
+    """The attention mask of a pack (Section "Intra-microbatch Reordering": sequences packed back to back, each
+    attending within itself, causally or bidirectionally) gives every query an allowed key range [lo, hi) and every
+    key an allowed query range; both bounds never decrease from one token to the next.  The GPU kernels take a
+    wavefront's extreme bounds from its first and last token on the strength of this.  Checked here on the mask the
+    oracle builds, by brute force over random packs with empty and one-token segments."""
+    from oracle import layer_oracle as orc
+    rng = np.random.default_rng(5)
+    for case in range(40):
+        n = int(rng.integers(1, 9))
+        lens = rng.integers(0, 40, n)
+        lens[rng.integers(0, n)] = int(rng.integers(1, 70))
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        modes = rng.integers(0, 2, n).astype(np.uint8)
+        T = int(cu[-1])
+        allowed = np.zeros((T, T), dtype=bool)                  # allowed[q, k]
+        q = rng.standard_normal((T, 1, 4))
+        for s in range(n):
+            a, b = int(cu[s]), int(cu[s + 1])
+            if b > a:
+                P, _ = orc._probabilities(q[a:b, 0], q[a:b, 0], 1.0, int(modes[s]))
+                allowed[a:b, a:b] = P > 0
+        for M in (allowed, allowed.T):                          # per query over keys, per key over queries
+            lo = np.array([np.flatnonzero(r)[0] for r in M])
+            hi = np.array([np.flatnonzero(r)[-1] + 1 for r in M])
+            for t in range(T):
+                assert M[t, lo[t]:hi[t]].all(), "allowed partners form one interval"
+            assert (np.diff(lo) >= 0).all() and (np.diff(hi) >= 0).all(), (case, cu.tolist(), modes.tolist())
