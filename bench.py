@@ -92,7 +92,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph that holds one forward + backward (no per-kernel figures)")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192,
+                    help="the oracle is timed on the leading segments of the pack up to about this many tokens (default: the whole 8192-token pack, 10-15 s)")
     ap.add_argument("--layers", type=int, default=1,
                     help="more than 1: time a stack of that many layers through mmtrain_stack_fwd / mmtrain_stack_bwd")
     ap.add_argument("--recompute", action="store_true",
