@@ -31,6 +31,7 @@
 // multiple of 16, e.g. 80) uses the next instantiation with the missing features read as zero and never
 // stored.
 #include "kernels.h"
+#include <algorithm>
 #include <type_traits>
 #include <utility>
 
@@ -284,6 +285,36 @@ __device__ __forceinline__ void unrotate(f32x16 (&g)[CB], const float2 *cs, int 
         }
 }
 
+// Stores a wavefront's 32 x D result (accumulator layout: lane = row, registers = features; 4 consecutive features
+// per lane and register quad) as bf16 rows of a row-major tensor.  The rows go through LDS so that a store
+// instruction writes 16 bytes per lane and D / 8 lanes cover a row, whole cache lines, instead of 8 bytes into
+// each of 32 rows.  stage: STAGE_BYTES<D> bytes of LDS that belong to this wavefront alone and that no wavefront still
+// reads as a tile (the callers put a barrier in front).  dst: row 0, feature 0; rows_valid rows and dh features exist.
+template <int D>
+constexpr int STAGE_BYTES = 32 * (2 * D + 16);
+template <int D, int CB>
+__device__ __forceinline__ void store_rows(uint8_t *stage, const f32x16 (&acc)[CB], float scale, bf16_t *dst, long ld,
+                                           int rows_valid, int dh) {
+    constexpr int RS = 2 * D + 16, LPR = D / 8, RPI = 64 / LPR;    // row stride in LDS (2-way bank conflicts at most)
+    const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+#pragma unroll
+    for (int c = 0; c < CB; ++c)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            uint2 w;
+            w.x = pack_bf16x2(acc[c][4 * gq] * scale, acc[c][4 * gq + 1] * scale);
+            w.y = pack_bf16x2(acc[c][4 * gq + 2] * scale, acc[c][4 * gq + 3] * scale);
+            *reinterpret_cast<uint2 *>(stage + l32 * RS + (32 * c + 8 * gq + 4 * half) * 2) = w;
+        }
+    const int r0 = lane / LPR, cb = (lane % LPR) * 16;
+#pragma unroll
+    for (int i = 0; i < 32 / RPI; ++i) {
+        const int r = i * RPI + r0;
+        const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * RS + cb);
+        if (r < rows_valid && cb / 2 < dh) *reinterpret_cast<uint4 *>(dst + (long)r * ld + cb / 2) = v;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // backward: dQ (and D = rowsum(dO * O)).  Same roles as the forward kernel: 8 wavefronts x 32 queries.
 // ------------------------------------------------------------------------------------------
@@ -414,19 +445,10 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
         block(std::integral_constant<int, 0>{});
         block(std::integral_constant<int, 1>{});
     }
-    if (valid) {
-        if (a.rope_cs) unrotate<CB>(dq, a.rope_cs + (long)q * (D / 2), half);
-        bf16_t *out = (bf16_t *)a.d_qkv + (long)q * ld + head * dh;
-#pragma unroll
-        for (int c = 0; c < CB; ++c)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                uint2 w;
-                w.x = pack_bf16x2(dq[c][4 * gq] * a.scale, dq[c][4 * gq + 1] * a.scale);
-                w.y = pack_bf16x2(dq[c][4 * gq + 2] * a.scale, dq[c][4 * gq + 3] * a.scale);
-                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(out + 32 * c + 8 * gq + 4 * half) = w;
-            }
-    }
+    lds_barrier();                                     // the tiles are done with: LDS now stages the output rows
+    if (valid && a.rope_cs) unrotate<CB>(dq, a.rope_cs + (long)q * (D / 2), half);
+    store_rows<D, CB>(smem + wave * STAGE_BYTES<D>, dq, a.scale, (bf16_t *)a.d_qkv + (long)(q0 + wave * 32) * ld + head * dh, ld,
+                      T - (q0 + wave * 32), dh);
     add_busy(a.cu_busy ? a.cu_busy + 1024 : nullptr, true);
 }
 
@@ -575,20 +597,10 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    if (valid) {
-        const float inv = 1.f / l_tot;
-        bf16_t *o = (bf16_t *)a.o + (long)q * nq + head * dh;
-#pragma unroll
-        for (int c = 0; c < CB; ++c)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                uint2 w;
-                w.x = pack_bf16x2(oacc[c][4 * gq] * inv, oacc[c][4 * gq + 1] * inv);
-                w.y = pack_bf16x2(oacc[c][4 * gq + 2] * inv, oacc[c][4 * gq + 3] * inv);
-                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(o + 32 * c + 8 * gq + 4 * half) = w;
-            }
-        if (half == 0) a.lse[(long)head * T + q] = (m_run * sl2 + __builtin_amdgcn_logf(l_tot)) * LN2;
-    }
+    lds_barrier();                                     // the tiles are done with: LDS now stages the output rows
+    store_rows<D, CB>(smem + wave * STAGE_BYTES<D>, oacc, valid ? 1.f / l_tot : 0.f, (bf16_t *)a.o + (long)(q0 + wave * 32) * nq + head * dh,
+                      nq, T - (q0 + wave * 32), dh);
+    if (valid && half == 0) a.lse[(long)head * T + q] = (m_run * sl2 + __builtin_amdgcn_logf(l_tot)) * LN2;
     add_busy(a.cu_busy, true);
 }
 
@@ -824,22 +836,13 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     }
     }
 done:
-    if (valid) {
-        if (a.rope_cs) unrotate<CB>(dk, a.rope_cs + (long)key * (D / 2), half);
-        bf16_t *okp = (bf16_t *)a.d_qkv + (long)key * ld + nq + g * dh;
-        bf16_t *ovp = okp + nk;
-#pragma unroll
-        for (int c = 0; c < CB; ++c)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                uint2 w;
-                w.x = pack_bf16x2(dk[c][4 * gq] * a.scale, dk[c][4 * gq + 1] * a.scale);
-                w.y = pack_bf16x2(dk[c][4 * gq + 2] * a.scale, dk[c][4 * gq + 3] * a.scale);
-                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(okp + 32 * c + 8 * gq + 4 * half) = w;
-                w.x = pack_bf16x2(dv[c][4 * gq], dv[c][4 * gq + 1]);
-                w.y = pack_bf16x2(dv[c][4 * gq + 2], dv[c][4 * gq + 3]);
-                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(ovp + 32 * c + 8 * gq + 4 * half) = w;
-            }
+    lds_barrier();                                     // the tiles are done with: LDS now stages the output rows
+    {
+        bf16_t *okp = (bf16_t *)a.d_qkv + (long)(k0 + wave * 32) * ld + nq + g * dh;
+        uint8_t *stage = smem + wave * STAGE_BYTES<D>;
+        store_rows<D, CB>(stage, dv, 1.f, okp + nk, ld, T - (k0 + wave * 32), dh);
+        if (valid && a.rope_cs) unrotate<CB>(dk, a.rope_cs + (long)key * (D / 2), half);
+        store_rows<D, CB>(stage, dk, a.scale, okp, ld, T - (k0 + wave * 32), dh);
     }
     add_busy(a.cu_busy ? a.cu_busy + 2048 : nullptr, true);
 }
@@ -1015,22 +1018,13 @@ __global__ __launch_bounds__(256) void attn_dkv_plain_kernel(AttnArgs a) {
     }
     }
 done:
-    if (valid) {
-        if (a.rope_cs) unrotate<CB>(dk, a.rope_cs + (long)key * (D / 2), half);
-        bf16_t *okp = (bf16_t *)a.d_qkv + (long)key * ld + nq + g * dh;
-        bf16_t *ovp = okp + nk;
-#pragma unroll
-        for (int c = 0; c < CB; ++c)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                uint2 w;
-                w.x = pack_bf16x2(dk[c][4 * gq] * a.scale, dk[c][4 * gq + 1] * a.scale);
-                w.y = pack_bf16x2(dk[c][4 * gq + 2] * a.scale, dk[c][4 * gq + 3] * a.scale);
-                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(okp + 32 * c + 8 * gq + 4 * half) = w;
-                w.x = pack_bf16x2(dv[c][4 * gq], dv[c][4 * gq + 1]);
-                w.y = pack_bf16x2(dv[c][4 * gq + 2], dv[c][4 * gq + 3]);
-                if (32 * c + 8 * gq + 4 * half < dh) *reinterpret_cast<uint2 *>(ovp + 32 * c + 8 * gq + 4 * half) = w;
-            }
+    lds_barrier();                                     // the tiles are done with: LDS now stages the output rows
+    {
+        bf16_t *okp = (bf16_t *)a.d_qkv + (long)(k0 + wave * 32) * ld + nq + g * dh;
+        uint8_t *stage = smem + wave * STAGE_BYTES<D>;
+        store_rows<D, CB>(stage, dv, 1.f, okp + nk, ld, T - (k0 + wave * 32), dh);
+        if (valid && a.rope_cs) unrotate<CB>(dk, a.rope_cs + (long)key * (D / 2), half);
+        store_rows<D, CB>(stage, dk, a.scale, okp, ld, T - (k0 + wave * 32), dh);
     }
     add_busy(a.cu_busy ? a.cu_busy + 2048 : nullptr, true);
 }
@@ -1043,7 +1037,7 @@ hipError_t set_smem(K kern, int bytes) {
 template <int D>
 hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
-    const int smem = 2 * 2 * BT2 * D * 2;
+    const int smem = std::max(2 * 2 * BT2 * D * 2, 8 * STAGE_BYTES<D>);
     if (!configured) {
         hipError_t e = set_smem(attn_fwd_kernel<D>, smem);
         if (e != hipSuccess) return e;
@@ -1058,7 +1052,7 @@ hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
     constexpr bool PIPELINED = D > 64;                  // see attn_dkv_plain_kernel
     constexpr int DKV_SLOT = 2 * BT2 * D * 2 + 2 * BT2 * 4;
-    const int smem_dq = 2 * 2 * BT2 * D * 2, smem_dkv = (PIPELINED ? 3 : 2) * DKV_SLOT;
+    const int smem_dq = std::max(2 * 2 * BT2 * D * 2, 8 * STAGE_BYTES<D>), smem_dkv = (PIPELINED ? 3 : 2) * DKV_SLOT;
     if (!configured) {
         hipError_t e = set_smem(attn_dq_kernel<D>, smem_dq);
         if (e != hipSuccess) return e;
