@@ -292,6 +292,8 @@ __device__ __forceinline__ void unrotate(f32x16 (&g)[CB], const float2 *cs, int 
 // reads as a tile (the callers put a barrier in front).  dst: row 0, feature 0; rows_valid rows and dh features exist.
 template <int D>
 constexpr int STAGE_BYTES = 32 * (2 * D + 16);
+template <int D>
+constexpr int DKV_STAGE_BYTES = 4 * 32 * D * 2;       // the pipelined dK/dV kernel's K rows, behind its three slots
 template <int D, int CB>
 __device__ __forceinline__ void store_rows(uint8_t *stage, const f32x16 (&acc)[CB], float scale, bf16_t *dst, long ld,
                                            int rows_valid, int dh) {
@@ -636,17 +638,7 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     const RowInfo first = key_range(a.tok_info, k0, T), last = key_range(a.tok_info, min(k0 + BQ, T) - 1, T);
     const int qbeg = first.lo, qend = last.hi;
 
-    bf16x8 kf[KS], vf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        uint4 v = make_uint4(0, 0, 0, 0), w = v;
-        if (valid && ks * 16 + half * 8 < dh) {
-            v = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + g * dh + ks * 16 + half * 8);
-            w = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + nk + g * dh + ks * 16 + half * 8);
-        }
-        kf[ks] = *reinterpret_cast<bf16x8 *>(&v);
-        vf[ks] = *reinterpret_cast<bf16x8 *>(&w);
-    }
+    bf16x8 kf[KS], vf[KS];                             // this wavefront's K and V rows as MFMA operands (filled below)
     f32x16 dk[CB], dv[CB];
 #pragma unroll
     for (int c = 0; c < CB; ++c) { dk[c] = zero16(); dv[c] = zero16(); }
@@ -804,9 +796,27 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
         }
     };
 
-    copy_tile(smem, head_of(0), qt_of(0));
-    if (n_steps > 1) copy_tile(smem + SLOT, head_of(1), qt_of(1));
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // K and V rows of this wavefront's 32 keys: copied into LDS the way tiles are (whole rows per instruction, rows
+    // beyond the pack and features beyond the head's width as zeros) and read back as fragments; loading them
+    // straight into the fragment layout takes 16 loads of 16 bytes per row.  The V rows stand in the third slot, which
+    // the barrier below frees for the third tile, the K rows behind the slots.
+    {
+        constexpr int HALF_TILE = 32 * D * 2;
+        static_assert(4 * HALF_TILE <= SLOT && DKV_STAGE_BYTES<D> == 4 * HALF_TILE, "room for the staged K and V rows");
+        RowCopier<D, HALF_TILE / 1024> cp_kv;
+        cp_kv.init(0, ld, dh);
+        uint8_t *stage_k = smem + 3 * SLOT + wave * HALF_TILE, *stage_v = smem + 2 * SLOT + wave * HALF_TILE;
+        cp_kv.issue(rs_q, stage_k, k0 + wave * 32, ld, nq + g * dh);
+        cp_kv.issue(rs_q, stage_v, k0 + wave * 32, ld, nq + nk + g * dh);
+        copy_tile(smem, head_of(0), qt_of(0));
+        if (n_steps > 1) copy_tile(smem + SLOT, head_of(1), qt_of(1));
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = frag_k<D>(stage_k, l32, ks, half);
+            vf[ks] = frag_k<D>(stage_v, l32, ks, half);
+        }
+    }
     lds_barrier();
     int slot = 0;
     bool have0 = false;                                // block 0's scores of this step were computed by the step before
@@ -1052,7 +1062,7 @@ hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
     constexpr bool PIPELINED = D > 64;                  // see attn_dkv_plain_kernel
     constexpr int DKV_SLOT = 2 * BT2 * D * 2 + 2 * BT2 * 4;
-    const int smem_dq = std::max(2 * 2 * BT2 * D * 2, 8 * STAGE_BYTES<D>), smem_dkv = (PIPELINED ? 3 : 2) * DKV_SLOT;
+    const int smem_dq = std::max(2 * 2 * BT2 * D * 2, 8 * STAGE_BYTES<D>), smem_dkv = PIPELINED ? 3 * DKV_SLOT + DKV_STAGE_BYTES<D> : 2 * DKV_SLOT;
     if (!configured) {
         hipError_t e = set_smem(attn_dq_kernel<D>, smem_dq);
         if (e != hipSuccess) return e;
