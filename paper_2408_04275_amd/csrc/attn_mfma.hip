@@ -25,7 +25,10 @@
 // The backward pass is two kernels: dQ (same roles as forward; also writes D = rowsum(dO * O)),
 // then dK/dV with one KEY per lane, looping over the query tiles that can see the workgroup's
 // keys and over the query heads of the key/value head's group, so grouped-query gradients are
-// summed in registers and nothing needs atomics: results are deterministic.
+// summed in registers and nothing needs atomics: results are deterministic.  The dK/dV kernel has two forms: for
+// heads wider than 64 features a software-pipelined one (one wavefront per SIMD, the next block's scores computed
+// under the current block's softmax, whole 64-query steps skipped per wavefront), for 64-wide heads a plain one
+// that leaves room for two workgroups per compute unit.
 //
 // Head dimensions: the kernels are instantiated for 64 and 128 features; a head of another width (a
 // multiple of 16, e.g. 80) uses the next instantiation with the missing features read as zero and never
