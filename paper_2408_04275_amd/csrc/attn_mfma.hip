@@ -296,7 +296,11 @@ __device__ __forceinline__ void unrotate(f32x16 (&g)[CB], const float2 *cs, int 
 template <int D>
 constexpr int STAGE_BYTES = 32 * (2 * D + 16);
 template <int D>
-constexpr int DKV_STAGE_BYTES = 4 * 32 * D * 2;       // the pipelined dK/dV kernel's K rows, behind its three slots
+constexpr int ROWS32_BYTES = 32 * D * 2;              // 32 rows of one operand, staged in the tile layout
+template <int D>
+constexpr int DKV_STAGE_BYTES = 4 * ROWS32_BYTES<D>;  // the pipelined dK/dV kernel's K rows, behind its three slots
+template <int D>
+constexpr int DQ_LDS_BYTES = 2 * BT2 * D * 2 + 8 * 2 * ROWS32_BYTES<D>;   // the dQ kernel: first slot, then Q and dO rows of 8 wavefronts
 template <int D, int CB>
 __device__ __forceinline__ void store_rows(uint8_t *stage, const f32x16 (&acc)[CB], float scale, bf16_t *dst, long ld,
                                            int rows_valid, int dh) {
@@ -350,23 +354,56 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
     const int kbeg = first.lo, kend = last.hi;
 
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
+    // wavefronts 4..7 copy the K tile, wavefronts 0..3 the V tile
+    RowCopier<D, COPIES> cp;
+    cp.init((wave & 3) * COPIES, ld, dh);
+    auto copy_kv = [&](uint8_t *slot, int kt) {
+        if (wave >= 4) cp.issue(rs, slot, kt, ld, nq + g * dh);
+        else cp.issue(rs, slot + TILE, kt, ld, nq + nk + g * dh);
+    };
+    TrReader<D> tr;
+    tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
+
+    // This wavefront's 32 rows of Q, dO and O: copied into LDS the way tiles are (whole rows per instruction, rows
+    // beyond the pack and features beyond the head's width as zeros) and read back in the fragment layout; loading
+    // them straight into that layout takes 24 loads of 16 bytes per row and a fifth of the kernel's time on packs
+    // of short segments.  They stand behind the first slot (Q and dO side by side, O then in Q's place); the second
+    // slot, which they cover, is first written after the first step's barrier.
     bf16x8 qf[KS], dof[KS];
     float Dq = 0.f;
+    {
+        const __amdgpu_buffer_rsrc_t rs_do = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<bf16_t *>((const bf16_t *)a.d_o), 0, (int)(uint32_t)((size_t)T * nq * 2), 0x00020000);
+        const __amdgpu_buffer_rsrc_t rs_o = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<bf16_t *>((const bf16_t *)a.o), 0, (int)(uint32_t)((size_t)T * nq * 2), 0x00020000);
+        RowCopier<D, ROWS32_BYTES<D> / 1024> cp_q, cp_o;
+        cp_q.init(0, ld, dh);
+        cp_o.init(0, nq, dh);
+        uint8_t *st_q = smem + SLOT + wave * 2 * ROWS32_BYTES<D>, *st_do = st_q + ROWS32_BYTES<D>;
+        cp_q.issue(rs, st_q, q0 + wave * 32, ld, head * dh);
+        cp_o.issue(rs_do, st_do, q0 + wave * 32, nq, head * dh);
+        copy_kv(smem, kbeg);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        uint4 v = make_uint4(0, 0, 0, 0), w = v, x = v;
-        if (valid && ks * 16 + half * 8 < dh) {
-            v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * dh + ks * 16 + half * 8);
-            w = *reinterpret_cast<const uint4 *>((const bf16_t *)a.d_o + (long)q * nq + head * dh + ks * 16 + half * 8);
-            x = *reinterpret_cast<const uint4 *>((const bf16_t *)a.o + (long)q * nq + head * dh + ks * 16 + half * 8);
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks] = frag_k<D>(st_q, l32, ks, half);
+            dof[ks] = frag_k<D>(st_do, l32, ks, half);
         }
-        qf[ks] = *reinterpret_cast<bf16x8 *>(&v);
-        dof[ks] = *reinterpret_cast<bf16x8 *>(&w);
-        const uint32_t dw[4] = {w.x, w.y, w.z, w.w}, ow[4] = {x.x, x.y, x.z, x.w};
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // Q has been read: O may take its place
+        cp_o.issue(rs_o, st_q, q0 + wave * 32, nq, head * dh);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            Dq += __uint_as_float(dw[e] << 16) * __uint_as_float(ow[e] << 16);
-            Dq += __uint_as_float(dw[e] & 0xffff0000u) * __uint_as_float(ow[e] & 0xffff0000u);
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 of = frag_k<D>(st_q, l32, ks, half);
+            const uint4 w = *reinterpret_cast<const uint4 *>(&dof[ks]), x = *reinterpret_cast<const uint4 *>(&of);
+            const uint32_t dw[4] = {w.x, w.y, w.z, w.w}, ow[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                Dq += __uint_as_float(dw[e] << 16) * __uint_as_float(ow[e] << 16);
+                Dq += __uint_as_float(dw[e] & 0xffff0000u) * __uint_as_float(ow[e] & 0xffff0000u);
+            }
         }
     }
     Dq += __shfl_xor(Dq, 32, 64);
@@ -380,19 +417,6 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     for (int c = 0; c < CB; ++c) dq[c] = zero16();
     const float sl2 = a.scale * LOG2E;
 
-    const __amdgpu_buffer_rsrc_t rs =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
-    // wavefronts 4..7 copy the K tile, wavefronts 0..3 the V tile
-    RowCopier<D, COPIES> cp;
-    cp.init((wave & 3) * COPIES, ld, dh);
-    auto copy_kv = [&](uint8_t *slot, int kt) {
-        if (wave >= 4) cp.issue(rs, slot, kt, ld, nq + g * dh);
-        else cp.issue(rs, slot + TILE, kt, ld, nq + nk + g * dh);
-    };
-    TrReader<D> tr;
-    tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
-
-    copy_kv(smem, kbeg);
     int slot = 0;
     for (int kt = kbeg; kt < kend; kt += BT2, slot ^= 1) {
         const uint8_t *sK = smem + slot * SLOT, *sV = sK + TILE;
@@ -1065,7 +1089,7 @@ hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
     constexpr bool PIPELINED = D > 64;                  // see attn_dkv_plain_kernel
     constexpr int DKV_SLOT = 2 * BT2 * D * 2 + 2 * BT2 * 4;
-    const int smem_dq = std::max(2 * 2 * BT2 * D * 2, 8 * STAGE_BYTES<D>), smem_dkv = PIPELINED ? 3 * DKV_SLOT + DKV_STAGE_BYTES<D> : 2 * DKV_SLOT;
+    const int smem_dq = std::max(DQ_LDS_BYTES<D>, 8 * STAGE_BYTES<D>), smem_dkv = PIPELINED ? 3 * DKV_SLOT + DKV_STAGE_BYTES<D> : 2 * DKV_SLOT;
     if (!configured) {
         hipError_t e = set_smem(attn_dq_kernel<D>, smem_dq);
         if (e != hipSuccess) return e;
