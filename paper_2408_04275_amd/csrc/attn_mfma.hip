@@ -515,13 +515,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
     const int kbeg = first.lo, kend = last.hi;
 
-    bf16x8 qf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (valid && ks * 16 + half * 8 < dh) v = *reinterpret_cast<const uint4 *>(qkv + (long)q * ld + head * dh + ks * 16 + half * 8);
-        qf[ks] = *reinterpret_cast<bf16x8 *>(&v);
-    }
+    bf16x8 qf[KS];                                     // this wavefront's Q rows as the MFMA's column operand (filled below)
     f32x16 oacc[CB];
 #pragma unroll
     for (int c = 0; c < CB; ++c) oacc[c] = zero16();
@@ -540,7 +534,17 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     TrReader<D> tr;
     tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
 
-    copy_kv(smem, kbeg);
+    // The Q rows go through LDS like the dQ kernel's Q, dO and O rows (see there), behind the two slots.
+    {
+        RowCopier<D, ROWS32_BYTES<D> / 1024> cp_q;
+        cp_q.init(0, ld, dh);
+        uint8_t *st_q = smem + 2 * SLOT + wave * ROWS32_BYTES<D>;
+        cp_q.issue(rs, st_q, q0 + wave * 32, ld, head * dh);
+        copy_kv(smem, kbeg);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = frag_k<D>(st_q, l32, ks, half);
+    }
     int slot = 0;
     for (int kt = kbeg; kt < kend; kt += BT2, slot ^= 1) {
         const uint8_t *sK = smem + slot * SLOT;
@@ -1074,7 +1078,7 @@ hipError_t set_smem(K kern, int bytes) {
 template <int D>
 hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
-    const int smem = std::max(2 * 2 * BT2 * D * 2, 8 * STAGE_BYTES<D>);
+    const int smem = std::max(2 * 2 * BT2 * D * 2 + 8 * ROWS32_BYTES<D>, 8 * STAGE_BYTES<D>);
     if (!configured) {
         hipError_t e = set_smem(attn_fwd_kernel<D>, smem);
         if (e != hipSuccess) return e;
