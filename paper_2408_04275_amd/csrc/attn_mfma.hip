@@ -921,17 +921,7 @@ __global__ __launch_bounds__(256) void attn_dkv_plain_kernel(AttnArgs a) {
     const RowInfo first = key_range(a.tok_info, k0, T), last = key_range(a.tok_info, min(k0 + BQ, T) - 1, T);
     const int qbeg = first.lo, qend = last.hi;
 
-    bf16x8 kf[KS], vf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        uint4 v = make_uint4(0, 0, 0, 0), w = v;
-        if (valid && ks * 16 + half * 8 < dh) {
-            v = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + g * dh + ks * 16 + half * 8);
-            w = *reinterpret_cast<const uint4 *>(qkv + (long)key * ld + nq + nk + g * dh + ks * 16 + half * 8);
-        }
-        kf[ks] = *reinterpret_cast<bf16x8 *>(&v);
-        vf[ks] = *reinterpret_cast<bf16x8 *>(&w);
-    }
+    bf16x8 kf[KS], vf[KS];                             // this wavefront's K and V rows as MFMA operands (filled below)
     f32x16 dk[CB], dv[CB];
 #pragma unroll
     for (int c = 0; c < CB; ++c) { dk[c] = zero16(); dv[c] = zero16(); }
@@ -964,7 +954,21 @@ __global__ __launch_bounds__(256) void attn_dkv_plain_kernel(AttnArgs a) {
     {
     // the (head, query tile) pairs form one sequence; the copy of the next pair is in flight during this one
     const int tiles_per_head = (qend - qbeg + BT2 - 1) / BT2, n_steps = group * tiles_per_head;
-    copy_tile(smem, g * group, qbeg);
+    // the K and V rows go through LDS as in the pipelined kernel, behind the two slots
+    {
+        RowCopier<D, ROWS32_BYTES<D> / 1024> cp_kv;
+        cp_kv.init(0, ld, dh);
+        uint8_t *stage_k = smem + 2 * SLOT + wave * 2 * ROWS32_BYTES<D>, *stage_v = stage_k + ROWS32_BYTES<D>;
+        cp_kv.issue(rs_q, stage_k, k0 + wave * 32, ld, nq + g * dh);
+        cp_kv.issue(rs_q, stage_v, k0 + wave * 32, ld, nq + nk + g * dh);
+        copy_tile(smem, g * group, qbeg);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = frag_k<D>(stage_k, l32, ks, half);
+            vf[ks] = frag_k<D>(stage_v, l32, ks, half);
+        }
+    }
     int slot = 0;
     for (int step = 0; step < n_steps; ++step, slot ^= 1) {
         const int hh = step / tiles_per_head, qt = qbeg + (step % tiles_per_head) * BT2;
@@ -1093,7 +1097,7 @@ hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
     constexpr bool PIPELINED = D > 64;                  // see attn_dkv_plain_kernel
     constexpr int DKV_SLOT = 2 * BT2 * D * 2 + 2 * BT2 * 4;
-    const int smem_dq = std::max(DQ_LDS_BYTES<D>, 8 * STAGE_BYTES<D>), smem_dkv = PIPELINED ? 3 * DKV_SLOT + DKV_STAGE_BYTES<D> : 2 * DKV_SLOT;
+    const int smem_dq = std::max(DQ_LDS_BYTES<D>, 8 * STAGE_BYTES<D>), smem_dkv = PIPELINED ? 3 * DKV_SLOT + DKV_STAGE_BYTES<D> : 2 * DKV_SLOT + 2 * DKV_STAGE_BYTES<D>;
     if (!configured) {
         hipError_t e = set_smem(attn_dq_kernel<D>, smem_dq);
         if (e != hipSuccess) return e;
