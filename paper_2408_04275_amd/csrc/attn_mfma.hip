@@ -266,6 +266,14 @@ struct LdsSched {
     static constexpr int allowed_frag(int e) { return before(e) - 1 - idx_frag(e / PER_M); }
     static constexpr int allowed_d(int e) { return before(e) - 1 - idx_d(e >> 2); }
 };
+// 128-wide head (16 score MFMAs, one per element, five fragments ahead, a transposing read per element): in front of
+// element 0 seven operations are out; fragment 0 was the third, the first D values the second of them
+static_assert(LdsSched<16, 1, 5, 1>::before(0) == 7 && LdsSched<16, 1, 5, 1>::allowed_frag(0) == 4 &&
+              LdsSched<16, 1, 5, 1>::allowed_d(0) == 5, "issue order of the pipelined section, start");
+// element 0 adds a fragment, a transposing read and two reads for queries 8 .. 11; fragment 1 was the fourth operation
+static_assert(LdsSched<16, 1, 5, 1>::before(1) == 11 && LdsSched<16, 1, 5, 1>::allowed_frag(1) == 7 &&
+              LdsSched<16, 1, 5, 1>::idx_d(1) == 10 && LdsSched<16, 1, 5, 1>::allowed_d(4) == LdsSched<16, 1, 5, 1>::before(4) - 11,
+              "issue order of the pipelined section, first element");
 
 // Inverse rotary embedding of a gradient held in accumulator layout (the backward pass of the rotation that
 // was applied to q and k before the attention): feature f < D/2 pairs with f + D/2, which sit in the same
