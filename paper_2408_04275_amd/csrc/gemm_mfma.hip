@@ -12,8 +12,10 @@
 // input-gradient GEMMs need no transposed copies in HBM and no transposes in registers:
 //   * operands whose contraction index is contiguous in memory (A of NT/NN, B of NT) are kept as
 //     tile[row][64 k] (128 bytes = eight 16-byte units per row).  Unit u of row r is stored at unit
-//     position u ^ ((r ^ (r >> 3)) & 7), which spreads the MFMA fragment reads (32 lanes = 32 consecutive
-//     rows, same unit, 16 bytes each) over all banks;
+//     position u ^ (r & 7).  A fragment read (lane l: row l & 15, unit 4 s + (l >> 4), 16 bytes) is served 16
+//     lanes at a time, lanes 0-7 together with 24-31 and 8-15 with 16-23 (measured), at full rate if those fall
+//     into 16 distinct 16-byte slots modulo 256 bytes: rows 0-7 of one unit and rows 8-15 of its neighbour do
+//     with this swizzle (with (r ^ (r >> 3)) & 7, which suits 32-row fragments, they ran at half rate);
 //   * operands whose contraction index is the row index in memory (B of NN, A and B of TN) are kept as
 //     tile[64 k][256 rows] (512 bytes per k) and the fragments are formed by the transposing LDS read
 //     ds_read_b64_tr_b16; 32-byte chunks are XOR-swizzled with k & 3 against bank conflicts.
@@ -73,7 +75,7 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
     tn = (t % width) / gsize;
 }
 
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+__device__ __forceinline__ int swz(int row) { return row & 7; }
 
 // Global memory is read through raw buffer descriptors: an access whose byte offset lies at or beyond
 // the descriptor's size returns zero, which is how out-of-range rows and the K tail are zero-filled
@@ -102,8 +104,8 @@ __device__ __forceinline__ uint4 buf_load(__amdgpu_buffer_rsrc_t r, uint32_t off
 // K-contiguous operand: X[rows, K] row-major, copied global -> LDS without passing through registers
 // (buffer_load ... lds).  One such instruction writes lane l's 16 bytes to LDS base + 16 l, i.e. one
 // instruction fills 8 consecutive tile rows (1 KiB); the swizzled layout is obtained by choosing which
-// 16-byte unit of the row each lane fetches: lane l of the slab starting at row r0 fetches unit
-// (l & 7) ^ swz(r0 + (l >> 3)).  Wavefront w copies rows 32 i + 8 w .. + 7 for i = 0..7.
+// 16-byte unit of the row each lane fetches: lane l of the slab starting at row r0 (a multiple of 8) fetches unit
+// (l & 7) ^ swz(r0 + (l >> 3)) = (l & 7) ^ (l >> 3).  Wavefront w copies rows 32 i + 8 w .. + 7 for i = 0..7.
 typedef __attribute__((address_space(3))) void lds_void;
 struct LoaderKC {
     static constexpr int ITEM_LDS = 32 * 128;      // LDS bytes between consecutive items
@@ -113,17 +115,17 @@ struct LoaderKC {
     __device__ __forceinline__ uint32_t step_soff(int k0) const { return (uint32_t)k0 * 2u; }
     uint32_t off0, row_step;      // byte offset of this lane's row at i = 0 (without the unit); bytes per 32 rows
     uint32_t vo_e, vo_o;          // fast path: this lane's byte offset for even / odd i, without k0 and i * row_step
-    int kc0, K, slab0;            // unit column (elements) for even i (odd i: kc0 ^ 32); first slab's LDS offset
+    int kc0, K, slab0;            // unit column (elements) this lane fetches; first slab's LDS offset
     bool full;                    // all 256 rows of the tile exist
     __device__ __forceinline__ void init(const bf16_t *X, int ld, int row0, int nrows, int K_) {
         rs = make_rsrc(X, ((size_t)(nrows - 1) * ld + K_) * 2);
         const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
         K = K_;
-        kc0 = (((lane & 7) ^ (lane >> 3) ^ w) & 7) * 8;
+        kc0 = (((lane & 7) ^ (lane >> 3)) & 7) * 8;
         off0 = (uint32_t)((size_t)(row0 + w * 8 + (lane >> 3)) * ld * 2);
         row_step = (uint32_t)ld * 64u;
         vo_e = off0 + (uint32_t)kc0 * 2u;
-        vo_o = off0 + (uint32_t)(kc0 ^ 32) * 2u;
+        vo_o = vo_e;
         full = row0 + BM <= nrows;
         slab0 = __builtin_amdgcn_readfirstlane(w * 8 * 128);
         // one register per item, kept there (recomputed inside the K loop they would cost a vector add per copy)
@@ -142,7 +144,7 @@ struct LoaderKC {
             const int so = __builtin_amdgcn_readfirstlane(k0 * 2 + i * (int)row_step);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst, 16, (int)((i & 1) ? vo_o : vo_e), so, 0, 0);
         } else {
-            const int kc = kc0 ^ ((i & 1) * 32);
+            const int kc = kc0;
             const uint32_t off = k0 + kc < K ? off0 + i * row_step + (uint32_t)(k0 + kc) * 2u : OOB;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst, 16, (int)off, 0, 0, 0);
         }
@@ -311,9 +313,8 @@ void gemm_mfma_kernel(const GemmP p) {
 
     // fragment addressing (v_mfma_f32_16x16x32_bf16: lane l holds row l & 15, k = 8 (l >> 4) .. + 7 of a
     // 16-row, 32-deep fragment).  K-contiguous tile: row block i, slice s -> row 16 i + (l & 15), unit
-    // 4 s + (l >> 4); the swizzle of that row is that of row (l & 15) xor (2 i & 7), so 4 x 2 offsets per
-    // operand cover all blocks and slices, the block itself being an immediate offset of the read (for odd
-    // pairs of blocks, where 2 i & 7 repeats, only the immediate differs).  K-strided tile: the 16 lanes with
+    // 4 s + (l >> 4); the swizzle of that row is that of row l & 15, so two offsets per operand (one per slice)
+    // cover all blocks, the block itself being an immediate offset of the read.  K-strided tile: the 16 lanes with
     // the same l >> 4 form rows 0..15 of the block at k = 8 (l >> 4) ..; lane j of them supplies the address
     // of k-row (j >> 2), rows 4 (j & 3) .. + 3, for each of the two transposing reads.
     const int frow = lane & 15, fq = lane >> 4;
@@ -322,9 +323,9 @@ void gemm_mfma_kernel(const GemmP p) {
     for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int sl = 0; sl < 2; ++sl) {
-            if (A_KC) a_rd[c][sl] = (wm * 128 + frow) * 128 + (((sl * 4 + fq) ^ swz(wm * 128 + frow) ^ (2 * c)) << 4);
+            if (A_KC) a_rd[c][sl] = (wm * 128 + frow) * 128 + (((sl * 4 + fq) ^ swz(frow)) << 4);
             else a_rd[c][sl] = (sl * 32 + 8 * fq + (frow >> 2)) * 512 + (frow & 3) * 8 + ((wm * 8 + c) ^ (frow >> 2)) * 32;
-            if (B_KC) b_rd[c][sl] = (wn * 128 + frow) * 128 + (((sl * 4 + fq) ^ swz(wn * 128 + frow) ^ (2 * c)) << 4);
+            if (B_KC) b_rd[c][sl] = (wn * 128 + frow) * 128 + (((sl * 4 + fq) ^ swz(frow)) << 4);
             else b_rd[c][sl] = (sl * 32 + 8 * fq + (frow >> 2)) * 512 + (frow & 3) * 8 + ((wn * 8 + c) ^ (frow >> 2)) * 32;
         }
 
@@ -361,7 +362,7 @@ void gemm_mfma_kernel(const GemmP p) {
         constexpr int sl = decltype(SL)::value, f = decltype(F)::value;
         constexpr bool is_a = frag_is_a(f);
         constexpr int i = frag_index(f);
-        // K-contiguous: blocks i and i ^ 4 share the swizzle term; K-strided: one offset per pair (wave half, block)
+        // K-contiguous: all blocks share the swizzle term; K-strided: one offset per pair (wave half, block)
         constexpr int kc_imm = i * 16 * 128, c_kc = i & 3;
         constexpr int ks_imm = (i >> 2) * 4 * 32, c_ks = i & 3;     // chunk (wm * 8 + i): bits 0..1 in the offset, bit 2 immediate
         if (is_a) {
