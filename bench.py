@@ -24,19 +24,42 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published)
 PEAK_F32_TFLOPS = 157.3
-# HBM-side traffic per launch of each GEMM class on workload 3, in bytes, mean over the class's 4 launches per
-# step: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script (KiB per dispatch), each scaled by
-# what the same counter reads for a plain 512 MiB device copy (FETCH_SIZE reads half the bytes copied: x2;
-# WRITE_SIZE reads them all: x1).  FETCH_SIZE counts what the eight L2s request from the fabric, whether it
-# is then served by the memory-side cache or by HBM.  A hardware counter cannot be read from inside this
-# process, so the figures are carried here and re-measured whenever the GEMM kernel changes.
-MEASURED_TRAFFIC_CONFIG3 = {
-    "gemm_nt": (2 * (836756.3 + 395602.7) / 2 + (274581.4 + 65570.4) / 2) * 1024,
-    "gemm_nn": (2 * 610691.7 + 93211.0) * 1024,
-    # four full-round kernels per step, plus the K-cut last round of the 22016 x 4096 gradient and its reduction
-    "gemm_tn": (2 * (4 * 594075.2 + 82077.6 + 24590.7) + 4 * 95750.2 + 77382.6 + 12288.0) / 4 * 1024,
-}
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak (published)
 PAPER_CONTEXT = "paper: 54.7% MFU, 72B MLLM on 1172 GPUs (abstract; Section 7.1) -- other hardware, whole system"
+# HBM-side traffic of the GEMM classes on workload 3 is a hardware-counter figure (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# KiB per dispatch, scaled by what the same counters read for a plain copy).  A counter cannot be read from inside this
+# process, so the figure is carried over from the committed summary of those runs and labelled as such.
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "layer_config3_hbm_traffic.txt")
+
+
+def read_traffic_profile(path=TRAFFIC_PROFILE):
+    """Mean bytes per launch of each GEMM class (4 launches per step) from the counter summary's table: per kernel
+    FETCH_SIZE x 2 (the counter reads half the bytes fetched, per the copy calibration in the file) + WRITE_SIZE, in
+    KiB per dispatch, times its dispatches; the K-cut tail kernel and its reduction belong to the weight-gradient
+    class.  None if the file is missing or has no table."""
+    import re
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return None
+    rows = {}
+    for ln in lines:
+        m = re.match(r"^(\S.*?)\s{2,}([0-9.]+)\s+([0-9.]+)\s+(\d+)\b", ln)
+        if m:
+            rows[m.group(1).strip()] = (float(m.group(2)), float(m.group(3)), int(m.group(4)))
+    steps = next((n for k, (_, _, n) in rows.items() if k.startswith("attn_fwd")), 0)
+    if not steps:
+        return None
+    cls = {"gemm_nt": 0.0, "gemm_nn": 0.0, "gemm_tn": 0.0}
+    for k, (fetch, write, n) in rows.items():
+        kib = (2.0 * fetch + write) * n
+        if k.startswith("gemm_mfma_kernel<true, true"):
+            cls["gemm_nt"] += kib
+        elif k.startswith("gemm_mfma_kernel<true, false"):
+            cls["gemm_nn"] += kib
+        elif k.startswith("gemm_mfma_kernel<false, false") or k.startswith("tail_reduce_kernel"):
+            cls["gemm_tn"] += kib
+    return {k: v * 1024.0 / (4 * steps) for k, v in cls.items()}
 
 
 def gemm_flops_by_layout(shape, T):
@@ -78,8 +101,52 @@ def cpu_baseline(shape, cu, modes, W, seed, target_tokens):
     orc.layer_bwd(W, cache, dy)
     dt = time.perf_counter() - t0
     fl = wl.model_flops(shape, sub_cu, sub_modes)["fwd_bwd"]
+    model, physical = cpu_identity()
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {n} segments ({Ts} of {int(cu[-1])} tokens) of the same pack, fp64 numpy, {dt:.1f} s"}
+            "implementation": "fp64 numpy; matrix products through numpy's BLAS, everything else plain numpy",
+            "cpu_model": model, "physical_cores": physical, "logical_cpus": os.cpu_count(),
+            "sample": f"first {n} segments ({Ts} of {int(cu[-1])} tokens) of the same pack, forward + backward, {dt:.1f} s"}
+
+
+def cpu_identity():
+    """(model name, number of physical cores) from /proc/cpuinfo; (None, None) where it cannot be read."""
+    try:
+        text = open("/proc/cpuinfo").read()
+    except OSError:
+        return None, None
+    model, cores = None, set()
+    phys = core = None
+    for ln in text.splitlines() + [""]:
+        key, _, val = ln.partition(":")
+        key, val = key.strip(), val.strip()
+        if key == "model name" and model is None:
+            model = val
+        elif key == "physical id":
+            phys = val
+        elif key == "core id":
+            core = val
+        elif not ln.strip():
+            if core is not None:
+                cores.add((phys, core))
+            phys = core = None
+    return model, (len(cores) or None)
+
+
+def hbm_kernel_bytes(shape, T):
+    """Algorithmic bytes per step of the memory-bound kernel classes (every tensor a kernel has to read or write, once;
+    bf16 activations, fp32 statistics): the figures the achieved GB/s of those kernels are quoted on."""
+    H, F, F1 = shape.hidden, shape.ffn_hidden, shape.fc1_rows
+    e = 2 if shape.dtype == 1 else 4
+    A = T * H * e
+    enc = shape.kind == 1
+    rope_cols = (shape.n_heads + shape.n_kv_heads) * shape.head_dim
+    return {
+        "norm_fwd": 2 * (2 * A + 2 * T * 4),                                 # two launches: read x, write h, statistics
+        "norm_bwd": 2 * (4 * A + 2 * T * 4),                                 # two launches: read d_out, x, d_res, write d_in
+        "rope": 0 if enc else 2 * T * rope_cols * e + T * shape.head_dim * 4,   # q and k in place + the (cos, sin) table
+        "act_fwd": T * (F1 + F) * e,                                         # read the pre-activation, write m
+        "act_bwd": T * (F + 2 * F1) * e,                                     # read d_m and the pre-activation, write its gradient
+    }
 
 
 def main():
@@ -96,6 +163,9 @@ def main():
                     help="the oracle is timed on the leading segments of the pack up to about this many tokens (default: the whole 8192-token pack, 10-15 s)")
     ap.add_argument("--layers", type=int, default=1,
                     help="more than 1: time a stack of that many layers through mmtrain_stack_fwd / mmtrain_stack_bwd")
+    ap.add_argument("--group", choices=["span", "sample"], default="span",
+                    help="decoder workloads: 'span' = every text run / image span is a document of its own (default); 'sample' = "
+                         "the whole 8192-token sequence is one causal document")
     ap.add_argument("--recompute", action="store_true",
                     help="with --layers: keep only layer inputs in forward and recompute each layer in backward")
     args = ap.parse_args()
@@ -113,7 +183,7 @@ def main():
 
     shape = wl.SHAPES[args.config]
     seed = args.seed if args.seed is not None else (wl.longtail_seed() if args.config == 4 else 0)
-    cu, modes, kinds = wl.make_segments(args.config, seed)
+    cu, modes, kinds = wl.make_segments(args.config, seed, group=args.group)
     T = int(cu[-1])
     W = wl.make_weights(shape, seed)
     x, dy = wl.make_activations(shape, T, seed)
@@ -166,22 +236,28 @@ def main():
                           "higher_is_better": True, "dtype": "bf16" if shape.dtype == wl.BF16 else "f32", "data": "synthetic",
                           "config": {"workload": f"config {args.config}: {shape.name}", "graph": True}}))
         return
-    names = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd"]
+    names = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "norm_fwd", "norm_bwd", "rope", "act_fwd", "act_bwd"]
     # shader-clock and 100 MHz counters at the start and end of the first workgroup of the last bf16 GEMM launch
     clock_probe = torch.zeros(4, dtype=torch.int64, device="cuda")
 
     def timed_pass(steps, class_mask):
-        """`steps` steps with HIP events around the launches of the classes in class_mask; wall time per step and the
-        event-timed duration per step of each class."""
-        for k in range(5):
+        """`steps` steps with HIP events around the launches of the classes in class_mask and one event at every
+        step's start, between its forward and backward call and at its end (on the stream the library launches on).
+        Returns wall time per step, the event-timed duration per step of each class, and per step (forward ms,
+        backward ms)."""
+        for k in range(len(names)):
             mm.mmtrain_profile_read(k, reset=True)
         mm.mmtrain_profile_enable(class_mask)
         mm.mmtrain_profile_gemm_clock(clock_probe)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(2 * steps + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
+        marks[0].record()
+        for i in range(steps):
             check(runner.forward(), "mmtrain_layer_fwd")
+            marks[2 * i + 1].record()
             check(runner.backward(), "mmtrain_layer_bwd")
+            marks[2 * i + 2].record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         mm.mmtrain_profile_enable(0)
@@ -190,15 +266,23 @@ def main():
         for k, name in enumerate(names):
             ms, n = mm.mmtrain_profile_read(k, reset=True)
             res[name] = {"ms_per_step": ms / steps, "launches_per_step": n / steps}
-        return dt * 1e3 / steps, res
+        per_step = [(marks[2 * i].elapsed_time(marks[2 * i + 1]), marks[2 * i + 1].elapsed_time(marks[2 * i + 2]))
+                    for i in range(steps)]
+        return dt * 1e3 / steps, res, per_step
 
     # Breakdown pass (untimed for the headline): every class bracketed by events.  It names the dominant GEMM class;
-    # the timed region then carries events around that class only (36 event pairs per step cost about 1 % of the step).
-    _, prof = timed_pass(max(3, min(args.steps, 10)), mm.PROF_ALL)
+    # the timed region then carries events around that class only (an event pair costs a few microseconds on the stream).
+    # It also keeps the matrix cores busy for tens of milliseconds right in front of the timed region, so that the timed
+    # steps run at the clock the chip sustains rather than on its way there.
+    n_breakdown = max(3, min(args.steps, 10))
+    breakdown_ms, prof, _ = timed_pass(n_breakdown, mm.PROF_ALL)
     dom = max(("gemm_nt", "gemm_nn", "gemm_tn"), key=lambda n: prof[n]["ms_per_step"])
-    ms_per_step, timed = timed_pass(args.steps, 1 << names.index(dom))
+    ms_per_step, timed, per_step = timed_pass(args.steps, 1 << names.index(dom))
     prof[dom] = timed[dom]                       # the dominant class's figures come from the timed region itself
     tflops = flops["fwd_bwd"] / (ms_per_step * 1e-3) / 1e12
+    step_ms = np.array([f + b for f, b in per_step])
+    fwd_ms = np.array([f for f, _ in per_step])
+    bwd_ms = np.array([b for _, b in per_step])
 
     gf = gemm_flops_by_layout(shape, T)
     peak = PEAK_BF16_TFLOPS if shape.dtype == wl.BF16 else PEAK_F32_TFLOPS
@@ -210,28 +294,48 @@ def main():
     af, ab = prof["attn_fwd"]["ms_per_step"], prof["attn_bwd"]["ms_per_step"]
     kernels["attn_fwd"] = {"tflops": flops["attn_fwd"] / (af * 1e-3) / 1e12 if af > 0 else None, "ms_per_step": af}
     kernels["attn_bwd"] = {"tflops": 2 * flops["attn_fwd"] / (ab * 1e-3) / 1e12 if ab > 0 else None, "ms_per_step": ab}
+    # the memory-bound kernels: algorithmic bytes over event-timed duration, against the 8 TB/s HBM peak
+    hb = hbm_kernel_bytes(shape, T)
+    for name in ("norm_fwd", "norm_bwd", "rope", "act_fwd", "act_bwd"):
+        ms, n = prof[name]["ms_per_step"], prof[name]["launches_per_step"]
+        if n > 0 and ms > 0:
+            gbs = hb[name] / (ms * 1e-3) / 1e9
+            kernels[name] = {"gb_per_s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS, "ms_per_step": ms,
+                             "launches_per_step": n, "algorithmic_bytes_per_step": hb[name]}
     dom_launches = max(prof[dom]["launches_per_step"], 1)
+    traffic = read_traffic_profile() if args.config == 3 and args.group == "span" else None
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"], "peak": peak, "unit": "TFLOP/s",
                 "frac": (kernels[dom]["tflops"] or 0.0) / peak,
                 "avg_launch_ms": kernels[dom]["ms_per_step"] / dom_launches,
                 "flops_per_launch": gf[{"gemm_nt": "NT", "gemm_nn": "NN", "gemm_tn": "TN"}[dom]] / dom_launches,
-                "traffic": MEASURED_TRAFFIC_CONFIG3[dom] if args.config == 3 else None,
+                "traffic": traffic[dom] if traffic else None,
                 "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+                "traffic_source": "carried over from profiles/layer_config3_hbm_traffic.txt (separate rocprofv3 --pmc runs of "
+                                  "this script), not measured in this run" if traffic else None,
                 "algorithmic_bytes_per_launch": gemm_bytes_by_layout(shape, T) / dom_launches}
+    hw = wl.hardware_flops(shape, cu, modes) if shape.dtype == wl.BF16 else None
 
     out = {
         "metric": "layer fwd+bwd TFLOP/s and % bf16 MFMA peak on packed multimodal microbatch",
         "value": tflops, "unit": "TFLOP/s", "pct_of_peak": 100.0 * tflops / peak, "peak_tflops": peak,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        # per-step figures from events on the launch stream inside the timed region (ms_per_step is wall time / steps)
+        "median_ms": float(np.median(step_ms)), "min_ms": float(step_ms.min()), "max_ms": float(step_ms.max()),
+        "fwd_ms": {"median": float(np.median(fwd_ms)), "min": float(fwd_ms.min())},
+        "bwd_ms": {"median": float(np.median(bwd_ms)), "min": float(bwd_ms.min())},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == wl.BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"config {args.config}: {shape.name}", "seed": int(seed), "total_tokens": T,
-                   "n_segments": int(len(cu) - 1), "max_segment": int(np.diff(cu).max()),
+                   "n_segments": int(len(cu) - 1), "max_segment": int(np.diff(cu).max()), "document": args.group,
                    "hidden": shape.hidden, "heads": f"{shape.n_heads}/{shape.n_kv_heads}x{shape.head_dim}",
                    "ffn_hidden": shape.ffn_hidden, "model_tflop_per_step": flops["fwd_bwd"] / 1e12,
+                   # what the matrix cores execute: + score recomputation in backward, masked parts of diagonal and
+                   # boundary blocks, head-dimension padding (never credited in `value`)
+                   "hardware_tflop_per_step": hw["fwd_bwd"] / 1e12 if hw else None,
                    "attention_share": 3 * flops["attn_fwd"] / flops["fwd_bwd"]},
         "roofline": roofline, "kernels": kernels,
-        "kernels_note": f"{dom}: events inside the timed region; the others: untimed breakdown pass before it",
+        "kernels_note": f"{dom}: events inside the timed region; the others: untimed breakdown pass of {n_breakdown} steps "
+                        f"({breakdown_ms:.3f} ms per step with all events) right before it",
         # the clock a compute unit sustained during the last GEMM launch of the timed region (the published peak is quoted at 2400 MHz)
         "gemm_shader_clock_mhz": mm.gemm_clock_mhz(clock_probe),
         "context": PAPER_CONTEXT,

@@ -35,8 +35,11 @@
  * owns x, y, dy, dx, weights, gradients, `ctx` (opaque; written by fwd, read by
  * bwd; size from mmtrain_layer_ctx_bytes) and `workspace` (scratch; size from
  * mmtrain_layer_workspace_bytes; may be reused by later calls on the same
- * stream).  All of these are DEVICE pointers, 256-byte aligned, unless a field
- * says "host".  Host arrays need only stay valid during the call.
+ * stream).  All of these are DEVICE pointers unless a field says "host"; ctx and
+ * workspace must be 256-byte aligned and every tensor (x, y, dy, dx, weights,
+ * gradients, qkv, o, lse ...) at least 16-byte aligned -- the kernels move 16 bytes
+ * per lane -- else MMTRAIN_ERR_INVALID_ARG.  Host arrays need only stay valid
+ * during the call.
  *
  * Asynchrony.  Calls validate on the host, enqueue kernels on `hip_stream`
  * (a hipStream_t; NULL = the default stream) and return without synchronising.
@@ -196,9 +199,12 @@ MMTRAIN_API const char *mmtrain_status_string(int status);
  * ------------------------------------------------------------------------ */
 typedef enum {
     MMTRAIN_PROF_GEMM_NT = 0, MMTRAIN_PROF_GEMM_NN = 1, MMTRAIN_PROF_GEMM_TN = 2,
-    MMTRAIN_PROF_ATTN_FWD = 3, MMTRAIN_PROF_ATTN_BWD = 4
+    MMTRAIN_PROF_ATTN_FWD = 3, MMTRAIN_PROF_ATTN_BWD = 4,
+    /* the memory-bound kernels: normalisation forward / backward, rotary embedding, SwiGLU or GELU forward / backward */
+    MMTRAIN_PROF_NORM_FWD = 5, MMTRAIN_PROF_NORM_BWD = 6, MMTRAIN_PROF_ROPE = 7,
+    MMTRAIN_PROF_ACT_FWD = 8, MMTRAIN_PROF_ACT_BWD = 9
 } mmtrain_prof_kind;
-#define MMTRAIN_PROF_ALL 0x1f
+#define MMTRAIN_PROF_ALL 0x3ff
 MMTRAIN_API void mmtrain_profile_enable(int class_mask);
 MMTRAIN_API int mmtrain_profile_read(int32_t kind, double *total_ms, int64_t *launches, int reset);
 /* Load balance of the attention kernels over the compute units (measurement aid; bf16 storage only).  While
@@ -296,16 +302,22 @@ MMTRAIN_API int mmtrain_pipeline_1f1b(const double *fwd, const double *bwd, int3
  * smallest microbatch first, the p-1 smallest of the rest last (ascending), and in between, interval by interval, the
  * microbatches whose first-stage forward time comes closest to the interval's size (p-1 of them for the first
  * interval, each aiming at its share of what is still open; one for every later interval).  The interval sizes come
- * from the timeline of the microbatches placed so far, advanced by O(p) operations per placement.  Size of a
- * microbatch = its total time over all stages; ties go to the lowest index; the loop runs until no microbatch is
- * left (the listing's l-p iterations would hand out l+p-2 microbatches).
+ * from the timeline of the microbatches placed so far, advanced by O(p) operations per placement.  Ties go to the
+ * lowest index; the loop runs until no microbatch is left (the listing's l-p iterations would hand out l+p-2
+ * microbatches).
  *   fwd, bwd        as above
+ *   sizes           host, [l], may be NULL: the size of each microbatch for "smallest" -- the section defines it as the
+ *                   microbatch's computation time in the modality encoder and the generator (the modules whose time
+ *                   depends on the data), finite and >= 0.  NULL: forward + backward time of the first and the last stage,
+ *                   i.e. the encoder's and the generator's stage of a pipeline encoder | backbone stages | generator; a
+ *                   caller whose encoder or generator spans several stages passes the sum over those stages.
  *   order           host, [l], out: order[q] = index of the microbatch to run at position q
  *   intervals_seen  host, [l], out, may be NULL: the interval size each loop iteration worked with
  *   n_intervals     host, out, may be NULL: number of loop iterations (entries written to intervals_seen)
- * Host memory only, no GPU call.  Returns MMTRAIN_OK or MMTRAIN_ERR_INVALID_ARG (as above; NULL order with l > 0). */
-MMTRAIN_API int mmtrain_inter_reorder(const double *fwd, const double *bwd, int32_t p, int32_t l, int32_t *order,
-                                      double *intervals_seen, int32_t *n_intervals);
+ * Host memory only, no GPU call.  Returns MMTRAIN_OK or MMTRAIN_ERR_INVALID_ARG (as above; NULL order with l > 0; a
+ * negative, infinite or NaN size). */
+MMTRAIN_API int mmtrain_inter_reorder(const double *fwd, const double *bwd, int32_t p, int32_t l, const double *sizes,
+                                      int32_t *order, double *intervals_seen, int32_t *n_intervals);
 
 /* Optimizer step of mixed-precision training with sharded optimizer state (Section 3: ZeRO-1 and mixed
  * precision for the LLM backbone; Section 4.2's memory constraint counts the optimizer state of one shard

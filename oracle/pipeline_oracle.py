@@ -15,8 +15,10 @@ forward pass i + p - 1; the last p - 1 intervals have nothing left to fill them.
 the gradient from the second stage, so an interval's size does not depend on what is put into it.
 
 Readings (the listing and the text leave these open or disagree with each other):
-  * size of a microbatch (MIN, SELECTMIN): its total computation time over all stages, forward plus backward;
-    with a constant backbone this ranks microbatches as their encoder + generator time does.  Ties: lowest index.
+  * size of a microbatch (MIN, SELECTMIN): the section defines it as the microbatch's computation time in the
+    modality encoder and the generator.  Which stages those are is the caller's knowledge: `sizes` gives the size
+    per microbatch; without it the first and the last stage (forward plus backward) are taken as the encoder's and
+    the generator's.  Ties: lowest index.
   * SELECTMIN(mb, p - 1) returns successive minima, so the rear runs from the smallest upwards.
   * the loop bound: one microbatch first, p - 1 at the rear, p - 1 for the first interval and one for each later
     interval add up to l only when the loop runs l - 2p + 2 times, not the l - p times of the listing; the loop
@@ -114,13 +116,17 @@ def select_closest(fwd0, mb, k, interval):
     return chosen
 
 
-def inter_reorder(fwd, bwd):
-    """fwd, bwd: [p][l] durations of the microbatches in their original order.  Returns the new order
-    (original indices, 0-based) and the interval sizes GETINTERVAL reported, one per loop iteration."""
+def inter_reorder(fwd, bwd, sizes=None):
+    """fwd, bwd: [p][l] durations of the microbatches in their original order; sizes: [l] or None.  Returns the new
+    order (original indices, 0-based) and the interval sizes GETINTERVAL reported, one per loop iteration."""
     p, l = len(fwd), len(fwd[0]) if fwd else 0
     if l == 0:
         return [], []
-    size = [sum(fwd[s][j] + bwd[s][j] for s in range(p)) for j in range(l)]
+    if sizes is not None:
+        size = list(sizes)
+    else:
+        data_dependent = sorted({0, p - 1})                # the encoder's and the generator's stage
+        size = [sum(fwd[s][j] + bwd[s][j] for s in data_dependent) for j in range(l)]
     mb = list(range(l))
     first = min(mb, key=lambda m: (size[m], m))
     ret_mb = [first]

@@ -32,6 +32,7 @@ EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_
            "mmtrain_pipeline_1f1b", "mmtrain_inter_reorder", "mmtrain_profile_attn_busy",
            "mmtrain_profile_gemm_clock")
 PROF_GEMM_NT, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD = range(5)
+PROF_NORM_FWD, PROF_NORM_BWD, PROF_ROPE, PROF_ACT_FWD, PROF_ACT_BWD = range(5, 10)
 
 WEIGHT_FIELDS = ("norm1_w", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                  "norm2_w", "norm2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -124,7 +125,7 @@ def load_library() -> C.CDLL:
     lib.mmtrain_pipeline_1f1b.restype = C.c_int
     lib.mmtrain_pipeline_1f1b.argtypes = [P, P, I, I, P, C.POINTER(C.c_double), P]
     lib.mmtrain_inter_reorder.restype = C.c_int
-    lib.mmtrain_inter_reorder.argtypes = [P, P, I, I, P, P, C.POINTER(C.c_int32)]
+    lib.mmtrain_inter_reorder.argtypes = [P, P, I, I, P, P, P, C.POINTER(C.c_int32)]
     _lib = lib
     return lib
 
@@ -237,15 +238,21 @@ def mmtrain_pipeline_1f1b(fwd, bwd, order=None):
     return rc, makespan.value, intervals
 
 
-def mmtrain_inter_reorder(fwd, bwd):
-    """Algorithm 2 through the C ABI.  fwd, bwd: [p, l].  Returns (status, order[l], intervals_seen)."""
+def mmtrain_inter_reorder(fwd, bwd, sizes=None):
+    """Algorithm 2 through the C ABI.  fwd, bwd: [p, l]; sizes: [l] or None (first + last stage).
+    Returns (status, order[l], intervals_seen)."""
     import numpy as np
     fwd, bwd = _stage_times(fwd), _stage_times(bwd)
     p, l = fwd.shape
+    if sizes is not None:
+        sizes = np.ascontiguousarray(sizes, dtype=np.float64)
+        if sizes.shape != (l,):
+            raise ValueError("sizes must be [l]")
     order = np.full(l, -1, dtype=np.int32)
     seen = np.full(l, -1.0, dtype=np.float64)
     n = C.c_int32(0)
     rc = load_library().mmtrain_inter_reorder(fwd.ctypes.data if l else None, bwd.ctypes.data if l else None, p, l,
+                                              sizes.ctypes.data if sizes is not None and l else None,
                                               order.ctypes.data if l else None, seen.ctypes.data if l else None, C.byref(n))
     return rc, order, seen[:n.value]
 
@@ -334,7 +341,7 @@ def mmtrain_attn_bwd(desc, batch, qkv, o, lse, d_o, d_qkv, workspace, workspace_
                                            _ptr(d_qkv), _ptr(workspace), workspace_bytes, _stream(stream))
 
 
-PROF_ALL = 0x1f
+PROF_ALL = 0x3ff
 
 
 def mmtrain_profile_enable(class_mask) -> None:

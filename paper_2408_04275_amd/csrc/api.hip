@@ -3,6 +3,7 @@
 #include "../../include/mmtrain.h"
 #include "kernels.h"
 #include <cmath>
+#include <initializer_list>
 #include <vector>
 
 using namespace mmt;
@@ -88,11 +89,29 @@ int check_batch(const mmtrain_batch *b) {
     return MMTRAIN_OK;
 }
 
+// The kernels move 16 bytes per lane (vector loads and stores, direct-to-LDS copies): every tensor pointer must be
+// 16-byte aligned.  A misaligned one (a view such as tensor[1:]) is an argument error, not a memory fault.
+bool misaligned(std::initializer_list<const void *> ptrs) {
+    uintptr_t bits = 0;
+    for (const void *p : ptrs) bits |= (uintptr_t)p;
+    return (bits & 15) != 0;
+}
+
 int check_weights(const Dims &D, const mmtrain_layer_weights *w) {
     if (!w) return MMTRAIN_ERR_INVALID_ARG;
     if (!w->norm1_w || !w->w_qkv || !w->w_o || !w->norm2_w || !w->w_fc1 || !w->w_fc2) return MMTRAIN_ERR_INVALID_ARG;
     if (D.kind == MMTRAIN_ENCODER &&
         (!w->norm1_b || !w->b_qkv || !w->b_o || !w->norm2_b || !w->b_fc1 || !w->b_fc2))
+        return MMTRAIN_ERR_INVALID_ARG;
+    if (misaligned({w->norm1_w, w->norm1_b, w->w_qkv, w->b_qkv, w->w_o, w->b_o, w->norm2_w, w->norm2_b, w->w_fc1, w->b_fc1,
+                    w->w_fc2, w->b_fc2}))
+        return MMTRAIN_ERR_INVALID_ARG;
+    return MMTRAIN_OK;
+}
+
+int check_grads(const mmtrain_layer_grads *g) {
+    if (g && misaligned({g->norm1_w, g->norm1_b, g->w_qkv, g->b_qkv, g->w_o, g->b_o, g->norm2_w, g->norm2_b, g->w_fc1, g->b_fc1,
+                         g->w_fc2, g->b_fc2}))
         return MMTRAIN_ERR_INVALID_ARG;
     return MMTRAIN_OK;
 }
@@ -197,6 +216,8 @@ hipError_t fill_zero(void *p, size_t elems, int dtype, hipStream_t st) {
 }
 
 #define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return MMTRAIN_ERR_HIP; } while (0)
+// the same with the launch bracketed by the events of profiling class `kind` (when that class is enabled)
+#define HIP_TRY_TIMED(kind, st, expr) do { ProfScope ps_((kind), (st)); hipError_t e_ = (expr); if (e_ != hipSuccess) return MMTRAIN_ERR_HIP; } while (0)
 
 // ---- optional per-kernel-class timing with HIP events on the caller's stream -------------
 struct Profiler {
@@ -286,7 +307,7 @@ int mmtrain_layer_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     if ((rc = check_weights(D, W))) return rc;
     const int T = batch->total_tokens;
     if (T == 0) return MMTRAIN_OK;
-    if (!x || !y || !ctx || x == y) return MMTRAIN_ERR_INVALID_ARG;
+    if (!x || !y || !ctx || x == y || misaligned({x, y})) return MMTRAIN_ERR_INVALID_ARG;
     if (((uintptr_t)ctx | (uintptr_t)workspace) & 255) return MMTRAIN_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < mmtrain_layer_workspace_bytes(desc, T, batch->n_segments, 0))
         return MMTRAIN_ERR_WORKSPACE;
@@ -299,9 +320,9 @@ int mmtrain_layer_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     HIP_TRY(prep_tokens(batch->cu_seqlens_dev, batch->seg_mask_dev, batch->mask_mode, batch->n_segments, T, c.tok_seg,
                         c.tok_info, D.d, D.rope_base, c.rope_cs, st));
     // attention block
-    HIP_TRY(norm_fwd(D.dtype, enc, x, W->norm1_w, W->norm1_b, c.h1, c.mean1, c.rstd1, T, D.H, D.eps, st));
+    HIP_TRY_TIMED(MMTRAIN_PROF_NORM_FWD, st, norm_fwd(D.dtype, enc, x, W->norm1_w, W->norm1_b, c.h1, c.mean1, c.rstd1, T, D.H, D.eps, st));
     HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.nqkv, D.H, c.h1, D.H, W->w_qkv, D.H, c.qkv, D.nqkv, W->b_qkv), st));
-    if (!enc) HIP_TRY(rope_inplace(D.dtype, c.qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, false, st));
+    if (!enc) HIP_TRY_TIMED(MMTRAIN_PROF_ROPE, st, rope_inplace(D.dtype, c.qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, false, st));
     AttnArgs a = mk_attn(D, batch, c);
     {
         ProfScope ps(MMTRAIN_PROF_ATTN_FWD, st);
@@ -309,10 +330,10 @@ int mmtrain_layer_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     }
     HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.H, D.nq, c.o, D.nq, W->w_o, D.nq, c.y1, D.H, W->b_o, x), st));
     // MLP block
-    HIP_TRY(norm_fwd(D.dtype, enc, c.y1, W->norm2_w, W->norm2_b, c.h2, c.mean2, c.rstd2, T, D.H, D.eps, st));
+    HIP_TRY_TIMED(MMTRAIN_PROF_NORM_FWD, st, norm_fwd(D.dtype, enc, c.y1, W->norm2_w, W->norm2_b, c.h2, c.mean2, c.rstd2, T, D.H, D.eps, st));
     HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.F1, D.H, c.h2, D.H, W->w_fc1, D.H, c.pre, D.F1, W->b_fc1), st));
-    if (enc) HIP_TRY(gelu_fwd(D.dtype, c.pre, c.m, (long)T * D.F, st));
-    else HIP_TRY(swiglu_fwd(D.dtype, c.pre, c.m, T, D.F, st));
+    if (enc) HIP_TRY_TIMED(MMTRAIN_PROF_ACT_FWD, st, gelu_fwd(D.dtype, c.pre, c.m, (long)T * D.F, st));
+    else HIP_TRY_TIMED(MMTRAIN_PROF_ACT_FWD, st, swiglu_fwd(D.dtype, c.pre, c.m, T, D.F, st));
     HIP_TRY(gemm(D.dtype, mk(GEMM_NT, T, D.H, D.F, c.m, D.F, W->w_fc2, D.F, y, D.H, W->b_fc2, c.y1), st));
     return MMTRAIN_OK;
 }
@@ -326,6 +347,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     if ((rc = check_batch(batch))) return rc;
     if ((rc = check_weights(D, W))) return rc;
     if (flags & ~(MMTRAIN_BWD_ACCUMULATE_WGRAD | MMTRAIN_BWD_WGRAD_F32)) return MMTRAIN_ERR_INVALID_ARG;
+    if ((rc = check_grads(grads))) return rc;
     const int T = batch->total_tokens;
     const bool accum = flags & MMTRAIN_BWD_ACCUMULATE_WGRAD;
     const bool g32 = flags & MMTRAIN_BWD_WGRAD_F32;          // gradient buffers hold fp32
@@ -345,7 +367,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
         }
         return MMTRAIN_OK;
     }
-    if (!x || !dy || !ctx || !dx) return MMTRAIN_ERR_INVALID_ARG;
+    if (!x || !dy || !ctx || !dx || misaligned({x, dy, dx})) return MMTRAIN_ERR_INVALID_ARG;
     if (((uintptr_t)ctx | (uintptr_t)workspace) & 255) return MMTRAIN_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < mmtrain_layer_workspace_bytes(desc, T, batch->n_segments, 1))
         return MMTRAIN_ERR_WORKSPACE;
@@ -361,14 +383,14 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), w.split_ws, w.split_bytes), st));
     if (G.w_fc2) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     if (enc && G.b_fc1) {                         // the bias gradient is the column sum of what this kernel writes
-        HIP_TRY(gelu_bwd_colsum(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F1, w.part_c, st));
+        HIP_TRY_TIMED(MMTRAIN_PROF_ACT_BWD, st, gelu_bwd_colsum(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F1, w.part_c, st));
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.F1, G.b_fc1, accum, st));
-    } else if (enc) HIP_TRY(gelu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, (long)T * D.F, st));
-    else HIP_TRY(swiglu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F, st));
+    } else if (enc) HIP_TRY_TIMED(MMTRAIN_PROF_ACT_BWD, st, gelu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, (long)T * D.F, st));
+    else HIP_TRY_TIMED(MMTRAIN_PROF_ACT_BWD, st, swiglu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F, st));
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.H, D.F1, w.d_pre, D.F1, W->w_fc1, D.H, w.d_h, D.H), w.split_ws, w.split_bytes), st));
     if (G.w_fc1) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     // d_y1 = dy + norm2_bwd(d_h2); the same kernel sums the columns of dy (b_fc2's gradient) and of d_y1 (b_o's)
-    HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
+    HIP_TRY_TIMED(MMTRAIN_PROF_NORM_BWD, st, norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
                      G.norm2_w ? w.part_g : nullptr, (enc && G.norm2_b) ? w.part_b : nullptr,
                      (enc && G.b_o) ? w.part_din : nullptr, (enc && G.b_fc2) ? w.part_dres : nullptr, T, D.H, st));
     {
@@ -388,7 +410,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
         ProfScope ps(MMTRAIN_PROF_ATTN_BWD, st);
         HIP_TRY(attn_bwd(D.dtype, a, st));
     }
-    if (!enc && !fused_unrotate) HIP_TRY(rope_inplace(D.dtype, w.d_qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, true, st));
+    if (!enc && !fused_unrotate) HIP_TRY_TIMED(MMTRAIN_PROF_ROPE, st, rope_inplace(D.dtype, w.d_qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, true, st));
     if (enc && G.b_qkv) {
         HIP_TRY(colsum_partials(D.dtype, w.d_qkv, T, D.nqkv, D.nqkv, w.part_c, st));
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.nqkv, G.b_qkv, accum, st));
@@ -396,7 +418,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.H, D.nqkv, w.d_qkv, D.nqkv, W->w_qkv, D.H, w.d_h, D.H), w.split_ws, w.split_bytes), st));
     if (G.w_qkv) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
     // dx = d_y1 + norm1_bwd(d_h1)
-    HIP_TRY(norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
+    HIP_TRY_TIMED(MMTRAIN_PROF_NORM_BWD, st, norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
                      G.norm1_w ? w.part_g : nullptr, (enc && G.norm1_b) ? w.part_b : nullptr, nullptr, nullptr, T, D.H, st));
     {
         const float *parts[2] = {w.part_g, w.part_b};
@@ -457,7 +479,7 @@ int mmtrain_stack_fwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mm
     for (int l = 0; l < n_layers; ++l)
         if ((rc = check_weights(D, &weights[l]))) return rc;
     if (batch->total_tokens == 0) return MMTRAIN_OK;
-    if (!x || !y || !ctx || x == y || (((uintptr_t)ctx | (uintptr_t)workspace) & 255)) return MMTRAIN_ERR_INVALID_ARG;
+    if (!x || !y || !ctx || x == y || misaligned({x, y}) || (((uintptr_t)ctx | (uintptr_t)workspace) & 255)) return MMTRAIN_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < p.ws_bytes(false)) return MMTRAIN_ERR_WORKSPACE;
     uint8_t *acts = (uint8_t *)ctx, *ctxs = acts + (size_t)(n_layers - 1) * p.act;
     for (int l = 0; l < n_layers; ++l) {
@@ -482,8 +504,10 @@ int mmtrain_stack_bwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mm
     if ((rc = plan_stack(desc, n_layers, batch->total_tokens, batch->n_segments, flags, MMTRAIN_STACK_RECOMPUTE | bwd_flags, p)))
         return rc;
     if (!weights) return MMTRAIN_ERR_INVALID_ARG;
-    for (int l = 0; l < n_layers; ++l)
+    for (int l = 0; l < n_layers; ++l) {
         if ((rc = check_weights(D, &weights[l]))) return rc;
+        if (grads && (rc = check_grads(&grads[l]))) return rc;
+    }
     const uint32_t lflags = flags & bwd_flags;
     if (batch->total_tokens == 0) {                 // an empty pack: every layer's gradients are zero (or left as they are)
         for (int l = 0; l < n_layers; ++l)
@@ -491,7 +515,7 @@ int mmtrain_stack_bwd(const mmtrain_layer_desc *desc, int32_t n_layers, const mm
                                         workspace_bytes, hip_stream))) return rc;
         return MMTRAIN_OK;
     }
-    if (!x || !dy || !ctx || !dx || (((uintptr_t)ctx | (uintptr_t)workspace) & 255)) return MMTRAIN_ERR_INVALID_ARG;
+    if (!x || !dy || !ctx || !dx || misaligned({x, dy, dx}) || (((uintptr_t)ctx | (uintptr_t)workspace) & 255)) return MMTRAIN_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < p.ws_bytes(true)) return MMTRAIN_ERR_WORKSPACE;
     uint8_t *acts = (uint8_t *)ctx, *ctxs = acts + (size_t)(n_layers - 1) * p.act;
     uint8_t *ws = (uint8_t *)workspace;
@@ -578,13 +602,17 @@ size_t mmtrain_attn_workspace_bytes(int32_t total_tokens, int32_t n_segments, in
     return ((b.off + 255) & ~size_t(255)) + 256;
 }
 
+// `tensors`: the call's device tensors, all required and 16-byte aligned (checked before anything is enqueued)
 static int attn_common(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, Dims &D, void *workspace,
-                       size_t workspace_bytes, AttnArgs &a, hipStream_t st) {
+                       size_t workspace_bytes, std::initializer_list<const void *> tensors, AttnArgs &a, hipStream_t st) {
     int rc = check_desc(desc, D);
     if (rc) return rc;
     if ((rc = check_batch(batch))) return rc;
     const int T = batch->total_tokens;
     if (T == 0) return MMTRAIN_OK;
+    for (const void *p : tensors)
+        if (!p) return MMTRAIN_ERR_INVALID_ARG;
+    if (misaligned(tensors)) return MMTRAIN_ERR_INVALID_ARG;
     if ((uintptr_t)workspace & 255) return MMTRAIN_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < mmtrain_attn_workspace_bytes(T, batch->n_segments, D.nh))
         return MMTRAIN_ERR_WORKSPACE;
@@ -608,9 +636,8 @@ int mmtrain_attn_fwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch,
     Dims D;
     AttnArgs a;
     hipStream_t st = (hipStream_t)hip_stream;
-    int rc = attn_common(desc, batch, D, workspace, workspace_bytes, a, st);
+    int rc = attn_common(desc, batch, D, workspace, workspace_bytes, {qkv, o, lse}, a, st);
     if (rc || batch->total_tokens == 0) return rc;
-    if (!qkv || !o || !lse) return MMTRAIN_ERR_INVALID_ARG;
     a.qkv = qkv; a.o = o; a.lse = lse;
     HIP_TRY(attn_fwd(D.dtype, a, st));
     return MMTRAIN_OK;
@@ -622,9 +649,8 @@ int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch,
     Dims D;
     AttnArgs a;
     hipStream_t st = (hipStream_t)hip_stream;
-    int rc = attn_common(desc, batch, D, workspace, workspace_bytes, a, st);
+    int rc = attn_common(desc, batch, D, workspace, workspace_bytes, {qkv, o, lse, d_o, d_qkv}, a, st);
     if (rc || batch->total_tokens == 0) return rc;
-    if (!qkv || !o || !lse || !d_o || !d_qkv) return MMTRAIN_ERR_INVALID_ARG;
     a.qkv = qkv; a.o = const_cast<void *>(o); a.lse = const_cast<float *>(lse); a.d_o = d_o; a.d_qkv = d_qkv;
     HIP_TRY(attn_bwd(D.dtype, a, st));
     return MMTRAIN_OK;
@@ -661,12 +687,13 @@ int mmtrain_pipeline_1f1b(const double *fwd, const double *bwd, int32_t p, int32
     return pipeline_1f1b(fwd, bwd, p, l, order, makespan, intervals) ? MMTRAIN_ERR_INVALID_ARG : MMTRAIN_OK;
 }
 
-int mmtrain_inter_reorder(const double *fwd, const double *bwd, int32_t p, int32_t l, int32_t *order,
+int mmtrain_inter_reorder(const double *fwd, const double *bwd, int32_t p, int32_t l, const double *sizes, int32_t *order,
                           double *intervals_seen, int32_t *n_intervals) {
     if (p < 1 || l < 0 || (l > 0 && (!fwd || !bwd || !order))) return MMTRAIN_ERR_INVALID_ARG;
     if ((size_t)p * (size_t)l > (size_t)1 << 28) return MMTRAIN_ERR_INVALID_ARG;
     if (!durations_ok(fwd, (size_t)p * l) || !durations_ok(bwd, (size_t)p * l)) return MMTRAIN_ERR_INVALID_ARG;
-    inter_reorder(fwd, bwd, p, l, order, intervals_seen, n_intervals);
+    if (sizes && !durations_ok(sizes, (size_t)l)) return MMTRAIN_ERR_INVALID_ARG;
+    inter_reorder(fwd, bwd, p, l, sizes, order, intervals_seen, n_intervals);
     return MMTRAIN_OK;
 }
 

@@ -70,8 +70,8 @@ void attn_tile_order(const int32_t *cu_host, const uint8_t *modes_host, int defa
 // fwd / bwd: [p][l] durations by original microbatch index; order: [l] (null: identity); return 0 on success
 int pipeline_1f1b(const double *fwd, const double *bwd, int p, int l, const int32_t *order, double *makespan,
                   double *intervals /* [l] or null */);
-int inter_reorder(const double *fwd, const double *bwd, int p, int l, int32_t *order, double *intervals_seen /* [l] or null */,
-                  int32_t *n_seen /* or null */);
+int inter_reorder(const double *fwd, const double *bwd, int p, int l, const double *sizes /* [l] or null */, int32_t *order,
+                  double *intervals_seen /* [l] or null */, int32_t *n_seen /* or null */);
 // attn_simple.hip: fp32 arithmetic on the vector ALUs, any storage dtype
 hipError_t attn_simple_fwd(int dtype, const AttnArgs &a, hipStream_t st);
 hipError_t attn_simple_bwd(int dtype, const AttnArgs &a, hipStream_t st);

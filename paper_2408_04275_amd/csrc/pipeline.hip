@@ -14,7 +14,11 @@
 // there.  The same sweep serves as GETINTERVAL: cursors stop in front of a position that is still empty, so placing a
 // microbatch costs O(p) further operations, and interval i never depends on an empty position (interval 1 aside,
 // which is the first microbatch's way through stages 2 .. p and back).
-// Choices the listing leaves open: a microbatch's size is its total time over all stages; equal sizes and equal
+// A microbatch's size (MIN, SELECTMIN) is, as the section defines it, its computation time in the modality encoder
+// and the generator, the modules whose time varies with the data: the caller passes it per microbatch, or, without
+// one, it is taken as the forward + backward time of the first and the last stage (the encoder's and the generator's
+// stage of a three-module pipeline).
+// Choices the listing leaves open: equal sizes and equal
 // distances go to the lowest index; the rear is in ascending order of size; the loop runs while microbatches remain
 // (the listing's l - p iterations would hand out more microbatches than there are); when k microbatches are picked
 // for one interval, each pick aims at the volume still open divided by the picks still to make.
@@ -105,13 +109,16 @@ int pipeline_1f1b(const double *fwd, const double *bwd, int p, int l, const int3
     return 0;
 }
 
-int inter_reorder(const double *fwd, const double *bwd, int p, int l, int32_t *order, double *intervals_seen,
-                  int32_t *n_seen) {
+int inter_reorder(const double *fwd, const double *bwd, int p, int l, const double *sizes, int32_t *order,
+                  double *intervals_seen, int32_t *n_seen) {
     if (n_seen) *n_seen = 0;
     if (l == 0) return 0;
     std::vector<double> size(l, 0.0);
-    for (int s = 0; s < p; ++s)
-        for (int j = 0; j < l; ++j) size[j] += fwd[(size_t)s * l + j] + bwd[(size_t)s * l + j];
+    for (int j = 0; j < l; ++j) {
+        if (sizes) { size[j] = sizes[j]; continue; }
+        size[j] = fwd[j] + bwd[j];                                                   // first stage: the modality encoder
+        if (p > 1) size[j] += fwd[(size_t)(p - 1) * l + j] + bwd[(size_t)(p - 1) * l + j];   // last stage: the generator
+    }
     std::vector<char> taken(l, 0);
     auto take_min = [&]() {
         int best = -1;

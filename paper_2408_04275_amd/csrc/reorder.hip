@@ -47,31 +47,66 @@ int intra_reorder(const double *sizes, int n, int m, int32_t *order, int32_t *gr
 // Work of the attention kernels' tiles, from the host copy of the segment offsets:
 //   query tile (FQ queries): 64-key steps between the first query's segment start and the last query's last key;
 //   key tile (BQ keys): 64-query steps between the first key's first query and the last key's segment end.
+// Runs on the launch path of every attention call, so it allocates nothing: the segments of the tiles' first and
+// last tokens come from one walk over the offsets (tile starts increase), the two tables are sorted in place, and
+// the result of the last pack is kept per thread -- forward, backward and every layer of a stack pass the same
+// pack, which is recognised by a hash of its offsets and mask modes.
+namespace {
+struct TileOrderCache {
+    uint64_t key = 0;
+    int S = -1, T = -1, default_mode = -1, use_order = 0;
+    uint8_t order_q[sizeof(AttnArgs::order_q)], order_k[sizeof(AttnArgs::order_k)];
+};
+thread_local TileOrderCache g_tile_order;
+
+uint64_t pack_hash(const int32_t *cu, const uint8_t *modes, int S) {
+    uint64_t h = 1469598103934665603ull;                       // FNV-1a over the offsets, then the modes
+    auto mix = [&](uint64_t v) { h = (h ^ v) * 1099511628211ull; };
+    for (int s = 0; s <= S; ++s) mix((uint32_t)cu[s]);
+    mix(modes ? 0x100 : 0x200);
+    if (modes) for (int s = 0; s < S; ++s) mix(modes[s]);
+    return h;
+}
+
+// idx[0..n) = 0..n-1 sorted by weight, descending, equal weights in index order (insertion sort: n <= 128)
+void order_desc(const int *w, int n, uint8_t *idx) {
+    for (int i = 0; i < n; ++i) {
+        int j = i;
+        while (j > 0 && w[idx[j - 1]] < w[i]) { idx[j] = idx[j - 1]; --j; }
+        idx[j] = (uint8_t)i;
+    }
+}
+}  // namespace
+
 void attn_tile_order(const int32_t *cu, const uint8_t *modes, int default_mode, int S, int T, AttnArgs &a) {
-    constexpr int FQ = 256, BK = 128;
+    constexpr int FQ = 256, BK = 128, MAXQ = (int)sizeof(a.order_q), MAXK = (int)sizeof(a.order_k);
     const int nq = (T + FQ - 1) / FQ, nk = (T + BK - 1) / BK;
     a.use_order = 0;
-    if (nq > (int)sizeof(a.order_q) || nk > (int)sizeof(a.order_k) || T == 0) return;
-    std::vector<int> seg_of(T);
-    for (int s = 0; s < S; ++s)
-        for (int t = cu[s]; t < cu[s + 1]; ++t) seg_of[t] = s;
-    auto bidir = [&](int s) { return (modes ? modes[s] : default_mode) == MASK_BIDIR; };
-    std::vector<double> wq(nq), wk(nk);
-    for (int i = 0; i < nq; ++i) {
-        const int q0 = i * FQ, q1 = std::min(q0 + FQ, T) - 1;
-        const int lo = cu[seg_of[q0]], hi = bidir(seg_of[q1]) ? cu[seg_of[q1] + 1] : q1 + 1;
-        wq[i] = (hi - lo + 63) / 64;
+    if (nq > MAXQ || nk > MAXK || T == 0) return;              // more tiles than the tables hold: index order
+    TileOrderCache &c = g_tile_order;
+    const uint64_t key = pack_hash(cu, modes, S);
+    if (!(c.key == key && c.S == S && c.T == T && c.default_mode == default_mode)) {
+        auto bidir = [&](int s) { return (modes ? modes[s] : default_mode) == MASK_BIDIR; };
+        int wq[MAXQ], wk[MAXK];
+        int s = 0;                                             // segment of token t: the tokens asked for only increase
+        auto seg_of = [&](int t) { while (cu[s + 1] <= t) ++s; return s; };
+        for (int i = 0; i < nq; ++i) {
+            const int q0 = i * FQ, q1 = std::min(q0 + FQ, T) - 1;
+            const int lo = cu[seg_of(q0)], s1 = seg_of(q1), hi = bidir(s1) ? cu[s1 + 1] : q1 + 1;
+            wq[i] = (hi - lo + 63) / 64;
+        }
+        s = 0;
+        for (int i = 0; i < nk; ++i) {
+            const int k0 = i * BK, k1 = std::min(k0 + BK, T) - 1;
+            const int s0 = seg_of(k0), lo = bidir(s0) ? cu[s0] : k0, hi = cu[seg_of(k1) + 1];
+            wk[i] = (hi - lo + 63) / 64;
+        }
+        order_desc(wq, nq, c.order_q);
+        order_desc(wk, nk, c.order_k);
+        c.key = key; c.S = S; c.T = T; c.default_mode = default_mode; c.use_order = 1;
     }
-    for (int i = 0; i < nk; ++i) {
-        const int k0 = i * BK, k1 = std::min(k0 + BK, T) - 1;
-        const int lo = bidir(seg_of[k0]) ? cu[seg_of[k0]] : k0, hi = cu[seg_of[k1] + 1];
-        wk[i] = (hi - lo + 63) / 64;
-    }
-    std::vector<int> idx;
-    sort_desc(wq.data(), nq, idx);
-    for (int i = 0; i < nq; ++i) a.order_q[i] = (uint8_t)idx[i];
-    sort_desc(wk.data(), nk, idx);
-    for (int i = 0; i < nk; ++i) a.order_k[i] = (uint8_t)idx[i];
+    for (int i = 0; i < nq; ++i) a.order_q[i] = c.order_q[i];
+    for (int i = 0; i < nk; ++i) a.order_k[i] = c.order_k[i];
     a.use_order = 1;
 }
 

@@ -146,12 +146,17 @@ def longtail_seed(total: int = 8192, dominant: int = 6000) -> int:
         seed += 1
 
 
-def make_segments(config: int, seed: int = 0, image_bidir: bool = False):
+def make_segments(config: int, seed: int = 0, image_bidir: bool = False, group: str = "span"):
     """Segment layout of one packed microbatch.
 
     Returns (cu_seqlens int32 [S+1], modes uint8 [S], kinds list[str]).
     `image_bidir` (decoder workloads only) gives image spans bidirectional
     attention instead of causal; encoder packs are always bidirectional.
+    `group` says what a "document" is for the decoder workloads 3-5: "span" (default) makes every text run and
+    every image span a segment of its own; "sample" takes the whole fixed-length sequence as ONE causal document,
+    the paper's training sample (Section 2.3: a sample is one sequence of interleaved subsequences), in which
+    text attends to the images in front of it.  Same spans, same tokens; only cu_seqlens and with it the number
+    of unmasked pairs (the attention FLOP count) change.
     """
     rng = np.random.default_rng(seed)
     if config == 1:
@@ -165,6 +170,10 @@ def make_segments(config: int, seed: int = 0, image_bidir: bool = False):
         lengths, kinds = _longtail_pack(rng, SHAPES[4].max_tokens)
     else:
         raise ValueError(f"unknown config {config}")
+    if group not in ("span", "sample"):
+        raise ValueError(f"unknown grouping {group!r}")
+    if group == "sample" and config in (3, 4, 5):
+        lengths, kinds = [int(sum(lengths))], ["sample"]
     modes = np.zeros(len(lengths), dtype=np.uint8)
     for i, k in enumerate(kinds):
         if SHAPES[config].kind == ENCODER or (image_bidir and k == "image"):
@@ -249,3 +258,52 @@ def model_flops(shape: LayerShape, cu: np.ndarray, modes: np.ndarray) -> Dict[st
     attn_fwd = 4.0 * shape.head_dim * shape.n_heads * attention_pairs(cu, modes)
     return {"gemm_fwd": gemm_fwd, "attn_fwd": attn_fwd,
             "fwd": gemm_fwd + attn_fwd, "fwd_bwd": 3.0 * (gemm_fwd + attn_fwd)}
+
+
+def hardware_flops(shape: LayerShape, cu: np.ndarray, modes: np.ndarray) -> Dict[str, float]:
+    """FLOPs the matrix cores actually execute for one forward + backward, as opposed to model_flops: the GEMMs
+    as they are, attention with everything the tiled kernels compute and model FLOPs do not credit --
+    the masked part of every 32 x 32 block that is not skipped as a whole (diagonal and segment-boundary blocks),
+    the recomputation of the scores in both backward kernels (dQ kernel: scores, dP, dQ = 6 d per pair;
+    dK/dV kernel: scores, dP, dV, dK = 8 d per pair) and the zero padding of head dimensions that are not 64 or 128.
+    The block rules restate the kernels' launch geometry: forward and dQ: 256 queries per workgroup walk the
+    keys [first query's first key, last query's last key) in 64-key steps, and a wavefront (32 queries) runs a 32-key
+    block unless the block lies outside [its first query's first key, its last query's last key); dK/dV: 128 keys per
+    workgroup, 32 per wavefront, walk the queries in 64-query steps, skipping per block (64-wide heads) or per step
+    (wider heads)."""
+    cu = np.asarray(cu, dtype=np.int64)
+    T = int(cu[-1])
+    d_pad = 64 if shape.head_dim <= 64 else 128
+    seg = np.repeat(np.arange(len(cu) - 1), np.diff(cu))
+    start, end = cu[seg], cu[seg + 1]
+    bidir = np.asarray(modes)[seg] == BIDIR
+    tok = np.arange(T)
+    q_lo, q_hi = start, np.where(bidir, end, tok + 1)             # keys a query sees
+    k_lo, k_hi = np.where(bidir, start, tok), end                 # queries that see a key
+    blocks_q = 0                                                  # 32 x 32 blocks run by the forward / dQ kernels
+    for q0 in range(0, T, 256):
+        kbeg, kend = int(q_lo[q0]), int(q_hi[min(q0 + 256, T) - 1])
+        for w0 in range(q0, min(q0 + 256, T), 32):
+            w1 = min(w0 + 32, T) - 1
+            lo, hi = int(q_lo[w0]), int(q_hi[w1])
+            for kb in range(kbeg, kend + (-(kend - kbeg)) % 64, 32):
+                blocks_q += kb < hi and kb + 32 > lo
+    blocks_k = 0                                                  # ... by the dK/dV kernel
+    per_step = d_pad > 64
+    for k0 in range(0, T, 128):
+        qbeg, qend = int(k_lo[k0]), int(k_hi[min(k0 + 128, T) - 1])
+        for w0 in range(k0, min(k0 + 128, T), 32):
+            w1 = min(w0 + 32, T) - 1
+            lo, hi = int(k_lo[w0]), int(k_hi[w1])
+            for qt in range(qbeg, qend, 64):
+                if per_step:
+                    blocks_k += 2 * (qt < hi and qt + 64 > lo)
+                else:
+                    blocks_k += (qt < hi and qt + 32 > lo) + (qt + 32 < hi and qt + 64 > lo)
+    pairs_q, pairs_k = 1024.0 * blocks_q, 1024.0 * blocks_k
+    nh = shape.n_heads
+    m = model_flops(shape, cu, modes)
+    attn_fwd = 4.0 * d_pad * nh * pairs_q
+    attn_bwd = 6.0 * d_pad * nh * pairs_q + 8.0 * d_pad * nh * pairs_k
+    return {"gemm_fwd_bwd": 3.0 * m["gemm_fwd"], "attn_fwd": attn_fwd, "attn_bwd": attn_bwd,
+            "fwd_bwd": 3.0 * m["gemm_fwd"] + attn_fwd + attn_bwd}

@@ -1,79 +1,86 @@
-"""What bf16 storage alone costs: the oracle with a bf16 rounding inserted wherever a layer that
-feeds bf16 matrix cores must store a tensor (every GEMM operand and GEMM output), compared with
-the unrounded oracle.  No GPU involved.
+"""What bf16 storage alone costs (oracle/bf16_storage.py): the oracle with a bf16 rounding inserted wherever a layer
+that feeds bf16 matrix cores must store a tensor, compared with the unrounded oracle.  No GPU involved.
 
-This fixes the parity bars from the arithmetic: the floor-at-RMS element-wise relative error of
-such a pipeline exceeds 2e-2 on weight gradients with no mistake anywhere, while the error relative
-to the tensor's scale stays far below 2e-2.  The bars in paper_2408_04275_amd.parity sit above this
-floor with a margin of less than 2x."""
+Pins of the emulation itself: its rounding against the library's bf16 conversion; with the rounding switched off it
+IS the oracle (decoder, encoder, stack), so every difference it shows comes from the roundings alone.
+Then the facts the parity bars rest on: a floor-at-RMS element-wise relative error above 2e-2 with no mistake
+anywhere, an error relative to the tensor's scale far below 2e-2, growth with the branch-to-residual ratio, and that
+the stored floors of the full-size cases (tests/golden/bf16_floor.json) belong to the inputs the tests draw today."""
+import json
+import os
+
 import numpy as np
+import pytest
+import torch
 
+import full_cases
+from oracle import bf16_storage
 from oracle import layer_oracle as orc
 from paper_2408_04275_amd import parity
 from paper_2408_04275_amd import workloads as wl
 
 
-def R(a):
-    return wl.round_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64)
-
-
-def rounded_decoder(shape, cu, modes, W, x, dy):
-    """Decoder layer forward + backward with every stored tensor rounded to bf16; fp64 arithmetic between."""
-    Wd = {k: v.astype(np.float64) for k, v in W.items()}
-    nh, nkv, d, F = shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn_hidden
-    T, nq, nk = x.shape[0], nh * d, nkv * d
-    sc = 1 / np.sqrt(d)
-    pos = orc.positions(cu)
-    h1, r1 = orc.rmsnorm_fwd(x, Wd["norm1_w"], 1e-5); h1 = R(h1)
-    qkv = R(h1 @ Wd["w_qkv"].T)
-    q = R(orc.rope(qkv[:, :nq].reshape(T, nh, d), pos, 1e4))
-    k = R(orc.rope(qkv[:, nq:nq + nk].reshape(T, nkv, d), pos, 1e4))
-    v = qkv[:, nq + nk:].reshape(T, nkv, d)
-    o, _ = orc.attention_fwd(q, k, v, cu, modes, sc); o = R(o.reshape(T, nq))
-    y1 = R(x + o @ Wd["w_o"].T)
-    h2, r2 = orc.rmsnorm_fwd(y1, Wd["norm2_w"], 1e-5); h2 = R(h2)
-    gu = R(h2 @ Wd["w_fc1"].T); g, u = gu[:, :F], gu[:, F:]
-    m = R(g * orc.sigmoid(g) * u)
-    y = R(y1 + m @ Wd["w_fc2"].T)
-    G = {}
-    d_m = R(dy @ Wd["w_fc2"]); G["w_fc2"] = R(dy.T @ m)
-    sg = orc.sigmoid(g)
-    d_pre = R(np.concatenate([d_m * u * sg * (1 + g * (1 - sg)), d_m * g * sg], 1))
-    d_h2 = R(d_pre @ Wd["w_fc1"]); G["w_fc1"] = R(d_pre.T @ h2)
-    dn, dg = orc.rmsnorm_bwd(d_h2, y1, Wd["norm2_w"], r2); G["norm2_w"] = R(dg)
-    d_y1 = R(dy + dn)
-    d_o = R(d_y1 @ Wd["w_o"]); G["w_o"] = R(d_y1.T @ o)
-    dq, dk, dv = orc.attention_bwd(d_o.reshape(T, nh, d), q, k, v, cu, modes, sc)
-    dq, dk = orc.rope(R(dq), pos, 1e4, True), orc.rope(R(dk), pos, 1e4, True)
-    d_qkv = R(np.concatenate([dq.reshape(T, nq), dk.reshape(T, nk), dv.reshape(T, nk)], 1))
-    d_h1 = R(d_qkv @ Wd["w_qkv"]); G["w_qkv"] = R(d_qkv.T @ h1)
-    dn, dg = orc.rmsnorm_bwd(d_h1, x, Wd["norm1_w"], r1); G["norm1_w"] = R(dg)
-    return y, R(d_y1 + dn), G
-
-
-def storage_floor(shape, cu, modes, std, seed):
+def floors(shape, cu, modes, std, seed):
     W = wl.make_weights(shape, seed, std=std)
     x, dy = (a.astype(np.float64) for a in wl.make_activations(shape, int(cu[-1]), seed))
-    y, c = orc.layer_fwd(0, shape.n_heads, shape.n_kv_heads, shape.head_dim, cu, modes, W, x)
+    y, c = orc.layer_fwd(shape.kind, shape.n_heads, shape.n_kv_heads, shape.head_dim, cu, modes, W, x)
     dx, G = orc.layer_bwd(W, c, dy)
-    ye, dxe, Ge = rounded_decoder(shape, cu, modes, W, x, dy)
+    ye, dxe, Ge = bf16_storage.layer_fwd_bwd_rounded(shape.kind, shape.n_heads, shape.n_kv_heads, shape.head_dim, cu, modes,
+                                                     W, x, dy)
     errs = {"y": parity.errors(ye, y), "dx": parity.errors(dxe, dx)}
     errs.update({k: parity.errors(Ge[k], G[k]) for k in G})
     return y, errs
 
 
-def test_bf16_storage_floor_sits_between_2e_2_and_the_bars():
+def test_rounding_is_the_library_conversion():
+    rng = np.random.default_rng(0)
+    a = np.concatenate([rng.standard_normal(200000) * 10.0 ** rng.integers(-6, 6, 200000),
+                        [0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895313892515355e38]])   # ties: to even both ways
+    want = torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(bf16_storage.bf16_round(a), want)
+    assert np.array_equal(bf16_storage.bf16_round(a), wl.round_bf16(a.astype(np.float32)).astype(np.float64))
+
+
+CU = np.array([0, 1, 1, 70, 199, 200, 457, 648])
+
+
+@pytest.mark.parametrize("kind", [wl.DECODER, wl.ENCODER])
+def test_without_rounding_the_emulation_is_the_oracle(kind, monkeypatch):
+    monkeypatch.setattr(bf16_storage, "R", lambda a: np.asarray(a, dtype=np.float64))
+    shape = wl.LayerShape("id", kind, wl.BF16, 96, 4, 2 if kind == wl.DECODER else 4, 16, 160, 648)
+    modes = np.array([0, 1, 1, 0, 1, 0, 1]) if kind == wl.DECODER else np.ones(7, dtype=int)
+    Ws = [wl.make_weights(shape, 3 + l, std=0.2) for l in range(2)]
+    x, dy = wl.make_activations(shape, 648, 3)
+    args = (kind, shape.n_heads, shape.n_kv_heads, shape.head_dim, CU, modes)
+    y, c = orc.layer_fwd(*args, Ws[0], x)
+    dx, G = orc.layer_bwd(Ws[0], c, dy)
+    ye, dxe, Ge = bf16_storage.layer_fwd_bwd_rounded(*args, Ws[0], x, dy)
+    assert np.max(np.abs(ye - y)) < 1e-12 and np.max(np.abs(dxe - dx)) < 1e-11
+    assert set(Ge) == set(G)
+    for k in G:
+        assert np.max(np.abs(Ge[k] - G[k])) < 1e-10 * max(1.0, np.max(np.abs(G[k]))), k
+    ry, caches = orc.stack_fwd(*args, Ws, x)
+    rdx, rG = orc.stack_bwd(Ws, caches, dy)
+    sy, sdx, sG = bf16_storage.stack_fwd_bwd_rounded(*args, Ws, x, dy)
+    assert np.max(np.abs(sy - ry)) < 1e-11 and np.max(np.abs(sdx - rdx)) < 1e-10 * max(1.0, np.max(np.abs(rdx)))
+    for l in range(2):
+        for k in rG[l]:
+            assert np.max(np.abs(sG[l][k] - rG[l][k])) < 1e-9 * max(1.0, np.max(np.abs(rG[l][k]))), (l, k)
+
+
+def test_bf16_storage_floor_sits_between_2e_2_and_the_flat_bars():
     shape = wl.LayerShape("floor", wl.DECODER, wl.BF16, 272, 4, 2, 64, 688, 648)
-    cu = np.array([0, 1, 1, 70, 199, 200, 457, 648]); modes = np.array([0, 1, 1, 0, 1, 0, 1])
-    y, errs = storage_floor(shape, cu, modes, 0.05, 1)
+    modes = np.array([0, 1, 1, 0, 1, 0, 1])
+    y, errs = floors(shape, CU, modes, 0.05, 1)
     # a single rounding: l2 about 1.7e-3
-    assert 1.4e-3 < parity.errors(R(y), y)["l2_err"] < 2.0e-3
+    assert 1.4e-3 < parity.errors(bf16_storage.bf16_round(y), y)["l2_err"] < 2.0e-3
     # the chain: several tensors exceed 2e-2 on the floored element-wise metric ...
     assert sum(e["floor_err"] > 2e-2 for e in errs.values()) >= 3
     assert max(e["l2_err"] for e in errs.values()) > 4e-3
-    # ... while every tensor is far below 2e-2 relative to its own scale, and within all three bars
+    # ... while every tensor is far below 2e-2 relative to its own scale, and within the flat bars the operator tests use
     for name, e in errs.items():
         assert e["max_err"] < 8e-3, (name, e)
+        assert e["big_err"] <= e["floor_err"]
         for k, bar in parity.BARS[wl.BF16].items():
             assert e[k] < bar, (name, k, e)
 
@@ -83,9 +90,41 @@ def test_bf16_storage_floor_grows_with_the_branch_to_residual_ratio():
     # attention branches are then as large as the residual stream and their roundings weigh more
     shape = wl.LayerShape("floor2", wl.DECODER, wl.BF16, 1024, 8, 8, 128, 2752, 512)
     cu = np.array([0, 150, 438, 512]); modes = np.array([0, 0, 1])
-    _, errs = storage_floor(shape, cu, modes, 0.04, 2)
+    _, errs = floors(shape, cu, modes, 0.04, 2)
     assert max(e["l2_err"] for e in errs.values()) > 5.5e-3
     assert max(e["floor_err"] for e in errs.values()) > 3.5e-2
     for name, e in errs.items():
         for k, bar in parity.BARS[wl.BF16].items():
             assert e[k] < bar, (name, k, e)
+
+
+def test_encoder_floor():
+    shape = wl.LayerShape("floor-enc", wl.ENCODER, wl.BF16, 272, 4, 4, 64, 528, 648)
+    _, errs = floors(shape, CU, np.ones(7, dtype=int), 0.05, 2)
+    assert len(errs) == 14
+    for name, e in errs.items():
+        assert 0 < e["l2_err"] < parity.BARS[wl.BF16]["l2_err"] and e["max_err"] < 8e-3, (name, e)
+
+
+def test_stored_floors_belong_to_todays_inputs_and_no_case_is_missing():
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "bf16_floor.json")) as f:
+        table = json.load(f)
+    assert set(table) == set(full_cases.CASES)
+    for name, entry in table.items():
+        assert entry["fingerprint"] == full_cases.fingerprint(name), name
+        shape = full_cases.segments(name)[0]
+        assert set(entry["tensors"]) == {"y", "dx"} | set(wl.weight_shapes(shape)), name
+        for tensor, e in entry["tensors"].items():
+            # every floor leaves the stated tolerance on max_err untouched, and no derived bar is looser than 0.2
+            assert e["max_err"] < 1.2e-2 and 0 < e["l2_err"] < 2e-2 and 0 < e["floor_err"] < 0.16, (name, tensor, e)
+
+
+def test_bars_from_floor():
+    b = parity.bars_from_floor({"floor_err": 5e-2, "l2_err": 6e-3, "max_err": 4e-3})
+    assert b == {"max_err": 2e-2, "floor_err": 1.5 * 5e-2, "l2_err": 1.25 * 6e-3}
+    ref = np.linspace(-1, 1, 1001)
+    with pytest.raises(AssertionError):
+        parity.check("t", ref * 1.01, ref, wl.BF16, floor={"floor_err": 1e-3, "l2_err": 1e-3})
+    parity.check("t", ref * 1.001, ref, wl.BF16, floor={"floor_err": 1e-3, "l2_err": 1e-3})
+    with pytest.raises(AssertionError):            # the l2 bar is the tighter of the two
+        parity.check("t", ref * 1.0014, ref, wl.BF16, floor={"floor_err": 1e-3, "l2_err": 1e-3})

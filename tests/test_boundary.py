@@ -124,6 +124,33 @@ def test_bwd_validation():
     assert mm.mmtrain_layer_bwd(**args(batch=batch([0, 20], T=16))) == mm.ERR_BAD_SEGMENTS
 
 
+def test_misaligned_tensors_are_rejected_on_the_host():
+    # a view such as tensor[1:] of a bf16 tensor is 2-byte aligned: the kernels move 16 bytes per lane, so the
+    # entry points refuse it instead of launching (no GPU involved: validation precedes every HIP call)
+    d = good_desc()
+    ok = batch([0, 16])
+    assert fwd(d, ok, x=FAKE + 2) == mm.ERR_INVALID_ARG
+    assert fwd(d, ok, y=FAKE + 256 + 8) == mm.ERR_INVALID_ARG
+    for field in ("norm1_w", "w_qkv", "w_o", "norm2_w", "w_fc1", "w_fc2"):
+        w = mm.Weights(*[FAKE] * 12)
+        setattr(w, field, FAKE + 4)
+        assert fwd(d, ok, weights=w) == mm.ERR_INVALID_ARG, field
+    w = mm.Weights(*[FAKE] * 12)
+    g = mm.Grads(*[FAKE] * 12)
+    args = lambda **k: dict(dict(desc=d, batch=ok, weights=w, x=FAKE, dy=FAKE, ctx=FAKE, dx=FAKE, grads=g,
+                                 flags=0, workspace=FAKE, workspace_bytes=1 << 40, stream=0), **k)
+    assert mm.mmtrain_layer_bwd(**args(dy=FAKE + 2)) == mm.ERR_INVALID_ARG
+    assert mm.mmtrain_layer_bwd(**args(dx=FAKE + 6)) == mm.ERR_INVALID_ARG
+    bad_g = mm.Grads(*[FAKE] * 12); bad_g.w_fc1 = FAKE + 2
+    assert mm.mmtrain_layer_bwd(**args(grads=bad_g)) == mm.ERR_INVALID_ARG
+    # attention operators: required tensors and their alignment are checked before the token tables are enqueued
+    big = 1 << 40
+    assert mm.mmtrain_attn_fwd(d, ok, FAKE + 2, FAKE, FAKE, FAKE, big, stream=0) == mm.ERR_INVALID_ARG
+    assert mm.mmtrain_attn_fwd(d, ok, FAKE, None, FAKE, FAKE, big, stream=0) == mm.ERR_INVALID_ARG
+    assert mm.mmtrain_attn_bwd(d, ok, FAKE, FAKE, FAKE, FAKE + 2, FAKE, FAKE, big, stream=0) == mm.ERR_INVALID_ARG
+    assert mm.mmtrain_attn_bwd(d, ok, FAKE, FAKE, FAKE, FAKE, None, FAKE, big, stream=0) == mm.ERR_INVALID_ARG
+
+
 def test_empty_pack_forward_is_a_no_op():
     assert fwd(good_desc(), batch([0], dev=False)) == mm.OK
     assert fwd(good_desc(), batch([0, 0, 0], dev=False)) == mm.OK

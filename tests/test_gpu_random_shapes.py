@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2408_04275_amd import workloads as wl
-from util import compare_layer, gpu_run, oracle_run, say, summary
+from util import compare_layer, gpu_run, oracle_run, say, storage_floors, summary
 
 pytestmark = pytest.mark.gpu
 
@@ -35,8 +35,9 @@ def test_random_shape(seed):
     W = wl.make_weights(shape, seed, std=0.05)
     x, dy = wl.make_activations(shape, int(cu[-1]), seed)
     ref = oracle_run(shape, cu, modes, W, x, dy)
+    floors = storage_floors(shape, cu, modes, W, x, dy, ref)
     got = gpu_run(shape, cu, modes, W, x, dy)
     what = (f"random {seed}: kind={shape.kind} dtype={shape.dtype} H={shape.hidden} heads={shape.n_heads}/{shape.n_kv_heads}x"
             f"{shape.head_dim} F={shape.ffn_hidden} T={int(cu[-1])} segments={np.diff(cu).tolist()} ")
-    errs = compare_layer(shape, got, ref, what)
-    say(f"{what}: {summary(errs)}")
+    errs = compare_layer(shape, got, ref, what, floors=floors)
+    say(f"{what}: {summary(errs, floors)}")

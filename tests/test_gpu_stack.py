@@ -4,7 +4,9 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import bf16_storage
 from oracle import layer_oracle as orc
+from paper_2408_04275_amd import parity
 from paper_2408_04275_amd import binding as mm
 from paper_2408_04275_amd import workloads as wl
 from paper_2408_04275_amd.harness import LayerRunner, StackRunner
@@ -37,16 +39,23 @@ def test_stack_matches_the_oracle(shape, recompute):
     ry, caches = orc.stack_fwd(shape.kind, shape.n_heads, shape.n_kv_heads, shape.head_dim, CU, modes, Ws, x,
                                eps=shape.norm_eps, rope_base=shape.rope_base)
     rdx, rG = orc.stack_bwd(Ws, caches, dy)
+    fy = fdx = None
+    fG = [{} for _ in range(n)]
+    if shape.dtype == wl.BF16:                       # what bf16 storage alone costs this stack, tensor by tensor
+        ey, edx, eG = bf16_storage.stack_fwd_bwd_rounded(shape.kind, shape.n_heads, shape.n_kv_heads, shape.head_dim, CU, modes,
+                                                         Ws, x, dy, eps=shape.norm_eps, rope_base=shape.rope_base)
+        fy, fdx = parity.errors(ey, ry), parity.errors(edx, rdx)
+        fG = [{k: parity.errors(eG[l][k], rG[l][k]) for k in rG[l]} for l in range(n)]
     r = StackRunner(shape, Ws, CU, modes, recompute=recompute)
     r.set_inputs(x, dy)
     r.step()
     y, dx, G = r.results()
     what = f"{shape.name} recompute={recompute} "
-    worst = [assert_parity(what + "y", y, ry, shape.dtype), assert_parity(what + "dx", dx, rdx, shape.dtype)]
+    worst = [assert_parity(what + "y", y, ry, shape.dtype, floor=fy), assert_parity(what + "dx", dx, rdx, shape.dtype, floor=fdx)]
     for l in range(n):
         assert set(G[l]) == set(rG[l])
         for k in rG[l]:
-            worst.append(assert_parity(what + f"layer {l} d{k}", G[l][k], rG[l][k], shape.dtype))
+            worst.append(assert_parity(what + f"layer {l} d{k}", G[l][k], rG[l][k], shape.dtype, floor=fG[l].get(k)))
     say(what + "max_err %.2e" % max(e["max_err"] for e in worst))
 
 

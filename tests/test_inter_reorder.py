@@ -123,6 +123,19 @@ def test_reorder_hand_worked_example():
     assert seen == g["R.intervals_seen"]
 
 
+def test_size_is_the_time_in_encoder_and_generator():
+    """The hand-worked example in which the backbone's time varies too: the section's size (encoder + generator time,
+    here the first and the last stage) and the total over all stages pick different first and last microbatches."""
+    g = read_golden()
+    order, seen = po.inter_reorder(g["S.fwd"], g["S.bwd"])
+    assert order == [int(v) for v in g["S.order"]] and seen == g["S.intervals_seen"]
+    order, seen = po.inter_reorder(g["S.fwd"], g["S.bwd"], sizes=g["S.total_sizes"])
+    assert order == [int(v) for v in g["S.order_total_sizes"]] and seen == g["S.intervals_seen_total_sizes"]
+    # explicit sizes equal to the default's give the default's result
+    enc_gen = [g["S.fwd"][0][j] + g["S.bwd"][0][j] + g["S.fwd"][2][j] + g["S.bwd"][2][j] for j in range(5)]
+    assert po.inter_reorder(g["S.fwd"], g["S.bwd"], sizes=enc_gen)[0] == [int(v) for v in g["S.order"]]
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_reorder_structure(seed):
     """What the section states about the result: a permutation; the smallest microbatch first; the p - 1 smallest of
@@ -132,7 +145,7 @@ def test_reorder_structure(seed):
     f, b = random_times(rng, p, l, seed % 2 == 0)
     order, seen = po.inter_reorder(f.tolist(), b.tolist())
     assert sorted(order) == list(range(l))
-    size = (f + b).sum(axis=0)
+    size = (f + b)[sorted({0, p - 1})].sum(axis=0)           # time in the first and the last stage
     assert size[order[0]] == size.min()
     n_rear = min(p - 1, l - 1)
     if n_rear:
@@ -192,6 +205,10 @@ def test_library_matches_hand_worked_examples():
     assert rc == 0 and ms == g["T.makespan"][0] and list(iv) == g["T.intervals"]
     rc, order, seen = mm.mmtrain_inter_reorder(g["R.fwd"], g["R.bwd"])
     assert rc == 0 and list(order) == [int(v) for v in g["R.order"]] and list(seen) == g["R.intervals_seen"]
+    rc, order, seen = mm.mmtrain_inter_reorder(g["S.fwd"], g["S.bwd"])
+    assert rc == 0 and list(order) == [int(v) for v in g["S.order"]] and list(seen) == g["S.intervals_seen"]
+    rc, order, seen = mm.mmtrain_inter_reorder(g["S.fwd"], g["S.bwd"], sizes=g["S.total_sizes"])
+    assert rc == 0 and list(order) == [int(v) for v in g["S.order_total_sizes"]] and list(seen) == g["S.intervals_seen_total_sizes"]
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -200,8 +217,9 @@ def test_library_matches_oracle(seed):
     for case in range(150):
         p, l = int(rng.integers(1, 8)), int(rng.integers(1, 20))
         f, b = random_times(rng, p, l, case % 2 == 0)
-        want, want_seen = po.inter_reorder(f.tolist(), b.tolist())
-        rc, order, seen = mm.mmtrain_inter_reorder(f, b)
+        sizes = None if case % 3 else (rng.integers(0, 5, l).astype(float) if case % 2 else rng.random(l))
+        want, want_seen = po.inter_reorder(f.tolist(), b.tolist(), None if sizes is None else sizes.tolist())
+        rc, order, seen = mm.mmtrain_inter_reorder(f, b, sizes)
         assert rc == 0
         assert list(order) == want, (p, l)
         np.testing.assert_allclose(seen, want_seen, rtol=0, atol=1e-12)
@@ -232,8 +250,10 @@ def test_library_rejects_bad_arguments():
     assert mm.mmtrain_pipeline_1f1b(f, bad)[0] == mm.ERR_INVALID_ARG
     assert mm.mmtrain_pipeline_1f1b(f, b, [0, 0, 1])[0] == mm.ERR_INVALID_ARG
     assert mm.mmtrain_pipeline_1f1b(f, b, [0, 1, 3])[0] == mm.ERR_INVALID_ARG
-    assert lib.mmtrain_inter_reorder(f.ctypes.data, b.ctypes.data, 0, 3, None, None, None) == mm.ERR_INVALID_ARG
-    assert lib.mmtrain_inter_reorder(f.ctypes.data, b.ctypes.data, 2, 3, None, None, None) == mm.ERR_INVALID_ARG
-    assert lib.mmtrain_inter_reorder(None, None, 2, 0, None, None, None) == mm.OK
+    assert mm.mmtrain_inter_reorder(f, b, sizes=[1.0, np.inf, 2.0])[0] == mm.ERR_INVALID_ARG
+    assert mm.mmtrain_inter_reorder(f, b, sizes=[1.0, -1.0, 2.0])[0] == mm.ERR_INVALID_ARG
+    assert lib.mmtrain_inter_reorder(f.ctypes.data, b.ctypes.data, 0, 3, None, None, None, None) == mm.ERR_INVALID_ARG
+    assert lib.mmtrain_inter_reorder(f.ctypes.data, b.ctypes.data, 2, 3, None, None, None, None) == mm.ERR_INVALID_ARG
+    assert lib.mmtrain_inter_reorder(None, None, 2, 0, None, None, None, None) == mm.OK
     rc, ms, _ = mm.mmtrain_pipeline_1f1b(np.ones((2, 0)), np.ones((2, 0)))
     assert rc == mm.OK and ms == 0.0

@@ -183,7 +183,7 @@ def test_finite_differences(kind):
     targets = [("x", x, dx)] + [(n, W[n], G[n]) for n in W]
     for name, arr, grad in targets:
         flat = arr.reshape(-1)
-        for i in rng.choice(flat.size, size=min(flat.size, 40), replace=False):
+        for i in rng.choice(flat.size, size=min(flat.size, 200), replace=False):
             old = flat[i]
             h = 1e-6 * max(1.0, abs(old))
             flat[i] = old + h
