@@ -66,7 +66,8 @@ typedef enum {
     MMTRAIN_ERR_BAD_SEGMENTS = -2,  /* cu_seqlens not starting at 0, decreasing, or not ending at T  */
     MMTRAIN_ERR_UNSUPPORTED = -3,   /* shape outside the supported set (see mmtrain_layer_desc)      */
     MMTRAIN_ERR_WORKSPACE = -4,     /* workspace_bytes smaller than mmtrain_layer_workspace_bytes    */
-    MMTRAIN_ERR_HIP = -5            /* a HIP call or kernel launch reported an error                 */
+    MMTRAIN_ERR_HIP = -5,           /* a HIP call or kernel launch reported an error                 */
+    MMTRAIN_ERR_TOO_LARGE = -6      /* input beyond the fixed maximum of mmtrain_attn_bwd_noalloc    */
 } mmtrain_status;
 
 typedef enum { MMTRAIN_F32 = 0, MMTRAIN_BF16 = 1 } mmtrain_dtype;
@@ -265,6 +266,25 @@ MMTRAIN_API int mmtrain_attn_fwd(const mmtrain_layer_desc *desc, const mmtrain_b
 MMTRAIN_API int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, const void *qkv,
                      const void *o, const float *lse, const void *d_o, void *d_qkv,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* mmtrain_attn_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * kernels as mmtrain_attn_bwd without the workspace: the scratch (per-token segment tables and the per-head
+ * row sums D that the dQ kernel hands to the dK/dV kernel) is a fixed array of MMTRAIN_NOALLOC_SCRATCH_BYTES
+ * inside the library, one copy on every GPU the library runs on, held until the process ends.  The call
+ * allocates nothing and frees nothing, on the device or through any library.
+ *   Limits: total_tokens <= MMTRAIN_NOALLOC_MAX_TOKENS and total_tokens * n_heads <=
+ *   MMTRAIN_NOALLOC_MAX_HEAD_TOKENS, else MMTRAIN_ERR_TOO_LARGE (checked on the host, nothing enqueued).
+ *   All calls on one GPU share that GPU's array, which keeps the previous call's contents; no entry has to
+ *   start at zero (every entry read was written by the same call).  Calls on one stream are ordered and safe;
+ *   calls that overlap on one GPU (different streams, different threads) race on the array.
+ *   The first call on a device looks the array's address up (a host-side query, no allocation). */
+#define MMTRAIN_NOALLOC_MAX_TOKENS 16384
+#define MMTRAIN_NOALLOC_MAX_HEAD_TOKENS (64 * 16384)
+#define MMTRAIN_NOALLOC_SCRATCH_BYTES (16384 * 4 + 16384 * 8 + 64 * 16384 * 4 + 4 * 256)
+MMTRAIN_API int mmtrain_attn_bwd_noalloc(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, const void *qkv,
+                                         const void *o, const float *lse, const void *d_o, void *d_qkv,
+                                         void *hip_stream);
 
 /* Intra-microbatch reordering (Algorithm 1, Section "Intra-microbatch Reordering"): greedy multiway
  * partitioning of n samples over m data-parallel groups.  The samples are sorted by size in descending

@@ -15,7 +15,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmmtrain.so")
 
-OK, ERR_INVALID_ARG, ERR_BAD_SEGMENTS, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5
+OK, ERR_INVALID_ARG, ERR_BAD_SEGMENTS, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
+NOALLOC_MAX_TOKENS, NOALLOC_MAX_HEAD_TOKENS = 16384, 64 * 16384
 F32, BF16 = 0, 1
 DECODER, ENCODER = 0, 1
 MASK_CAUSAL, MASK_BIDIR = 0, 1
@@ -30,7 +31,7 @@ EXPORTS = ("mmtrain_layer_ctx_bytes", "mmtrain_layer_workspace_bytes", "mmtrain_
            "mmtrain_attn_bwd", "mmtrain_profile_enable", "mmtrain_profile_read", "mmtrain_intra_reorder", "mmtrain_adam_step",
            "mmtrain_stack_ctx_bytes", "mmtrain_stack_workspace_bytes", "mmtrain_stack_fwd", "mmtrain_stack_bwd",
            "mmtrain_pipeline_1f1b", "mmtrain_inter_reorder", "mmtrain_profile_attn_busy",
-           "mmtrain_profile_gemm_clock")
+           "mmtrain_profile_gemm_clock", "mmtrain_attn_bwd_noalloc")
 PROF_GEMM_NT, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD = range(5)
 PROF_NORM_FWD, PROF_NORM_BWD, PROF_ROPE, PROF_ACT_FWD, PROF_ACT_BWD = range(5, 10)
 
@@ -110,6 +111,8 @@ def load_library() -> C.CDLL:
     lib.mmtrain_attn_fwd.argtypes = [P, P, P, P, P, P, S, P]
     lib.mmtrain_attn_bwd.restype = C.c_int
     lib.mmtrain_attn_bwd.argtypes = [P, P, P, P, P, P, P, P, S, P]
+    lib.mmtrain_attn_bwd_noalloc.restype = C.c_int
+    lib.mmtrain_attn_bwd_noalloc.argtypes = [P, P, P, P, P, P, P, P]
     lib.mmtrain_profile_enable.restype = None
     lib.mmtrain_profile_enable.argtypes = [C.c_int]
     lib.mmtrain_profile_attn_busy.restype = None
@@ -339,6 +342,12 @@ def mmtrain_attn_bwd(desc, batch, qkv, o, lse, d_o, d_qkv, workspace, workspace_
     b = batch.struct if isinstance(batch, PackedBatch) else batch
     return load_library().mmtrain_attn_bwd(_ref(desc), _ref(b), _ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o),
                                            _ptr(d_qkv), _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def mmtrain_attn_bwd_noalloc(desc, batch, qkv, o, lse, d_o, d_qkv, stream=None) -> int:
+    b = batch.struct if isinstance(batch, PackedBatch) else batch
+    return load_library().mmtrain_attn_bwd_noalloc(_ref(desc), _ref(b), _ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o),
+                                                   _ptr(d_qkv), _stream(stream))
 
 
 PROF_ALL = 0x3ff

@@ -4,6 +4,7 @@
 #include "kernels.h"
 #include <cmath>
 #include <initializer_list>
+#include <mutex>
 #include <vector>
 
 using namespace mmt;
@@ -273,6 +274,7 @@ const char *mmtrain_status_string(int status) {
         case MMTRAIN_ERR_UNSUPPORTED: return "unsupported shape";
         case MMTRAIN_ERR_WORKSPACE: return "workspace too small";
         case MMTRAIN_ERR_HIP: return "HIP error";
+        case MMTRAIN_ERR_TOO_LARGE: return "input larger than the static scratch of the no-allocation entry point";
         default: return "unknown status";
     }
 }
@@ -654,6 +656,54 @@ int mmtrain_attn_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch,
     a.qkv = qkv; a.o = const_cast<void *>(o); a.lse = const_cast<float *>(lse); a.d_o = d_o; a.d_qkv = d_qkv;
     HIP_TRY(attn_bwd(D.dtype, a, st));
     return MMTRAIN_OK;
+}
+
+// ---- attention backward for callers that cannot allocate ---------------------------------------------------
+// The scratch mmtrain_attn_bwd takes as its workspace (per-token segment tables, D = rowsum(dO * O) per head and
+// token, handed from the dQ kernel to the dK/dV kernel) lives in a file-scope device array instead.  In host code
+// the array's name is only a stand-in: its device address is looked up once per device and used from then on.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[MMTRAIN_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};           // device address of `scratch` on each device, once looked up
+
+// The current device's copy of the array (every device holds its own, at its own address).
+int scratch_address(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MMTRAIN_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MMTRAIN_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MMTRAIN_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int mmtrain_attn_bwd_noalloc(const mmtrain_layer_desc *desc, const mmtrain_batch *batch, const void *qkv, const void *o,
+                             const float *lse, const void *d_o, void *d_qkv, void *hip_stream) {
+    Dims D;
+    int rc = check_desc(desc, D);
+    if (rc) return rc;
+    if ((rc = check_batch(batch))) return rc;
+    if (batch->total_tokens > MMTRAIN_NOALLOC_MAX_TOKENS ||
+        (int64_t)batch->total_tokens * D.nh > MMTRAIN_NOALLOC_MAX_HEAD_TOKENS ||
+        mmtrain_attn_workspace_bytes(batch->total_tokens, batch->n_segments, D.nh) > MMTRAIN_NOALLOC_SCRATCH_BYTES)
+        return MMTRAIN_ERR_TOO_LARGE;
+    if (batch->total_tokens == 0) return MMTRAIN_OK;
+    if (!qkv || !o || !lse || !d_o || !d_qkv) return MMTRAIN_ERR_INVALID_ARG;
+    void *ws = nullptr;
+    if ((rc = scratch_address(&ws))) return rc;
+    // Nothing in the scratch has to start at zero: the kernels write every entry they later read.
+    return mmtrain_attn_bwd(desc, batch, qkv, o, lse, d_o, d_qkv, ws, MMTRAIN_NOALLOC_SCRATCH_BYTES, hip_stream);
 }
 
 int mmtrain_intra_reorder(const double *sizes, int32_t n, int32_t m, int32_t *order, int32_t *group_begin,

@@ -21,14 +21,14 @@ def header_symbols():
 def test_library_exports_every_declared_symbol():
     lib = mm.load_library()
     names = header_symbols()
-    assert len(names) == 22 and set(names) == set(mm.EXPORTS)
+    assert len(names) == 23 and set(names) == set(mm.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
 
 
 def test_status_strings():
     assert mm.mmtrain_status_string(0) == "ok"
-    for s in (-1, -2, -3, -4, -5):
+    for s in (-1, -2, -3, -4, -5, -6):
         assert mm.mmtrain_status_string(s) not in ("ok", "unknown status")
     assert mm.mmtrain_status_string(-99) == "unknown status"
 
