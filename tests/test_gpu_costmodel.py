@@ -1,0 +1,57 @@
+"""The cost input of the paper's intra-microbatch reordering (Algorithm 1, Section 5.2), produced by code: this library's
+event-timed step time fitted as c0 + a * tokens + b * unmasked pairs on the 7B-shaped layer, checked on held-out packs,
+and then used as the sizes mmtrain_intra_reorder balances -- with the resulting groups timed on the GPU."""
+import numpy as np
+import pytest
+
+from paper_2408_04275_amd import binding as mm
+from paper_2408_04275_amd import costmodel as cm
+from paper_2408_04275_amd import workloads as wl
+from util import say
+
+pytestmark = pytest.mark.gpu
+
+
+def pack_of(lengths):
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    return cu, np.zeros(len(lengths), dtype=np.uint8)
+
+
+def test_fitted_cost_predicts_held_out_packs_and_balances_a_skewed_batch():
+    shape = wl.SHAPES[3]
+    W = wl.make_weights(shape, 0)
+    packs = cm.training_packs(3)
+    feats = [cm.pack_features(cu, modes) for _, cu, modes in packs]
+    times = [cm.measure(shape, W, cu, modes, steps=8) for _, cu, modes in packs]
+    coef, res = cm.fit(feats, times)
+    say(f"cost model: step_ms = {coef[0]:.3f} + {coef[1] * 1e3:.4f} per kilo-token + {coef[2] * 1e6:.4f} per mega-pair; "
+        f"largest residual on the {len(packs)} training packs {100 * np.max(np.abs(res)):.1f} %")
+    assert coef[1] > 0 and coef[2] > 0
+    assert np.max(np.abs(res)) < 0.07            # training packs go down to 2048 tokens, where tile quantisation shows
+    # held-out packs: other seeds of the workload generators, a long-tailed pack, a shorter pack
+    held = [wl.make_segments(3, 11)[:2], wl.make_segments(4, 5)[:2], wl.make_segments(3, 12, image_bidir=True)[:2],
+            pack_of([3000, 700, 1200, 244])]
+    for cu, modes in held:
+        t, p = cm.pack_features(cu, modes)
+        ms, want = cm.measure(shape, W, cu, modes, steps=8), cm.predict(coef, t, p)
+        say(f"held-out pack T={t} pairs={p}: measured {ms:.3f} ms, predicted {want:.3f} ms ({100 * (want / ms - 1):+.1f} %)")
+        assert abs(want / ms - 1) < 0.05
+    # A skewed batch of samples in arrival order, four data-parallel groups: each group's samples form its pack.
+    rng = np.random.default_rng(17)
+    lengths = np.clip(np.rint(rng.lognormal(6.0, 1.2, 24)), 16, 6000).astype(int)
+    costs = cm.sample_costs(coef, lengths)
+    m = 4
+    rc, order, begin, load = mm.mmtrain_intra_reorder(costs, m)
+    assert rc == 0
+
+    def group_times(groups):
+        return [cm.measure(shape, W, *pack_of(lengths[g]), steps=6) for g in groups]
+
+    arrival = [np.arange(j * 6, (j + 1) * 6) for j in range(m)]
+    reordered = [order[begin[j]:begin[j + 1]] for j in range(m)]
+    t_arr, t_new = group_times(arrival), group_times(reordered)
+    say(f"skewed batch, {m} groups: arrival order {['%.2f' % t for t in t_arr]} ms, reordered {['%.2f' % t for t in t_new]} ms")
+    assert max(t_new) < max(t_arr)
+    # the fitted sizes are what made the groups even: measured group times follow the predicted loads
+    for j in range(m):
+        assert abs((coef[0] + load[j]) / t_new[j] - 1) < 0.08

@@ -94,22 +94,31 @@ def test_c_abi_matches_the_oracle():
         assert np.allclose(load, [sum(sizes[d] for d in g) for g in ref_groups])
 
 
-def test_c_abi_on_measured_costs_balances_packs():
-    # cost model of a pack on this library: a * tokens + b * attention pairs; samples = packs with very
-    # different attention work; reordered groups must be no worse than the arrival order
+def test_cost_model_fit_recovers_its_coefficients_and_feeds_the_reordering():
+    # the fit (least squares of c0 + a tokens + b pairs) on synthetic timings with known coefficients and 1 % noise;
+    # the GPU test of the same name in tests/test_gpu_costmodel.py fits this library's measured step time instead
+    from paper_2408_04275_amd import costmodel as cm
     from paper_2408_04275_amd import workloads as wl
     rng = np.random.default_rng(3)
-    a, b = 1.1e-6, 6.0e-11        # seconds per token and per (query, key) pair, of the order measured on MI355X
-    costs = []
-    for seed in range(16):
-        cu, modes = wl.random_segments(rng, 8192, 1 + int(rng.integers(1, 24)))
-        costs.append(a * 8192 + b * wl.attention_pairs(cu, modes))
+    c0, a, b = 0.15, 9.0e-4, 4.0e-8           # ms, ms per token, ms per pair
+    feats = [cm.pack_features(cu, modes) for _, cu, modes in cm.training_packs(3)]
+    assert len({t for t, _ in feats}) >= 4                       # the token count varies, so `a` is identified
+    ms = [(c0 + a * t + b * p) * (1 + 0.01 * rng.standard_normal()) for t, p in feats]
+    coef, res = cm.fit(feats, ms)
+    assert abs(coef[1] / a - 1) < 0.05 and abs(coef[2] / b - 1) < 0.05 and np.max(np.abs(res)) < 0.04
+    # a sample's cost is additive over a pack: the pack's prediction is c0 + the sum of its samples' costs
+    cu, modes, _ = wl.make_segments(3, 9)
+    t, p = cm.pack_features(cu, modes)
+    assert cm.predict(coef, t, p) == pytest.approx(coef[0] + cm.sample_costs(coef, np.diff(cu)).sum(), rel=1e-12)
+    # a skewed batch of samples: the reordered groups are no worse than the arrival order, and within the 4/3 bound
+    lengths = np.clip(np.rint(rng.lognormal(6.0, 1.2, 32)), 16, 8192).astype(int)
+    costs = cm.sample_costs(coef, lengths)
     m = 4
     rc, order, begin, load = mm.mmtrain_intra_reorder(costs, m)
     assert rc == 0
-    arrival = [sum(costs[j * 4:(j + 1) * 4]) for j in range(m)]
+    arrival = [costs[j * 8:(j + 1) * 8].sum() for j in range(m)]
     assert load.max() <= max(arrival) + 1e-12
-    assert load.max() <= (4.0 / 3.0) * max(sum(costs) / m, max(costs))
+    assert load.max() <= (4.0 / 3.0) * max(costs.sum() / m, costs.max())
 
 
 def test_c_abi_rejects_bad_arguments():
