@@ -12,6 +12,7 @@ SOURCES = ["api.hip", "elementwise.hip", "gemm_simple.hip", "gemm_mfma.hip", "at
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+FLAGS += os.environ.get("MMTRAIN_EXTRA_HIPCC_FLAGS", "").split()      # e.g. -D switches of timing experiments
 
 
 def _compile(src: str) -> str:

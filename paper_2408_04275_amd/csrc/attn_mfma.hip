@@ -507,6 +507,21 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     add_busy(a.cu_busy ? a.cu_busy + 1024 : nullptr, true);
 }
 
+// Exchange between lane l and lane l ^ 32 in one vector instruction (the two halves of a wavefront hold the two halves of
+// every query's keys): after the swap the first result holds the lower half's values in both halves, the second the upper's.
+__device__ __forceinline__ float max_across_halves(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_halves(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// The forward kernel's running maximum is lazy: the reference the exponentials are taken against moves only when a
+// step's maximum exceeds it by more than 2^LAZY_LOG2 (in units of the exponent), so the output accumulators are rescaled
+// a few times per query instead of at almost every step; exponentials stay below 2^LAZY_LOG2, far inside fp32 and bf16 range.
+constexpr float LAZY_LOG2 = 8.f;
+
 // ------------------------------------------------------------------------------------------
 // forward.  512 threads: 8 wavefronts x 32 queries = 256 queries per workgroup (two wavefronts per SIMD, so that one can
 // run its softmax on the vector ALUs while the other occupies the matrix core), walking the keys 64 at a time through
@@ -592,7 +607,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
         }
         // online softmax on the raw scores (the scale is folded into the exponent);
         // register i of block b  <->  key kt + 32 b + 8 (i >> 2) + 4 half + (i & 3)
-        float mx = m_run;
+        float mx = -INFINITY;
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
             if (!act[b]) continue;
@@ -607,18 +622,19 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[b][i]);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_use = mx == -INFINITY ? 0.f : mx;
-        if (__builtin_amdgcn_ballot_w64(mx != m_run) != 0) {           // some lane's maximum moved
-            const float corr = __builtin_amdgcn_exp2f((m_run - m_use) * sl2);
+        mx = max_across_halves(mx);
+        // move the reference only where the step's maximum is more than 2^LAZY_LOG2 above it (always from -inf)
+        const bool need = (mx - m_run) * sl2 > LAZY_LOG2;
+        if (__builtin_amdgcn_ballot_w64(need) != 0) {
+            const float corr = need ? __builtin_amdgcn_exp2f((m_run - mx) * sl2) : 1.f;
+            m_run = need ? mx : m_run;
             l_run *= corr;
 #pragma unroll
             for (int c = 0; c < CB; ++c)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) oacc[c][i] *= corr;
         }
-        m_run = mx;
-        const float msc = m_use * sl2;
+        const float msc = m_run == -INFINITY ? 0.f : m_run * sl2;
         const uint32_t tv = slot * SLOT + TILE;
         auto block = [&](auto B_) {
             constexpr int b = decltype(B_)::value;
@@ -655,7 +671,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
         block(std::integral_constant<int, 1>{});
     }
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float l_tot = sum_across_halves(l_run);
     lds_barrier();                                     // the tiles are done with: LDS now stages the output rows
     store_rows<D, CB>(smem + wave * STAGE_BYTES<D>, oacc, valid ? 1.f / l_tot : 0.f, (bf16_t *)a.o + (long)(q0 + wave * 32) * nq + head * dh,
                       nq, T - (q0 + wave * 32), dh);
