@@ -262,6 +262,25 @@ hipError_t gemm(int dtype, const GemmArgs &g, hipStream_t st) {
     return gemm_simple(dtype, g, st);
 }
 
+// Weight-gradient GEMMs of a backward pass whose outputs have few tiles are not launched where they stand but
+// collected and run together at the end of the pass (gemm_mfma_group): their operands all live until then.
+struct DeferredWgrads {
+    GemmArgs g[4];
+    int n = 0;
+};
+hipError_t wgrad(int dtype, const GemmArgs &g, DeferredWgrads &later, hipStream_t st) {
+    if (dtype == DT_BF16 && later.n < 4 && gemm_mfma_few_tiles(g)) {
+        later.g[later.n++] = g;
+        return hipSuccess;
+    }
+    return gemm(dtype, g, st);
+}
+hipError_t run_deferred(const DeferredWgrads &later, hipStream_t st) {
+    if (later.n == 0) return hipSuccess;
+    ProfScope ps(MMTRAIN_PROF_GEMM_TN, st);
+    return gemm_mfma_group(later.g, later.n, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -383,14 +402,15 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
 
     // ---- MLP block:  y = y1 + m . Wfc2^T (+ b_fc2)
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), w.split_ws, w.split_bytes), st));
-    if (G.w_fc2) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
+    DeferredWgrads later;
+    if (G.w_fc2) HIP_TRY(wgrad(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), later, st));
     if (enc && G.b_fc1) {                         // the bias gradient is the column sum of what this kernel writes
         HIP_TRY_TIMED(MMTRAIN_PROF_ACT_BWD, st, gelu_bwd_colsum(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F1, w.part_c, st));
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.F1, G.b_fc1, accum, st));
     } else if (enc) HIP_TRY_TIMED(MMTRAIN_PROF_ACT_BWD, st, gelu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, (long)T * D.F, st));
     else HIP_TRY_TIMED(MMTRAIN_PROF_ACT_BWD, st, swiglu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F, st));
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.H, D.F1, w.d_pre, D.F1, W->w_fc1, D.H, w.d_h, D.H), w.split_ws, w.split_bytes), st));
-    if (G.w_fc1) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
+    if (G.w_fc1) HIP_TRY(wgrad(D.dtype, splittable(f32out(mk(GEMM_TN, D.F1, D.H, T, w.d_pre, D.F1, c.h2, D.H, G.w_fc1, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), later, st));
     // d_y1 = dy + norm2_bwd(d_h2); the same kernel sums the columns of dy (b_fc2's gradient) and of d_y1 (b_o's)
     HIP_TRY_TIMED(MMTRAIN_PROF_NORM_BWD, st, norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
                      G.norm2_w ? w.part_g : nullptr, (enc && G.norm2_b) ? w.part_b : nullptr,
@@ -403,7 +423,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
 
     // ---- attention block:  y1 = x + o . Wo^T (+ b_o)
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.nq, D.H, w.d_y1, D.H, W->w_o, D.nq, w.d_o, D.nq), w.split_ws, w.split_bytes), st));
-    if (G.w_o) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.nq, T, w.d_y1, D.H, c.o, D.nq, G.w_o, D.nq, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
+    if (G.w_o) HIP_TRY(wgrad(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.nq, T, w.d_y1, D.H, c.o, D.nq, G.w_o, D.nq, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), later, st));
     AttnArgs a = mk_attn(D, batch, c);
     a.d_o = w.d_o; a.d_qkv = w.d_qkv; a.Dsum = w.Dsum;
     const bool fused_unrotate = !enc && D.dtype == DT_BF16 && (D.d == 64 || D.d == 128);       // the matrix-core kernels rotate dQ, dK back themselves
@@ -418,7 +438,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
         HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.nqkv, G.b_qkv, accum, st));
     }
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.H, D.nqkv, w.d_qkv, D.nqkv, W->w_qkv, D.H, w.d_h, D.H), w.split_ws, w.split_bytes), st));
-    if (G.w_qkv) HIP_TRY(gemm(D.dtype, splittable(f32out(mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), st));
+    if (G.w_qkv) HIP_TRY(wgrad(D.dtype, splittable(f32out(mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), later, st));
     // dx = d_y1 + norm1_bwd(d_h1)
     HIP_TRY_TIMED(MMTRAIN_PROF_NORM_BWD, st, norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
                      G.norm1_w ? w.part_g : nullptr, (enc && G.norm1_b) ? w.part_b : nullptr, nullptr, nullptr, T, D.H, st));
@@ -427,6 +447,7 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
         void *outs[2] = {G.norm1_w, enc ? G.norm1_b : nullptr};
         HIP_TRY(reduce_partials_set(gdt, parts, outs, 2, nb, D.H, accum, st));
     }
+    HIP_TRY(run_deferred(later, st));
     return MMTRAIN_OK;
 }
 

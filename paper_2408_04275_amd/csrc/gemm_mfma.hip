@@ -66,6 +66,30 @@ struct GemmP {
     unsigned long long *clock_probe;       // see GemmArgs
 };
 
+// Several products of one layout and epilogue in one launch (the weight gradients of a narrow layer, each with too few
+// tiles to fill the chip): the work items of problem i are [first[i], first[i + 1]); first[i] for i >= n is the total.
+constexpr int MAX_GROUP = 4;
+struct GemmGroup {
+    GemmP p[MAX_GROUP];
+    int first[MAX_GROUP + 1];
+    int n;
+};
+// what the kernel needs from its argument, for one product or a group
+__device__ __forceinline__ const GemmP &first_problem(const GemmP &a) { return a; }
+__device__ __forceinline__ const GemmP &first_problem(const GemmGroup &a) { return a.p[0]; }
+__device__ __forceinline__ int work_items(const GemmP &a, bool split) { return a.tile_count * (split ? a.splits : 1); }
+__device__ __forceinline__ int work_items(const GemmGroup &a, bool) { return a.first[MAX_GROUP]; }
+// work item `logical` of the launch -> its problem and its index among that problem's items
+__device__ __forceinline__ GemmP pick(const GemmP &a, int logical, int &local) { local = logical; return a; }
+__device__ __forceinline__ GemmP pick(const GemmGroup &a, int logical, int &local) {
+    GemmP p = a.p[0];
+    local = logical;
+    if (logical >= a.first[1]) { p = a.p[1]; local = logical - a.first[1]; }
+    if (logical >= a.first[2]) { p = a.p[2]; local = logical - a.first[2]; }
+    if (logical >= a.first[3]) { p = a.p[3]; local = logical - a.first[3]; }
+    return p;
+}
+
 // position t of the tile order -> tile coordinates: column-major inside groups of GROUP_M tile-rows
 __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int &tm, int &tn) {
     const int width = GROUP_M * tiles_n;
@@ -290,21 +314,23 @@ __device__ __forceinline__ void mfma_copy(f32x4 &acc, const bf16x8 &b, const bf1
 template <bool KC> struct LoaderSel { typedef LoaderKC type; };
 template <> struct LoaderSel<false> { typedef LoaderKS type; };
 
-template <bool A_KC, bool B_KC, bool HAS_ADD, bool OUT_F32>
+template <bool A_KC, bool B_KC, bool HAS_ADD, bool OUT_F32, typename ARG = GemmP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void gemm_mfma_kernel(const GemmP p) {
+void gemm_mfma_kernel(const ARG arg) {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const unsigned long long *const probe_ = first_problem(arg).clock_probe;
+    unsigned long long *const clock_probe = const_cast<unsigned long long *>(probe_);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    if (p.clock_probe && blockIdx.x == 0 && threadIdx.x == 0) {
-        p.clock_probe[0] = (unsigned long long)clock64();
-        p.clock_probe[1] = (unsigned long long)wall_clock64();
+    if (clock_probe && blockIdx.x == 0 && threadIdx.x == 0) {
+        clock_probe[0] = (unsigned long long)clock64();
+        clock_probe[1] = (unsigned long long)wall_clock64();
     }
 
     // ---- persistent workgroup -> tiles.  Workgroup b runs on XCD b % 8 (round-robin dispatch); XCD x
     // owns a contiguous run of the tile order, and its workgroups stride through that run together.
-    const int ntiles = p.tile_count * (OUT_F32 ? p.splits : 1);   // work items: (K chunk, tile), chunk-major
+    const int ntiles = work_items(arg, OUT_F32);                  // work items: (K chunk, tile), chunk-major
     const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
     const int per = ntiles >> 3, rem = ntiles & 7;
     const int run_begin = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
@@ -330,9 +356,10 @@ void gemm_mfma_kernel(const GemmP p) {
         }
 
     for (int logical = run_begin + q; logical < run_end; logical += wg_per_xcd) {
-    int tm, tn;
-    const int chunk = OUT_F32 ? logical / p.tile_count : 0;
-    const int tl = logical - chunk * p.tile_count;             // tile within this launch
+    int tm, tn, item;
+    const GemmP p = pick(arg, logical, item);                  // (a group: the problem this work item belongs to)
+    const int chunk = OUT_F32 ? item / p.tile_count : 0;
+    const int tl = item - chunk * p.tile_count;                // tile within this launch
     tile_coords(p.tile_begin + tl, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     // this work item's K range (only the fp32-output kernels are ever split)
@@ -584,9 +611,9 @@ void gemm_mfma_kernel(const GemmP p) {
     }
     lds_barrier();      // staging area is free again: the next tile's first stage may overwrite it
     }   // tiles of this workgroup
-    if (p.clock_probe && blockIdx.x == 0 && threadIdx.x == 0) {
-        p.clock_probe[2] = (unsigned long long)clock64();
-        p.clock_probe[3] = (unsigned long long)wall_clock64();
+    if (clock_probe && blockIdx.x == 0 && threadIdx.x == 0) {
+        clock_probe[2] = (unsigned long long)clock64();
+        clock_probe[3] = (unsigned long long)wall_clock64();
     }
 }
 
@@ -623,6 +650,25 @@ hipError_t launch(const GemmP &p, hipStream_t st) {
     const int items = p.tile_count * (OUT_F32 ? p.splits : 1);
     if (items <= 0) return hipSuccess;
     kern<<<items < n_cu ? items : n_cu, 256, SMEM_BYTES, st>>>(p);
+    return hipGetLastError();
+}
+
+template <bool HAS_ADD, bool OUT_F32>
+hipError_t launch_group_tn(const GemmGroup &g, hipStream_t st) {
+    static bool configured = false;
+    auto kern = gemm_mfma_kernel<false, false, HAS_ADD, OUT_F32, GemmGroup>;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    int n_cu = 0;
+    hipError_t e = compute_units(n_cu);
+    if (e != hipSuccess) return e;
+    const int items = g.first[MAX_GROUP];
+    if (items <= 0) return hipSuccess;
+    kern<<<items < n_cu ? items : n_cu, 256, SMEM_BYTES, st>>>(g);
     return hipGetLastError();
 }
 
@@ -744,6 +790,33 @@ int gemm_mfma_tail_splits(const GemmArgs &g, int n_cu, int &tail_tiles) {
     if (s < 2 || (long)g.K * (s - 1) / s < 4096) return 1;
     tail_tiles = (int)rem;
     return (int)s;
+}
+
+// Weight-gradient products whose outputs have few tiles (at most 128: a narrow layer), run together: every tile of every
+// product is one work item with the whole contraction, so nothing is cut along K, nothing goes through scratch and one
+// launch fills the chip that each product alone would leave mostly idle.
+bool gemm_mfma_few_tiles(const GemmArgs &g) {
+    return g.layout == GEMM_TN && !g.bias && !g.residual && gemm_mfma_supported(g) &&
+           (long)ceil_div(g.M, BM) * ceil_div(g.N, BN) <= 128;
+}
+
+hipError_t gemm_mfma_group(const GemmArgs *gs, int n, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    if (n > MAX_GROUP) return hipErrorInvalidValue;
+    GemmGroup grp = {};
+    int total = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!gemm_mfma_few_tiles(gs[i]) || gs[i].accumulate != gs[0].accumulate || gs[i].c_f32 != gs[0].c_f32)
+            return hipErrorInvalidValue;
+        grp.p[i] = params(gs[i]);
+        grp.first[i] = total;
+        total += grp.p[i].tile_count;
+    }
+    for (int i = n; i <= MAX_GROUP; ++i) grp.first[i] = total;
+    for (int i = n; i < MAX_GROUP; ++i) grp.p[i] = grp.p[0];
+    grp.n = n;
+    if (gs[0].c_f32) return launch_group_tn<false, true>(grp, st);
+    return gs[0].accumulate ? launch_group_tn<true, false>(grp, st) : launch_group_tn<false, false>(grp, st);
 }
 
 hipError_t gemm_mfma(const GemmArgs &g, hipStream_t st) {

@@ -32,6 +32,10 @@ hipError_t gemm_simple(int dtype, const GemmArgs &g, hipStream_t st);
 // gemm_mfma.hip: bf16 MFMA kernel.  `supported` checks alignment requirements.
 bool gemm_mfma_supported(const GemmArgs &g);
 hipError_t gemm_mfma(const GemmArgs &g, hipStream_t st);
+// Weight gradients with few output tiles (gemm_mfma_few_tiles: transposed-A layout, no bias / residual, at most 128 tiles of
+// 256 x 256) computed together in one launch, none of them cut along K; up to 4, all with the same accumulate / c_f32.
+bool gemm_mfma_few_tiles(const GemmArgs &g);
+hipError_t gemm_mfma_group(const GemmArgs *gs, int n, hipStream_t st);
 
 // Segment bookkeeping produced by prep_tokens():
 //   tok_seg[t]  = index of the segment that holds token t
