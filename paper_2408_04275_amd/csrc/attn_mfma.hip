@@ -523,23 +523,28 @@ __device__ __forceinline__ float sum_across_halves(float v) {
 constexpr float LAZY_LOG2 = 8.f;
 
 // ------------------------------------------------------------------------------------------
-// forward.  512 threads: 8 wavefronts x 32 queries = 256 queries per workgroup (two wavefronts per SIMD, so that one can
-// run its softmax on the vector ALUs while the other occupies the matrix core), walking the keys 64 at a time through
+// forward.  WAVES wavefronts x 32 queries per workgroup, two wavefronts per SIMD either way (so that one can run its
+// softmax on the vector ALUs while the other occupies the matrix core): 8 wavefronts = 256 queries, one workgroup per
+// compute unit (every K / V tile is fetched once for 256 queries), or 4 wavefronts = 128 queries, two workgroups per
+// compute unit (less masked work on short segments; used for 64-wide heads).  The keys are walked 64 at a time through
 // two LDS slots of {K tile, V tile}, both copied global -> LDS directly in their memory order (wavefronts 4..7 copy K,
 // 0..3 copy V).  O^T = V^T . P^T takes V^T from the row-major tile by the transposing LDS read, the same scheme as
 // dQ^T = K^T . dS^T above.  One barrier per step: after it every wavefront has finished the previous step, so the slot
 // that step used may be refilled.
 // ------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
+template <int D, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 2) void attn_fwd_kernel(AttnArgs a) {
+    constexpr int FQW = WAVES * 32;                                // queries per workgroup
     constexpr int KS = D / 16, CB = D / 32;
     constexpr int TILE = BT2 * D * 2, SLOT = 2 * TILE;             // K tile, then V tile
-    constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                 // per wavefront (4 wavefronts per tile)
+    constexpr int COPIES = BT2 * D * 2 / 1024 / 4;                 // per wavefront and tile (four wavefronts copy a tile)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    add_busy(a.cu_busy, false);
-
     const int head = blockIdx.x, g = head / (a.nh / a.nkv);
-    const int q0 = (a.use_order ? a.order_q[blockIdx.y] : blockIdx.y) * FQ;
+    // the dispatch order is kept per FQ-query tile; the workgroups of one tile (two, with four wavefronts each) follow each other
+    constexpr int PER_TILE = FQ / FQW;
+    const int q0 = (a.use_order ? a.order_q[blockIdx.y / PER_TILE] * PER_TILE + blockIdx.y % PER_TILE : blockIdx.y) * FQW;
+    if (q0 >= a.T) return;                                         // second half of a last tile that the pack only half fills
+    add_busy(a.cu_busy, false);
     // the wavefront's index as a scalar: what is derived from it (copy destinations, buffer descriptors) stays uniform
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5, l32 = lane & 31;
     const int T = a.T;
@@ -553,7 +558,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
     const bool valid = q < T;
     const WaveBounds wb = wave_bounds(me, q0 + wave * 32, T);
     const int w_lo_min = wb.lo_min, w_lo_max = wb.lo_max, w_hi_max = wb.hi_max, w_hi_min = wb.hi_min;
-    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQ, T) - 1, T);
+    const RowInfo first = query_range(a.tok_info, q0, T), last = query_range(a.tok_info, min(q0 + FQW, T) - 1, T);
     const int kbeg = first.lo, kend = last.hi;
 
     bf16x8 qf[KS];                                     // this wavefront's Q rows as the MFMA's column operand (filled below)
@@ -565,21 +570,22 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(AttnArgs a) {
 
     const __amdgpu_buffer_rsrc_t rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv), 0, (int)(uint32_t)((size_t)T * ld * 2), 0x00020000);
-    // wavefronts 4..7 copy the K tile, wavefronts 0..3 the V tile
+    // eight wavefronts: 4..7 copy the K tile, 0..3 the V tile; four wavefronts: each copies its quarter of both
     RowCopier<D, COPIES> cp;
     cp.init((wave & 3) * COPIES, ld, dh);
     auto copy_kv = [&](uint8_t *slot, int kt) {
-        if (wave >= 4) cp.issue(rs, slot, kt, ld, nq + g * dh);
-        else cp.issue(rs, slot + TILE, kt, ld, nq + nk + g * dh);
+        if (WAVES == 4 || wave >= 4) cp.issue(rs, slot, kt, ld, nq + g * dh);
+        if (WAVES == 4 || wave < 4) cp.issue(rs, slot + TILE, kt, ld, nq + nk + g * dh);
     };
     TrReader<D> tr;
     tr.init((uint32_t)(uintptr_t)(lds_void *)smem);
 
-    // The Q rows go through LDS like the dQ kernel's Q, dO and O rows (see there), behind the two slots.
+    // The Q rows go through LDS like the dQ kernel's Q, dO and O rows (see there): behind the two slots, or, with four
+    // wavefronts (whose Q rows fill a slot exactly), in the second slot, which is first written after the first barrier.
     {
         RowCopier<D, ROWS32_BYTES<D> / 1024> cp_q;
         cp_q.init(0, ld, dh);
-        uint8_t *st_q = smem + 2 * SLOT + wave * ROWS32_BYTES<D>;
+        uint8_t *st_q = smem + (WAVES == 4 ? SLOT : 2 * SLOT) + wave * ROWS32_BYTES<D>;
         cp_q.issue(rs, st_q, q0 + wave * 32, ld, head * dh);
         copy_kv(smem, kbeg);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1122,16 +1128,23 @@ hipError_t set_smem(K kern, int bytes) {
     return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
+// Wavefronts per workgroup of the forward kernel: four for 64-wide heads (packs of ViT-sized segments: 0.068 -> 0.054 ms
+// on the encoder workload), eight for 128-wide heads (no difference there within 2 %, and half the K / V tile traffic).
+// The dQ kernel, which has the same structure, gains nothing from four (0.182 -> 0.185 ms backward on that workload).
+template <int D>
+constexpr int FWD_WAVES = D <= 64 ? 4 : 8;
+
 template <int D>
 hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
     static bool configured = false;
-    const int smem = std::max(2 * 2 * BT2 * D * 2 + 8 * ROWS32_BYTES<D>, 8 * STAGE_BYTES<D>);
+    constexpr int W = FWD_WAVES<D>;
+    const int smem = std::max(2 * 2 * BT2 * D * 2 + (W == 4 ? 0 : W * ROWS32_BYTES<D>), W * STAGE_BYTES<D>);
     if (!configured) {
-        hipError_t e = set_smem(attn_fwd_kernel<D>, smem);
+        hipError_t e = set_smem(attn_fwd_kernel<D, W>, smem);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    attn_fwd_kernel<D><<<dim3(a.nh, ceil_div(a.T, FQ)), 512, smem, st>>>(a);
+    attn_fwd_kernel<D, W><<<dim3(a.nh, ceil_div(a.T, FQ) * (FQ / (W * 32))), W * 64, smem, st>>>(a);
     return hipGetLastError();
 }
 

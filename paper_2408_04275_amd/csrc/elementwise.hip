@@ -441,6 +441,11 @@ hipError_t rope_inplace(int dtype, void *qkv, int ld, int T, int n_rot_heads, in
 
 // ---- SwiGLU --------------------------------------------------------------------------
 // gu[T, 2F] = [gate | up];  m = gate * sigmoid(gate) * up.
+// 1 / (1 + exp(-x)) with the hardware exponential and reciprocal (each within an fp32 rounding or two; the library's
+// expf and the IEEE division take some twenty instructions more per element)
+__device__ __forceinline__ float sigmoid_fast(float x) {
+    return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(x * -1.4426950408889634f));
+}
 template <typename T>
 __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T *__restrict__ gu, T *__restrict__ m, long nchunks, int F) {
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
@@ -452,7 +457,7 @@ __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T *__restrict__ g
     load8_stream(gu + t * 2 * F + c, g);
     load8_stream(gu + t * 2 * F + F + c, u);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) g[j] = g[j] / (1.f + expf(-g[j])) * u[j];
+    for (int j = 0; j < 8; ++j) g[j] = g[j] * sigmoid_fast(g[j]) * u[j];
     store8_stream(m + t * F + c, g);
 }
 
@@ -471,7 +476,7 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T *__restrict__ d
     load8_stream(d_m + t * F + c, dm);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const float s = 1.f / (1.f + expf(-g[j]));
+        const float s = sigmoid_fast(g[j]);
         const float dg = dm[j] * u[j] * s * (1.f + g[j] * (1.f - s));
         u[j] = dm[j] * g[j] * s;
         g[j] = dg;
@@ -496,6 +501,19 @@ hipError_t swiglu_bwd(int dtype, const void *d_m, const void *gu, void *d_gu, in
 }
 
 // ---- GELU (erf form) -----------------------------------------------------------------
+// Phi(v) and phi(v) of the standard normal distribution.  The library erff costs some forty vector instructions, which
+// made these kernels bound by the vector ALUs (GELU backward ran at 3.6 TB/s); this is the five-term rational
+// approximation of Abramowitz & Stegun 7.1.26, erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p x), x >= 0,
+// absolute error 1.5e-7, whose exponential exp(-v^2 / 2) is phi's as well: a dozen instructions for both.  In fp32
+// arithmetic Phi comes out within 3e-7 (absolute; an fp32 rounding of a value near 1 is 6e-8).
+__device__ __forceinline__ void normal_cdf_pdf(float v, float &cdf, float &pdf) {
+    const float e = __builtin_amdgcn_exp2f(v * v * -0.72134752044448170f);            // exp(-v^2 / 2)
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.23164189f, fabsf(v), 1.f));              // p / sqrt(2) = 0.3275911 / 1.41421356
+    const float poly = ((((1.061405429f * t - 1.453152027f) * t + 1.421413741f) * t - 0.284496736f) * t + 0.254829592f) * t;
+    const float h = 0.5f * poly * e;                                                     // the smaller tail
+    cdf = v >= 0.f ? 1.f - h : h;
+    pdf = 0.3989422804014327f * e;
+}
 template <typename T>
 __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ z, T *__restrict__ a, long nchunks) {
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
@@ -503,7 +521,11 @@ __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ z, 
     float v[8];
     load8(z + idx * 8, v);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = 0.5f * v[j] * (1.f + erff(v[j] * 0.70710678118654752f));
+    for (int j = 0; j < 8; ++j) {
+        float cdf, pdf;
+        normal_cdf_pdf(v[j], cdf, pdf);
+        v[j] *= cdf;
+    }
     store8(a + idx * 8, v);
 }
 // gelu'(z) = Phi(z) + z * phi(z)
@@ -517,8 +539,8 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T *__restrict__ d_a
     load8(d_a + idx * 8, g);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const float cdf = 0.5f * (1.f + erff(v[j] * 0.70710678118654752f));
-        const float pdf = 0.3989422804014327f * expf(-0.5f * v[j] * v[j]);
+        float cdf, pdf;
+        normal_cdf_pdf(v[j], cdf, pdf);
         v[j] = g[j] * (cdf + v[j] * pdf);
     }
     store8(d_z + idx * 8, v);
@@ -544,8 +566,8 @@ __global__ __launch_bounds__(256) void gelu_bwd_colsum_kernel(const T *__restric
             if (r + k < r1) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float cdf = 0.5f * (1.f + erff(v[k][j] * 0.70710678118654752f));
-                    const float pdf = 0.3989422804014327f * expf(-0.5f * v[k][j] * v[k][j]);
+                    float cdf, pdf;
+                    normal_cdf_pdf(v[k][j], cdf, pdf);
                     v[k][j] = g[k][j] * (cdf + v[k][j] * pdf);
                 }
                 store8(d_z + (size_t)(r + k) * N + c, v[k]);
