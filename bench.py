@@ -166,6 +166,9 @@ def main():
     ap.add_argument("--group", choices=["span", "sample"], default="span",
                     help="decoder workloads: 'span' = every text run / image span is a document of its own (default); 'sample' = "
                          "the whole 8192-token sequence is one causal document")
+    ap.add_argument("--seed-sweep", type=int, default=None,
+                    help="also time the layer on the packs of seeds 0 .. N-1 of the workload's generator (20 steps each) and report "
+                         "median and range over the packs; default 5 for workload 3, 0 otherwise")
     ap.add_argument("--recompute", action="store_true",
                     help="with --layers: keep only layer inputs in forward and recompute each layer in backward")
     args = ap.parse_args()
@@ -340,6 +343,30 @@ def main():
         "gemm_shader_clock_mhz": mm.gemm_clock_mhz(clock_probe),
         "context": PAPER_CONTEXT,
     }
+    # The same layer on other packs of the workload's generator: the step time depends on the pack through attention.
+    n_sweep = args.seed_sweep if args.seed_sweep is not None else (5 if args.config == 3 and args.seed is None else 0)
+    if n_sweep > 0 and args.config != 4:
+        del runner
+        torch.cuda.empty_cache()
+        pcts, mss = [], []
+        for sd in range(n_sweep):
+            cu_s, modes_s, _ = wl.make_segments(args.config, sd, group=args.group)
+            r = LayerRunner(shape, W, cu_s, modes_s)
+            r.set_inputs(*wl.make_activations(shape, int(cu_s[-1]), sd))
+            for _ in range(3):
+                r.step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                r.step()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / 20
+            mss.append(ms)
+            pcts.append(100.0 * wl.model_flops(shape, cu_s, modes_s)["fwd_bwd"] / (ms * 1e-3) / 1e12 / peak)
+            del r
+        out["seed_sweep"] = {"seeds": list(range(n_sweep)), "steps_each": 20, "ms_per_step": mss, "pct_of_peak": pcts,
+                             "median_pct": float(np.median(pcts)), "min_pct": float(min(pcts)), "max_pct": float(max(pcts))}
+        runner = None
     if not args.no_cpu_baseline:
         del runner
         torch.cuda.empty_cache()
