@@ -42,7 +42,8 @@ struct Ctx {
 
 struct BwdWs {
     void *d_m, *d_pre, *d_h, *d_y1, *d_o, *d_qkv;
-    float *Dsum, *part_g, *part_b, *part_c, *part_din, *part_dres;
+    float *Dsum, *part_g, *part_b, *part_c, *part_din, *part_dres;      // partial sums of the second normalisation's backward pass and of fc1's bias
+    float *part_g1, *part_b1, *part_c2;                                 // ... of the first normalisation's and of the QKV bias (all reduced at the end of the pass)
     void *split_ws; size_t split_bytes;     // fp32 partial products of split weight-gradient GEMMs
 };
 
@@ -158,6 +159,9 @@ void carve_bwd(Bump &b, const Dims &D, size_t T, BwdWs &w) {
     w.part_dres = enc ? b.take<float>((size_t)norm_bwd_blocks((int)T, D.H) * D.H) : nullptr;
     const int maxn = D.nqkv > D.F1 ? (D.nqkv > D.H ? D.nqkv : D.H) : (D.F1 > D.H ? D.F1 : D.H);
     w.part_c = b.take<float>((size_t)colsum_slabs((int)T) * maxn);
+    w.part_g1 = b.take<float>((size_t)norm_bwd_blocks((int)T, D.H) * D.H);
+    w.part_b1 = enc ? b.take<float>((size_t)norm_bwd_blocks((int)T, D.H) * D.H) : nullptr;
+    w.part_c2 = enc ? b.take<float>((size_t)colsum_slabs((int)T) * D.nqkv) : nullptr;
     // scratch for the fp32 partial products of GEMMs that are cut along K (see gemm_scratch_bytes)
     auto need = [](size_t M, size_t N) -> size_t { return gemm_scratch_bytes(M, N); };
     size_t sb = 0;
@@ -404,9 +408,16 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.F, D.H, dy, D.H, W->w_fc2, D.F, w.d_m, D.F), w.split_ws, w.split_bytes), st));
     DeferredWgrads later;
     if (G.w_fc2) HIP_TRY(wgrad(D.dtype, splittable(f32out(mk(GEMM_TN, D.H, D.F, T, dy, D.H, c.m, D.F, G.w_fc2, D.F, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), later, st));
+    // Partial sums (gain, bias and column-sum gradients) are reduced by ONE launch at the end of the pass: every array
+    // has a buffer of its own in the workspace.
+    ReduceJob jobs[8];
+    int n_jobs = 0;
+    auto reduce_later = [&](const float *part, void *out, int rows, int N) {
+        if (part && out) jobs[n_jobs++] = {part, out, rows, N};
+    };
     if (enc && G.b_fc1) {                         // the bias gradient is the column sum of what this kernel writes
         HIP_TRY_TIMED(MMTRAIN_PROF_ACT_BWD, st, gelu_bwd_colsum(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F1, w.part_c, st));
-        HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.F1, G.b_fc1, accum, st));
+        reduce_later(w.part_c, G.b_fc1, ns, D.F1);
     } else if (enc) HIP_TRY_TIMED(MMTRAIN_PROF_ACT_BWD, st, gelu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, (long)T * D.F, st));
     else HIP_TRY_TIMED(MMTRAIN_PROF_ACT_BWD, st, swiglu_bwd(D.dtype, w.d_m, c.pre, w.d_pre, T, D.F, st));
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.H, D.F1, w.d_pre, D.F1, W->w_fc1, D.H, w.d_h, D.H), w.split_ws, w.split_bytes), st));
@@ -415,10 +426,11 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     HIP_TRY_TIMED(MMTRAIN_PROF_NORM_BWD, st, norm_bwd(D.dtype, enc, w.d_h, c.y1, W->norm2_w, c.mean2, c.rstd2, dy, w.d_y1,
                      G.norm2_w ? w.part_g : nullptr, (enc && G.norm2_b) ? w.part_b : nullptr,
                      (enc && G.b_o) ? w.part_din : nullptr, (enc && G.b_fc2) ? w.part_dres : nullptr, T, D.H, st));
-    {
-        const float *parts[4] = {w.part_g, w.part_b, w.part_din, w.part_dres};
-        void *outs[4] = {G.norm2_w, enc ? G.norm2_b : nullptr, enc ? G.b_o : nullptr, enc ? G.b_fc2 : nullptr};
-        HIP_TRY(reduce_partials_set(gdt, parts, outs, 4, nb, D.H, accum, st));
+    reduce_later(w.part_g, G.norm2_w, nb, D.H);
+    if (enc) {
+        reduce_later(w.part_b, G.norm2_b, nb, D.H);
+        reduce_later(w.part_din, G.b_o, nb, D.H);
+        reduce_later(w.part_dres, G.b_fc2, nb, D.H);
     }
 
     // ---- attention block:  y1 = x + o . Wo^T (+ b_o)
@@ -434,19 +446,17 @@ int mmtrain_layer_bwd(const mmtrain_layer_desc *desc, const mmtrain_batch *batch
     }
     if (!enc && !fused_unrotate) HIP_TRY_TIMED(MMTRAIN_PROF_ROPE, st, rope_inplace(D.dtype, w.d_qkv, D.nqkv, T, D.nh + D.nkv, D.d, c.rope_cs, true, st));
     if (enc && G.b_qkv) {
-        HIP_TRY(colsum_partials(D.dtype, w.d_qkv, T, D.nqkv, D.nqkv, w.part_c, st));
-        HIP_TRY(reduce_partials(gdt, w.part_c, ns, D.nqkv, G.b_qkv, accum, st));
+        HIP_TRY(colsum_partials(D.dtype, w.d_qkv, T, D.nqkv, D.nqkv, w.part_c2, st));
+        reduce_later(w.part_c2, G.b_qkv, ns, D.nqkv);
     }
     HIP_TRY(gemm(D.dtype, splittable(mk(GEMM_NN, T, D.H, D.nqkv, w.d_qkv, D.nqkv, W->w_qkv, D.H, w.d_h, D.H), w.split_ws, w.split_bytes), st));
     if (G.w_qkv) HIP_TRY(wgrad(D.dtype, splittable(f32out(mk(GEMM_TN, D.nqkv, D.H, T, w.d_qkv, D.nqkv, c.h1, D.H, G.w_qkv, D.H, nullptr, nullptr, accum), g32), w.split_ws, w.split_bytes), later, st));
     // dx = d_y1 + norm1_bwd(d_h1)
     HIP_TRY_TIMED(MMTRAIN_PROF_NORM_BWD, st, norm_bwd(D.dtype, enc, w.d_h, x, W->norm1_w, c.mean1, c.rstd1, w.d_y1, dx,
-                     G.norm1_w ? w.part_g : nullptr, (enc && G.norm1_b) ? w.part_b : nullptr, nullptr, nullptr, T, D.H, st));
-    {
-        const float *parts[2] = {w.part_g, w.part_b};
-        void *outs[2] = {G.norm1_w, enc ? G.norm1_b : nullptr};
-        HIP_TRY(reduce_partials_set(gdt, parts, outs, 2, nb, D.H, accum, st));
-    }
+                     G.norm1_w ? w.part_g1 : nullptr, (enc && G.norm1_b) ? w.part_b1 : nullptr, nullptr, nullptr, T, D.H, st));
+    reduce_later(w.part_g1, G.norm1_w, nb, D.H);
+    if (enc) reduce_later(w.part_b1, G.norm1_b, nb, D.H);
+    HIP_TRY(reduce_jobs(gdt, jobs, n_jobs, accum, st));
     HIP_TRY(run_deferred(later, st));
     return MMTRAIN_OK;
 }

@@ -34,6 +34,7 @@
 // multiple of 16, e.g. 80) uses the next instantiation with the missing features read as zero and never
 // stored.
 #include "kernels.h"
+#include <atomic>
 #include <algorithm>
 #include <type_traits>
 #include <utility>
@@ -1136,13 +1137,13 @@ constexpr int FWD_WAVES = D <= 64 ? 4 : 8;
 
 template <int D>
 hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
-    static bool configured = false;
+    static std::atomic<bool> configured{false};     // set once; concurrent first calls repeat the same idempotent set-up
     constexpr int W = FWD_WAVES<D>;
     const int smem = std::max(2 * 2 * BT2 * D * 2 + (W == 4 ? 0 : W * ROWS32_BYTES<D>), W * STAGE_BYTES<D>);
-    if (!configured) {
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = set_smem(attn_fwd_kernel<D, W>, smem);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     attn_fwd_kernel<D, W><<<dim3(a.nh, ceil_div(a.T, FQ) * (FQ / (W * 32))), W * 64, smem, st>>>(a);
     return hipGetLastError();
@@ -1150,17 +1151,17 @@ hipError_t launch_fwd(const AttnArgs &a, hipStream_t st) {
 
 template <int D>
 hipError_t launch_bwd(const AttnArgs &a, hipStream_t st) {
-    static bool configured = false;
+    static std::atomic<bool> configured{false};     // set once; concurrent first calls repeat the same idempotent set-up
     constexpr bool PIPELINED = D > 64;                  // see attn_dkv_plain_kernel
     constexpr int DKV_SLOT = 2 * BT2 * D * 2 + 2 * BT2 * 4;
     const int smem_dq = std::max(DQ_LDS_BYTES<D>, 8 * STAGE_BYTES<D>), smem_dkv = PIPELINED ? 3 * DKV_SLOT + DKV_STAGE_BYTES<D> : 2 * DKV_SLOT + 2 * DKV_STAGE_BYTES<D>;
-    if (!configured) {
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = set_smem(attn_dq_kernel<D>, smem_dq);
         if (e != hipSuccess) return e;
         if constexpr (PIPELINED) e = set_smem(attn_dkv_kernel<D>, smem_dkv);
         else e = set_smem(attn_dkv_plain_kernel<D>, smem_dkv);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     attn_dq_kernel<D><<<dim3(a.nh, ceil_div(a.T, FQ)), 512, smem_dq, st>>>(a);
     if constexpr (PIPELINED) attn_dkv_kernel<D><<<dim3(a.nkv, ceil_div(a.T, BQ)), 256, smem_dkv, st>>>(a);

@@ -320,12 +320,15 @@ hipError_t reduce_partials(int dtype, const float *part, int rows, int N, void *
     return hipGetLastError();
 }
 
-// Up to four reductions of the same shape in one launch (blockIdx.y picks the array): the gain, bias and column-sum
-// partial sums that one normalisation-backward launch leaves behind.
-struct ReduceSet { const float *part[4]; void *out[4]; };
+// Up to eight reductions of different shapes in one launch (blockIdx.y picks the job): everything a backward pass leaves
+// behind as partial sums -- gain and bias gradients of both normalisations, the bias gradients of the four linears --
+// is added up by one kernel at the end of the pass instead of by one launch where each array is produced.
+struct ReduceJobSet { const float *part[8]; void *out[8]; int rows[8]; int N[8]; };
 template <typename T>
-__global__ __launch_bounds__(256) void reduce_partials_set_kernel(ReduceSet set, int rows, int N, bool accumulate) {
+__global__ __launch_bounds__(256) void reduce_jobs_kernel(ReduceJobSet set, bool accumulate) {
     __shared__ float red[32][36];
+    const int N = set.N[blockIdx.y], rows = set.rows[blockIdx.y];
+    if (blockIdx.x * 32 >= N) return;                                 // the grid is as wide as the widest job
     const float *part = set.part[blockIdx.y];
     T *out = (T *)set.out[blockIdx.y];
     const int cl = threadIdx.x & 7, rl = threadIdx.x >> 3;
@@ -345,23 +348,28 @@ __global__ __launch_bounds__(256) void reduce_partials_set_kernel(ReduceSet set,
     }
 }
 
-hipError_t reduce_partials_set(int dtype, const float *const *parts, void *const *outs, int n, int rows, int N,
-                               bool accumulate, hipStream_t st) {
-    ReduceSet set = {};
-    int m = 0;
-    for (int i = 0; i < n && m < 4; ++i)
-        if (parts[i] && outs[i]) { set.part[m] = parts[i]; set.out[m] = outs[i]; ++m; }
-    if (m == 0 || N == 0) return hipSuccess;
-    if (N % 4) {                                   // the vector form needs whole quads: fall back to one launch each
+hipError_t reduce_jobs(int dtype, const ReduceJob *jobs, int n, bool accumulate, hipStream_t st) {
+    ReduceJobSet set = {};
+    int m = 0, widest = 0;
+    bool quads = true;
+    for (int i = 0; i < n && m < 8; ++i) {
+        if (!jobs[i].part || !jobs[i].out || jobs[i].N <= 0) continue;
+        set.part[m] = jobs[i].part; set.out[m] = jobs[i].out; set.rows[m] = jobs[i].rows; set.N[m] = jobs[i].N;
+        widest = jobs[i].N > widest ? jobs[i].N : widest;
+        quads = quads && jobs[i].N % 4 == 0;
+        ++m;
+    }
+    if (m == 0) return hipSuccess;
+    if (!quads) {                                  // the vector form needs whole quads: one launch each
         for (int i = 0; i < m; ++i) {
-            hipError_t e = reduce_partials(dtype, set.part[i], rows, N, set.out[i], accumulate, st);
+            hipError_t e = reduce_partials(dtype, set.part[i], set.rows[i], set.N[i], set.out[i], accumulate, st);
             if (e != hipSuccess) return e;
         }
         return hipSuccess;
     }
-    dim3 grid(ceil_div(N, 32), m);
-    if (dtype == DT_F32) reduce_partials_set_kernel<float><<<grid, 256, 0, st>>>(set, rows, N, accumulate);
-    else reduce_partials_set_kernel<bf16_t><<<grid, 256, 0, st>>>(set, rows, N, accumulate);
+    dim3 grid(ceil_div(widest, 32), m);
+    if (dtype == DT_F32) reduce_jobs_kernel<float><<<grid, 256, 0, st>>>(set, accumulate);
+    else reduce_jobs_kernel<bf16_t><<<grid, 256, 0, st>>>(set, accumulate);
     return hipGetLastError();
 }
 

@@ -31,6 +31,7 @@
 // XCD works on a contiguous run of the tile order, which goes in column-major groups of 8
 // tile-rows so that concurrently resident tiles share A and B panels.
 #include "kernels.h"
+#include <atomic>
 #include <utility>
 #include <type_traits>
 
@@ -619,7 +620,8 @@ void gemm_mfma_kernel(const ARG arg) {
 
 // compute units of the current device, rounded down to whole XCD octets (one persistent workgroup each)
 hipError_t compute_units(int &n) {
-    static int n_cu = 0;
+    static std::atomic<int> cached{0};
+    int n_cu = cached.load(std::memory_order_relaxed);
     if (n_cu == 0) {
         int dev = 0, v = 0;
         hipError_t e = hipGetDevice(&dev);
@@ -628,6 +630,7 @@ hipError_t compute_units(int &n) {
         if (v <= 0) v = 256;
         v &= ~7;
         n_cu = v ? v : 8;
+        cached.store(n_cu, std::memory_order_relaxed);
     }
     n = n_cu;
     return hipSuccess;
@@ -635,13 +638,13 @@ hipError_t compute_units(int &n) {
 
 template <bool A_KC, bool B_KC, bool HAS_ADD, bool OUT_F32 = false>
 hipError_t launch(const GemmP &p, hipStream_t st) {
-    static bool configured = false;
+    static std::atomic<bool> configured{false};     // set once; concurrent first calls repeat the same idempotent set-up
     auto kern = gemm_mfma_kernel<A_KC, B_KC, HAS_ADD, OUT_F32>;
-    if (!configured) {
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     // one persistent workgroup per compute unit (the tile needs the CU's whole LDS and register file)
     int n_cu = 0;
@@ -655,13 +658,13 @@ hipError_t launch(const GemmP &p, hipStream_t st) {
 
 template <bool HAS_ADD, bool OUT_F32>
 hipError_t launch_group_tn(const GemmGroup &g, hipStream_t st) {
-    static bool configured = false;
+    static std::atomic<bool> configured{false};     // set once; concurrent first calls repeat the same idempotent set-up
     auto kern = gemm_mfma_kernel<false, false, HAS_ADD, OUT_F32, GemmGroup>;
-    if (!configured) {
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     int n_cu = 0;
     hipError_t e = compute_units(n_cu);

@@ -98,10 +98,10 @@ hipError_t norm_bwd(int dtype, bool layernorm, const void *d_out, const void *x,
 // out[c] (+)= sum_r part[r, c]
 hipError_t reduce_partials(int dtype, const float *part, int rows, int N, void *out, bool accumulate,
                            hipStream_t st);
-// the same for up to 4 arrays of one shape in a single launch; pairs with a null member are skipped
-hipError_t reduce_partials_set(int dtype, const float *const *parts, void *const *outs, int n, int rows, int N,
-                               bool accumulate, hipStream_t st);
 int colsum_slabs(int T);
+// out[N] (+)= the sum of the rows of part[rows, N], for up to eight arrays of different shapes in one launch (null part or out: skipped)
+struct ReduceJob { const float *part; void *out; int rows, N; };
+hipError_t reduce_jobs(int dtype, const ReduceJob *jobs, int n, bool accumulate, hipStream_t st);
 hipError_t colsum_partials(int dtype, const void *in, int T, int N, int ld, float *part, hipStream_t st);
 hipError_t rope_inplace(int dtype, void *qkv, int ld, int T, int n_rot_heads, int d, const float2 *rope_cs,
                         bool inverse, hipStream_t st);
