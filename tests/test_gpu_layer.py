@@ -55,6 +55,21 @@ def test_peaky_softmax_decoder():
     run_case(shape, RAGGED_CU, RAGGED_MODES, seed=3, std=0.15, what="peaky decoder ")
 
 
+# ---- many rows on a narrow layer: the row-walking kernels take several rows per workgroup --------------------
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("kind", [wl.DECODER, wl.ENCODER])
+def test_many_rows_narrow_layer(kind, dtype):
+    # 5003 tokens, 144 wide: more rows than the normalisation kernels have workgroups (each walks several rows, the
+    # next one requested ahead), a last workgroup with fewer rows, and column counts that end inside a thread's chunk
+    rng = np.random.default_rng(11)
+    T = 5003
+    cuts = np.sort(rng.choice(np.arange(1, T), size=47, replace=False))
+    cu = np.concatenate([[0], cuts, [T]]).astype(np.int32)
+    modes = (np.ones(48, dtype=np.uint8) if kind == wl.ENCODER else rng.integers(0, 2, size=48).astype(np.uint8))
+    shape = wl.LayerShape("rows", kind, dtype, 144, 2, 2 if kind == wl.ENCODER else 1, 64, 272, T)
+    run_case(shape, cu, modes, seed=5, std=0.05, what=f"many rows kind={kind} dtype={dtype} ")
+
+
 # ---- edge cases ----------------------------------------------------------------------
 def test_empty_pack():
     shape = wl.LayerShape("e", wl.DECODER, wl.BF16, 256, 4, 2, 64, 512, 0)
