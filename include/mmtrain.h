@@ -44,6 +44,14 @@
  * Asynchrony.  Calls validate on the host, enqueue kernels on `hip_stream`
  * (a hipStream_t; NULL = the default stream) and return without synchronising.
  *
+ * Threads and devices.  The library is written for one GPU per process (the
+ * device that is current at the first call).  Calls may come from several host
+ * threads on different streams as long as each has its own ctx and workspace:
+ * what the library sets up at first use (kernel attributes, the device's unit
+ * counts, a per-thread cache of the attention tile order) is idempotent.  The
+ * measurement aids (mmtrain_profile_*) are process-wide and not thread-safe;
+ * mmtrain_attn_bwd_noalloc shares one scratch array per device.
+ *
  * Errors.  Every call returns an mmtrain_status (0 = OK, negative = error).
  * Argument and segment validation happens before any HIP call; on such an error
  * nothing has been enqueued.  The library never throws and never aborts.
