@@ -15,8 +15,8 @@ PROGRESS_LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__fi
 
 
 def say(msg):
-    """Progress line of a long test: appended to gpurun_out/progress.log (pytest captures stdout/stderr),
-    so that a long oracle run leaves a trace while it works."""
+    """Progress line of a long test: appended to PROGRESS_LOG (pytest captures stdout/stderr), so that a long oracle
+    run leaves a trace while it works."""
     line = f"[{time.strftime('%H:%M:%S')}] {msg}"
     print(line, flush=True)
     try:
