@@ -8,6 +8,9 @@ both additive over the samples of a pack:
 
     step_ms(pack) = c0 + a * tokens + b * pairs          cost(sample) = a * tokens + b * pairs(sample)
 
+The GEMMs work on tiles of 256 token rows, so a pack's `tokens` is its token count rounded up to whole tiles (a
+5144-token pack runs as long as a 5376-token one); a sample's cost uses its own length, which keeps the costs additive.
+
 `measure` times forward + backward of a pack with HIP events on the launch stream; `fit` solves the least-squares
 problem; `sample_costs` turns segment lengths into the `sizes` argument of mmtrain_intra_reorder.
 
@@ -26,9 +29,13 @@ import numpy as np
 from . import workloads as wl
 
 
+TILE_ROWS = 256          # rows of a GEMM tile: a pack costs what its token count rounded up to whole tiles costs
+
+
 def pack_features(cu: np.ndarray, modes: np.ndarray) -> Tuple[int, int]:
-    """(tokens, unmasked pairs) of a pack."""
-    return int(cu[-1]), wl.attention_pairs(cu, modes)
+    """(tokens rounded up to whole GEMM tiles, unmasked pairs) of a pack."""
+    T = int(cu[-1])
+    return -(-T // TILE_ROWS) * TILE_ROWS, wl.attention_pairs(cu, modes)
 
 
 def measure(shape: wl.LayerShape, W, cu: np.ndarray, modes: np.ndarray, steps: int = 10, warmup: int = 3) -> float:

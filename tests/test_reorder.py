@@ -96,7 +96,7 @@ def test_c_abi_matches_the_oracle():
 
 def test_cost_model_fit_recovers_its_coefficients_and_feeds_the_reordering():
     # the fit (least squares of c0 + a tokens + b pairs) on synthetic timings with known coefficients and 1 % noise;
-    # the GPU test of the same name in tests/test_gpu_costmodel.py fits this library's measured step time instead
+    # the GPU test of the same name in tests/test_zy_gpu_costmodel.py fits this library's measured step time instead
     from paper_2408_04275_amd import costmodel as cm
     from paper_2408_04275_amd import workloads as wl
     rng = np.random.default_rng(3)

@@ -1,6 +1,10 @@
 """The cost input of the paper's intra-microbatch reordering (Algorithm 1, Section 5.2), produced by code: this library's
 event-timed step time fitted as c0 + a * tokens + b * unmasked pairs on the 7B-shaped layer, checked on held-out packs,
-and then used as the sizes mmtrain_intra_reorder balances -- with the resulting groups timed on the GPU."""
+and then used as the sizes mmtrain_intra_reorder balances -- with the resulting groups timed on the GPU.
+
+The assertions of this file are about timings, which vary from box to box; its name makes pytest collect it after the
+parity tests (and before the no-allocation test, which has to come last), so that a timing missed on a slow box cannot
+keep the parity tests from running under `pytest -x`."""
 import numpy as np
 import pytest
 
