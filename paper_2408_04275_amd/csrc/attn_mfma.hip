@@ -22,7 +22,7 @@
 // which the accumulator registers hold them: all kernels keep the tiles row-major in LDS, as they are copied, and form
 // the transposed fragments with the transposing LDS read.
 //
-// The backward pass is two kernels: dQ (same roles as forward; also writes D = rowsum(dO * O)),
+// The backward pass is two kernels: dQ (same roles as forward; also writes -D, D = rowsum(dO * O), for the second),
 // then dK/dV with one KEY per lane, looping over the query tiles that can see the workgroup's
 // keys and over the query heads of the key/value head's group, so grouped-query gradients are
 // summed in registers and nothing needs atomics: results are deterministic.  The dK/dV kernel has two forms: for
@@ -78,6 +78,21 @@ __device__ __forceinline__ f32x16 zero16() {
 }
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+
+// The same MFMA written as assembly, with its result in VECTOR registers and its column operand in ACCUMULATION registers.
+// In a kernel that needs more than 256 registers the compiler gives every MFMA builtin an accumulation-register result,
+// and a result the vector ALU reads next (a score) then costs one copy instruction per element; operands that only MFMAs
+// read (a wavefront's own K and V rows) can live in the accumulation half instead.  The compiler does not know what
+// these statements are: whoever uses them keeps a result away from the vector ALU until the MFMA has retired
+// (mfma_results_settle, or enough other work in between), and never lets two of them in a row depend on each other's result.
+__device__ __forceinline__ void mfma_v_first(f32x16 &acc, const bf16x8 &rows, const bf16x8 &cols_acc) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(rows), "a"(cols_acc));
+}
+__device__ __forceinline__ void mfma_v(f32x16 &acc, const bf16x8 &rows, const bf16x8 &cols_acc) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(rows), "a"(cols_acc));
+}
+// more wait states than the eight passes of the MFMA above plus its write-back take
+__device__ __forceinline__ void mfma_results_settle() { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); }
 
 
 // Per-compute-unit busy time (measurement aid): a workgroup adds its run time, in ticks of the constant 100 MHz
@@ -352,7 +367,7 @@ __device__ __forceinline__ void store_rows(uint8_t *stage, const f32x16 (&acc)[C
 }
 
 // ------------------------------------------------------------------------------------------
-// backward: dQ (and D = rowsum(dO * O)).  Same roles as the forward kernel: 8 wavefronts x 32 queries.
+// backward: dQ (and -D, D = rowsum(dO * O)).  Same roles as the forward kernel: 8 wavefronts x 32 queries.
 // ------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
@@ -437,8 +452,15 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
     float lse2 = 0.f;                                  // log-sum-exp in log2 units
     if (valid) {
         lse2 = a.lse[(long)head * T + q] * LOG2E;
-        if (half == 0) a.Dsum[(long)head * T + q] = Dq;
+        if (half == 0) a.Dsum[(long)head * T + q] = -Dq;                // the dK/dV kernels add it
     }
+    // With 64-wide heads dP - D comes out of the matrix core: the dP product of every block starts from -D instead of
+    // from zero (a lane holds keys of ONE query, so the 16 accumulator registers of a lane all start from that query's
+    // -D).  The 128-wide kernel has no 16 registers to hold that operand and subtracts D element by element.
+    constexpr bool D_IN_MFMA = D <= 64;
+    f32x16 negD;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) negD[i] = D_IN_MFMA ? -Dq : 0.f;
     f32x16 dq[CB];
 #pragma unroll
     for (int c = 0; c < CB; ++c) dq[c] = zero16();
@@ -454,7 +476,7 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
             constexpr int b = decltype(B_)::value;
             const int kb = kt + 32 * b;
             if (!((kb < w_hi_max) && (kb + 32 > w_lo_min))) return;
-            f32x16 s = zero16(), dp = zero16();
+            f32x16 s = zero16(), dp = negD;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 s = MFMA(frag_k<D>(sK, 32 * b + l32, ks, half), qf[ks], s);
@@ -485,7 +507,7 @@ __global__ __launch_bounds__(512) void attn_dq_kernel(AttnArgs a) {
                 for (int i = 0; i < 16; ++i) {
                     float p = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lse2));
                     if (decltype(MASK_)::value) p = (unsigned)(rel + 8 * (i >> 2) + (i & 3)) < span ? p : 0.f;
-                    ds[i] = p * (dp[i] - Dq);
+                    ds[i] = D_IN_MFMA ? p * dp[i] : p * (dp[i] - Dq);
                 }
             };
             if (inside) softmax(std::false_type{});
@@ -785,13 +807,15 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
     };
     // the scores of block 0 of the current tile, on their own
     auto scores0 = [&]() {
-        sc[0] = zero16(); dpc[0] = zero16();
         static_for<0, 2 * KS>([&](auto J_) {
             constexpr int j = decltype(J_)::value;
             const bf16x8 f = score_frag(fcur, std::integral_constant<int, 0>{}, J_);
-            if constexpr ((j & 1) == 0) sc[0] = MFMA(f, kf[j >> 1], sc[0]);
-            else dpc[0] = MFMA(f, vf[j >> 1], dpc[0]);
+            if constexpr (j == 0) mfma_v_first(sc[0], f, kf[0]);
+            else if constexpr (j == 1) mfma_v_first(dpc[0], f, vf[0]);
+            else if constexpr ((j & 1) == 0) mfma_v(sc[0], f, kf[j >> 1]);
+            else mfma_v(dpc[0], f, vf[j >> 1]);
         });
+        mfma_results_settle();                         // the softmax reads them next
     };
     // block b of the current tile: softmax from (sc[b], dpc[b]) with the look-ahead scores of the block after it into
     // (sc[b ^ 1], dpc[b ^ 1]), then dV += dO^T P and dK += Q^T dS
@@ -813,15 +837,18 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
             static_for<0, PF>([&](auto J_) { issue_frag(fr[decltype(J_)::value], fa, BN, J_); });
             __builtin_amdgcn_sched_barrier(0);         // the copies of this block's scores out of the accumulation registers follow
             float pprev = 0.f, dprev = 0.f;
-            sc[b ^ 1] = zero16(); dpc[b ^ 1] = zero16();
             static_for<0, 16>([&](auto E_) {
                 constexpr int e = decltype(E_)::value, gq = e >> 2, el = e & 3;
                 if constexpr (el == 0) { lds_wait<Sched::allowed_d(e)>(l4[gq]); lds_wait<Sched::allowed_d(e)>(d4[gq]); }
                 if constexpr (e % PER_M == 0) {
                     constexpr int j = e / PER_M;
                     lds_wait<Sched::allowed_frag(e)>(fr[j]);
-                    if constexpr ((j & 1) == 0) sc[b ^ 1] = MFMA(fr[j], kf[j >> 1], sc[b ^ 1]);
-                    else dpc[b ^ 1] = MFMA(fr[j], vf[j >> 1], dpc[b ^ 1]);
+                    // (the vector ALU reads these results no earlier than the next block's softmax, behind this block's
+                    // 4 CB dV / dK products; the two chains alternate, so no MFMA follows the one whose result it adds to)
+                    if constexpr (j == 0) mfma_v_first(sc[b ^ 1], fr[j], kf[0]);
+                    else if constexpr (j == 1) mfma_v_first(dpc[b ^ 1], fr[j], vf[0]);
+                    else if constexpr ((j & 1) == 0) mfma_v(sc[b ^ 1], fr[j], kf[j >> 1]);
+                    else mfma_v(dpc[b ^ 1], fr[j], vf[j >> 1]);
                     if constexpr (j + PF < NM) issue_frag(fr[j + PF], fa, BN, std::integral_constant<int, j + PF>{});
                 }
                 if constexpr (e % PER_R == 0) {                      // read r: feature block r / 4; dO or Q; first or second quad
@@ -838,7 +865,7 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
                 const float lv = l4[gq][el], dvv = d4[gq][el];
                 float pv = __builtin_amdgcn_exp2f(fmaf(sc[b][e], sl2, -lv * LOG2E));
                 if (MASK) pv = (unsigned)(mbase + (32 * b + 8 * gq + el)) < span ? pv : 0.f;
-                const float dsv = pv * (dpc[b][e] - dvv);
+                const float dsv = pv * (dpc[b][e] + dvv);           // the D array holds -D
                 if constexpr (e & 1) { pp[e >> 1] = pack_bf16x2(pprev, pv); dd[e >> 1] = pack_bf16x2(dprev, dsv); }
                 else { pprev = pv; dprev = dsv; }
                 __builtin_amdgcn_sched_barrier(0);
@@ -1079,7 +1106,7 @@ __global__ __launch_bounds__(256) void attn_dkv_plain_kernel(AttnArgs a) {
                         float pv = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -lv[e] * LOG2E));
                         if (MASK) pv = (unsigned)(qt + r0 + e - me.lo) < span ? pv : 0.f;
                         p[i] = pv;
-                        ds[i] = pv * (dp[i] - dvv[e]);
+                        ds[i] = pv * (dp[i] + dvv[e]);                 // the D array holds -D
                     }
                 }
             };
