@@ -1062,13 +1062,16 @@ __global__ __launch_bounds__(256) void attn_dkv_plain_kernel(AttnArgs a) {
             constexpr int b = decltype(B_)::value;
             const int qb = qt + 32 * b;
             if (!((qb < w_hi_max) && (qb + 32 > w_lo_min))) return;
-            // S[q, key] and dP[q, key]: rows = queries (registers), columns = keys (lanes)
-            f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                s = MFMA(frag_k<D>(sQ, 32 * b + l32, ks, half), kf[ks], s);
-                dp = MFMA(frag_k<D>(sdO, 32 * b + l32, ks, half), vf[ks], dp);
-            }
+            // S[q, key] and dP[q, key]: rows = queries (registers), columns = keys (lanes); as assembly, so that the
+            // results land in vector registers (see mfma_v), with the wait the vector ALU needs before it reads them
+            f32x16 s, dp;
+            static_for<0, KS>([&](auto K_) {
+                constexpr int ks = decltype(K_)::value;
+                const bf16x8 fq = frag_k<D>(sQ, 32 * b + l32, ks, half), fo = frag_k<D>(sdO, 32 * b + l32, ks, half);
+                if constexpr (ks == 0) { mfma_v_first(s, fq, kf[0]); mfma_v_first(dp, fo, vf[0]); }
+                else { mfma_v(s, fq, kf[ks]); mfma_v(dp, fo, vf[ks]); }
+            });
+            mfma_results_settle();
             const uint32_t tq = slot * SLOT, tdo = tq + TILE;
             // dO^T and Q^T fragments of MFMA 0 of the block
             shortx4 o0[4], o1[4], q0f[4], q1f[4];
