@@ -415,8 +415,24 @@ __global__ __launch_bounds__(256) void reduce_partials_vec_kernel(const float *_
     const int cl = threadIdx.x & 7, rl = threadIdx.x >> 3;
     const int c = blockIdx.x * 32 + cl * 4;
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    if (c < N)
-        for (int r = rl; r < rows; r += 32) s += *reinterpret_cast<const f32x4 *>(part + (size_t)r * N + c);
+    if (c < N) {
+        // eight rows in flight per thread: a thread's rows are 32 apart, and one load at a time leaves the kernel waiting
+        // on memory latency (8 arrays of a few megabytes took 20 us)
+        f32x4 t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = s;
+        int r = rl;
+        for (; r + 7 * 32 < rows; r += 256) {
+            const float *q = part + (size_t)r * N + c;
+            f32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4 *>(q + (size_t)(32 * u) * N);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] += v[u];
+        }
+        for (; r < rows; r += 32) t[0] += *reinterpret_cast<const f32x4 *>(part + (size_t)r * N + c);
+        s = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+    }
     *reinterpret_cast<f32x4 *>(&red[rl][cl * 4]) = s;
     __syncthreads();
     const int oc = blockIdx.x * 32 + threadIdx.x;
@@ -457,8 +473,24 @@ __global__ __launch_bounds__(256) void reduce_jobs_kernel(ReduceJobSet set, bool
     const int cl = threadIdx.x & 7, rl = threadIdx.x >> 3;
     const int c = blockIdx.x * 32 + cl * 4;
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    if (c < N)
-        for (int r = rl; r < rows; r += 32) s += *reinterpret_cast<const f32x4 *>(part + (size_t)r * N + c);
+    if (c < N) {
+        // eight rows in flight per thread: a thread's rows are 32 apart, and one load at a time leaves the kernel waiting
+        // on memory latency (8 arrays of a few megabytes took 20 us)
+        f32x4 t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = s;
+        int r = rl;
+        for (; r + 7 * 32 < rows; r += 256) {
+            const float *q = part + (size_t)r * N + c;
+            f32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4 *>(q + (size_t)(32 * u) * N);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] += v[u];
+        }
+        for (; r < rows; r += 32) t[0] += *reinterpret_cast<const f32x4 *>(part + (size_t)r * N + c);
+        s = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+    }
     *reinterpret_cast<f32x4 *>(&red[rl][cl * 4]) = s;
     __syncthreads();
     const int oc = blockIdx.x * 32 + threadIdx.x;
