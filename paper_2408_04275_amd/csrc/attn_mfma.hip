@@ -835,7 +835,7 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnArgs a) {
             lds_read16<b * 128>(l4[0], lcur);
             lds_read16<b * 128 + BT2 * 4>(d4[0], lcur);
             static_for<0, PF>([&](auto J_) { issue_frag(fr[decltype(J_)::value], fa, BN, J_); });
-            __builtin_amdgcn_sched_barrier(0);         // the copies of this block's scores out of the accumulation registers follow
+            __builtin_amdgcn_sched_barrier(0);         // (the first reads stay in front of the elements' chunks)
             float pprev = 0.f, dprev = 0.f;
             static_for<0, 16>([&](auto E_) {
                 constexpr int e = decltype(E_)::value, gq = e >> 2, el = e & 3;

@@ -52,7 +52,7 @@ struct AttnArgs {
     float *lse;                 // [nh, T]
     const void *d_o;            // bwd: [T, nh*d]
     void *d_qkv;                // bwd: [T, ld_qkv]
-    float *Dsum;                // bwd scratch: [nh, T]
+    float *Dsum;                // bwd scratch: [nh, T]; D = rowsum(dO * O) per query and head (the matrix-core kernels keep -D there)
     // MFMA path: tok_info[t] = {segment start, segment end | (bidirectional ? 1 << 30 : 0)}
     const int2 *tok_info;
     // MFMA path, backward: when not null, the [T, d/2] (cos, sin) table of the rotary embedding; dQ and dK are
